@@ -1,0 +1,4 @@
+"""CPU oracle (test infrastructure only): see decoder.py."""
+from .decoder import (PI_OK, PI_CANCELLED, OracleModel, OracleKV, stage_forward, verify_greedy,
+                      kv_rollback, rmsnorm, linear, rope, attention, silu, visible_cells,
+                      round_to_storage, to_f64, top2_gap)
