@@ -1,0 +1,200 @@
+/* pipeinfer.h -- C ABI of the MI355X speculative-verification library.
+ *
+ * One target-model pipeline stage of PipeInfer on one GPU: a contiguous slice of decoder
+ * layers evaluated on a micro-batch of speculated tokens over a KV cache with a tree
+ * attention mask, greedy token verification, KV commit/rollback, and Early Inference
+ * Cancellation as a device-visible flag probed at every layer boundary.
+ *
+ * Conventions
+ *  - Every function returns an int32_t status: PI_OK (0), PI_CANCELLED (1, not an error)
+ *    or a negative PI_E_* code.  No exceptions, no global state besides handles.
+ *  - "device" pointers are caller-owned GPU memory (e.g. torch tensors); "host" pointers
+ *    are ordinary CPU memory.  The library never frees or keeps a caller pointer beyond
+ *    the call, except the asynchronous work enqueued on the given stream, which reads and
+ *    writes the buffers of that call until the stream reaches it.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Forward,
+ *    verify and rollback only enqueue work and return; load/alloc/free/read-back calls
+ *    are blocking.
+ *  - pi_model and pi_kv own their device memory until the matching *_free.  A pi_model
+ *    carries one set of activation scratch buffers: at most one forward per model may be
+ *    in flight at a time (issue them on one stream, or serialise streams with events).
+ *  - Tokens per run: 1 .. PI_MAX_BATCH.  All sizes are validated on the host before any
+ *    launch; a shape the kernels do not support returns PI_E_SHAPE, never a launch.
+ */
+#ifndef PIPEINFER_H
+#define PIPEINFER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PI_OK 0
+#define PI_CANCELLED 1
+#define PI_E_ARG (-1)       /* NULL/invalid argument */
+#define PI_E_SHAPE (-2)     /* configuration or size not supported */
+#define PI_E_OOM (-3)       /* device allocation failed */
+#define PI_E_SLOT_LIVE (-4) /* a speculative write targets a live canonical cell */
+#define PI_E_HIP (-5)       /* HIP runtime error */
+#define PI_E_STATE (-6)     /* model not fully loaded / handle misuse */
+
+#define PI_MAX_BATCH 16  /* tokens per run */
+#define PI_WINDOW 64     /* cells addressable by one run's mask word */
+
+#define PI_DTYPE_F32 0
+#define PI_DTYPE_BF16 1
+#define PI_LOC_HOST 0
+#define PI_LOC_DEVICE 1
+
+/* Tensor kinds for pi_model_set_tensor.  Matrices are logical [out_features][in_features]
+ * row-major; norm gains are [d_model] and always fp32. */
+enum {
+  PI_T_EMBED = 0,      /* [vocab][d_model]            */
+  PI_T_ATTN_NORM = 1,  /* [d_model], per layer        */
+  PI_T_WQ = 2,         /* [n_q_heads*head_dim][d]     */
+  PI_T_WK = 3,         /* [n_kv_heads*head_dim][d]    */
+  PI_T_WV = 4,         /* [n_kv_heads*head_dim][d]    */
+  PI_T_WO = 5,         /* [d][n_q_heads*head_dim]     */
+  PI_T_FFN_NORM = 6,   /* [d_model], per layer        */
+  PI_T_WG = 7,         /* [ffn][d]  (gate)            */
+  PI_T_WU = 8,         /* [ffn][d]  (up)              */
+  PI_T_WD = 9,         /* [d][ffn]  (down)            */
+  PI_T_FINAL_NORM = 10,/* [d_model]                   */
+  PI_T_LM_HEAD = 11    /* [vocab][d_model]            */
+};
+
+typedef struct pi_model pi_model;
+typedef struct pi_kv pi_kv;
+
+/* Decoder shape.  The paper does not print the decoder formulas (Section "Background and
+ * Motivation" names the attention module and the MLP of a Llama-2-style layer); this
+ * library evaluates: pre-norm RMSNorm(eps), bias-free projections, rotary embedding on
+ * adjacent pairs with base `rope_base`, softmax(QK^T/sqrt(head_dim)) with grouped-query
+ * sharing, SwiGLU MLP, final RMSNorm and an untied LM head.
+ * Constraints: head_dim in {32,64,128}; d_model, n_q_heads*head_dim multiples of 32;
+ * n_q_heads a multiple of n_kv_heads with ratio <= 8; vocab a multiple of 16.
+ * `dtype` is the storage type of the weight matrices; `max_pos` bounds RoPE positions. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype;   /* PI_DTYPE_F32 | PI_DTYPE_BF16 */
+  int32_t max_pos; /* positions must be < max_pos */
+} pi_model_config;
+
+/* Create a model: allocates device storage for all weights (in the library's own tiled
+ * layout), RoPE tables and activation scratch.  Weights start unset; every tensor must be
+ * supplied once with pi_model_set_tensor before the first forward (PI_E_STATE otherwise).
+ * Blocking. */
+int32_t pi_model_load(const pi_model_config* cfg, pi_model** out);
+
+/* Supply one tensor.  `src` holds the logical row-major tensor in `src_dtype`
+ * (PI_DTYPE_F32: float; PI_DTYPE_BF16: 16-bit bf16 patterns) at `src_loc` (host or device).
+ * Matrices must come in the model's dtype or in fp32 (rounded to bf16, nearest-even, for
+ * a bf16 model); gains must be fp32.  `layer` is ignored for the three global tensors.
+ * The tensor is repacked into the internal layout; `src` may be reused after return.
+ * Blocking. */
+int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void* src,
+                            int32_t src_dtype, int32_t src_loc);
+
+int32_t pi_model_free(pi_model* m);
+
+/* Bytes of weight storage one full forward streams (all layers + LM head), for rooflines. */
+int32_t pi_model_weight_bytes(const pi_model* m, int64_t* layer_bytes, int64_t* lm_head_bytes);
+
+/* KV cache of `n_cells` cells per layer (Section "KV Cache"; cells [0, kv_len) are the
+ * canonical sequence, cells >= kv_len are free for speculative runs' private writes,
+ * Section "Pipelined KV Cache Multibuffering").  Zero-filled, kv_len = 0.
+ * kv_dtype: PI_DTYPE_F32 or PI_DTYPE_BF16 (values rounded nearest-even when stored).
+ * n_cells must be a multiple of 16.  Blocking. */
+int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv** out);
+int32_t pi_kv_free(pi_kv* kv);
+
+/* Write K and V of cells [cell_begin, cell_begin+n) of one layer from caller data laid out
+ * [n][n_kv_heads][head_dim] (src_dtype/src_loc as above).  Used for synthetic prefill.
+ * Does not change kv_len.  Blocking. */
+int32_t pi_kv_set_cells(pi_kv* kv, int32_t layer, int32_t cell_begin, int32_t n, const void* k_src,
+                        const void* v_src, int32_t src_dtype, int32_t src_loc);
+/* Read cells back as fp32 into host buffers [n][n_kv_heads][head_dim].  Blocking. */
+int32_t pi_kv_get_cells(const pi_kv* kv, int32_t layer, int32_t cell_begin, int32_t n,
+                        float* k_dst_host, float* v_dst_host);
+/* Set / read the canonical length.  Blocking. */
+int32_t pi_kv_set_len(pi_kv* kv, int32_t kv_len);
+int32_t pi_kv_len(const pi_kv* kv, int32_t* out);
+/* Raw cache image (K then V, internal layout) for whole-buffer comparisons: size query
+ * with dst_host == NULL, else copy `*nbytes` bytes to the host.  Blocking. */
+int32_t pi_kv_raw(const pi_kv* kv, void* dst_host, int64_t* nbytes);
+
+/* One run's batch (the paper's run record: batch plus token -> logits map; Section
+ * "Asynchronous Speculation / State tracking").  All arrays are device pointers of n entries.
+ * Token i writes its K/V to cell slots[i] (must be >= kv_len and inside the window
+ * [window_base, window_base+PI_WINDOW)), and attends to cells [0, prefix_len) plus window
+ * cell window_base+c for every set bit c of mask[i] (tree attention mask, Section
+ * "Speculative Inference / Verification"; mask[i] must include token i's own cell). */
+typedef struct {
+  int32_t n;
+  const int32_t* tokens;    /* used iff layer_begin == 0 */
+  const int32_t* positions; /* RoPE positions */
+  const int32_t* slots;
+  const uint64_t* mask;
+  int32_t prefix_len;
+  int32_t window_base;
+} pi_run_desc;
+
+/* Evaluate layers [layer_begin, layer_end) for one run (one pipeline node's share, Section
+ * "Asynchronous Speculation": each node evaluates its allocated layers and passes the
+ * activations on).
+ *   hidden_in  [n][d_model] fp32 device: input activations, read iff layer_begin > 0.
+ *   hidden_out [n][d_model] fp32 device: written iff layer_end < n_layers and not cancelled.
+ *   logits_out [n][vocab]   fp32 device: written iff layer_end == n_layers and not cancelled
+ *              (logits_out[i] is the distribution of the token that follows token i).
+ *   cancel_flag: device-visible int32 (device memory or mapped pinned host memory), or
+ *              NULL for runs that must never stop (non-speculative runs, Section "Early
+ *              Inference Cancellation / Performance considerations").  It is probed before
+ *              the first layer of the call and at every layer boundary; once a non-zero
+ *              value is seen no further layer starts, outputs stay untouched and the run
+ *              reports PI_CANCELLED.  It may only go 0 -> 1 during a run.
+ *   run_status: device-visible int32[2], written by the device: [0] = PI_OK, PI_CANCELLED
+ *              or PI_E_SLOT_LIVE, [1] = layers_done = index of the first layer NOT
+ *              evaluated (== layer_end on success).  K/V of layers < layers_done were
+ *              written to the run's slots; clean them with pi_kv_rollback.
+ * Asynchronous: returns PI_OK after enqueueing; read run_status after synchronising. */
+int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t layer_begin,
+                         int32_t layer_end, const float* hidden_in, float* hidden_out,
+                         float* logits_out, const int32_t* cancel_flag, int32_t* run_status,
+                         void* stream);
+
+/* Greedy token-tree verification (Section "Speculative Inference / Verification"; greedy
+ * sampling as in Section "Experiments").  logits[i] follows tree node i; parent[i] < i is
+ * node i's parent, -1 = child of the last accepted token (parent == NULL: linear chain).
+ * Walk from the root with expected = root_expected: accept the lowest-index child whose
+ * draft token equals expected, then expected = argmax(logits[child]) (lowest id on ties);
+ * stop at the first node without a matching child.
+ * Outputs (device): accepted_nodes[n] (first accepted_count entries valid, rest -1),
+ * result[2] = {accepted_count, bonus_token} where bonus_token is the target's own next
+ * token after the accepted path.  vocab <= 2^24.  Asynchronous. */
+int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                         int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
+                         int32_t* result, void* stream);
+
+/* Commit / roll back a run's cells (Sections "KV Cache" and "Pipelined KV Cache
+ * Multibuffering / Sequence partitions"): the cells of the accepted path are copied, all
+ * layers, to canonical cells kv_len .. kv_len+a-1 in path order, every other cell in
+ * slots[] is zero-filled (free again), and kv_len += a.  accepted_nodes/result are the
+ * device outputs of pi_verify_greedy; pass result == NULL to discard the whole run
+ * (cancelled run: a = 0).  Asynchronous; kv_len is updated on the device. */
+int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t* accepted_nodes,
+                       const int32_t* result, void* stream);
+
+const char* pi_strerror(int32_t status);
+
+/* Tuning hook (not needed for correct use): override the work split of one projection phase
+ * (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head): number of column slices, row blocks per work
+ * unit, and grid size; 0 keeps the built-in choice.  Values outside what the scratch buffers
+ * and LDS allow are ignored. */
+int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k, int32_t rbu, int32_t grid);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEINFER_H */

@@ -1,0 +1,260 @@
+"""ctypes binding of the C ABI in include/pipeinfer.h: argument marshalling only.
+
+Every step of the hot path runs inside libpipeinfer_hip.so; this module converts Python
+objects to pointers and sizes.  Device buffers are torch tensors (torch is used for device
+memory and streams only).  There is no CPU fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_int32, c_int64, c_void_p, c_float, POINTER, byref
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipeinfer_hip.so")
+
+PI_OK, PI_CANCELLED = 0, 1
+PI_E_ARG, PI_E_SHAPE, PI_E_OOM, PI_E_SLOT_LIVE, PI_E_HIP, PI_E_STATE = -1, -2, -3, -4, -5, -6
+PI_MAX_BATCH, PI_WINDOW = 16, 64
+PI_DTYPE_F32, PI_DTYPE_BF16 = 0, 1
+PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
+(PI_T_EMBED, PI_T_ATTN_NORM, PI_T_WQ, PI_T_WK, PI_T_WV, PI_T_WO, PI_T_FFN_NORM, PI_T_WG, PI_T_WU,
+ PI_T_WD, PI_T_FINAL_NORM, PI_T_LM_HEAD) = range(12)
+
+EXPORTS = [
+    "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
+    "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
+    "pi_stage_forward", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
+]
+
+
+class PiModelConfig(ctypes.Structure):
+    _fields_ = [("n_layers", c_int32), ("d_model", c_int32), ("n_q_heads", c_int32),
+                ("n_kv_heads", c_int32), ("head_dim", c_int32), ("ffn", c_int32), ("vocab", c_int32),
+                ("rms_eps", c_float), ("rope_base", c_float), ("dtype", c_int32), ("max_pos", c_int32)]
+
+
+class PiRunDesc(ctypes.Structure):
+    _fields_ = [("n", c_int32), ("tokens", c_void_p), ("positions", c_void_p), ("slots", c_void_p),
+                ("mask", c_void_p), ("prefix_len", c_int32), ("window_base", c_int32)]
+
+
+class PiError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (fails loudly if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libpipeinfer_hip.so is missing: run __graft_entry__.build() "
+                               "(python -m paper_2407_11798_amd.build) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.pi_model_load.argtypes = [POINTER(PiModelConfig), POINTER(c_void_p)]
+        L.pi_model_set_tensor.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_int32, c_int32]
+        L.pi_model_free.argtypes = [c_void_p]
+        L.pi_model_weight_bytes.argtypes = [c_void_p, POINTER(c_int64), POINTER(c_int64)]
+        L.pi_kv_alloc.argtypes = [c_void_p, c_int32, c_int32, POINTER(c_void_p)]
+        L.pi_kv_free.argtypes = [c_void_p]
+        L.pi_kv_set_cells.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_int32, c_int32]
+        L.pi_kv_get_cells.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+        L.pi_kv_set_len.argtypes = [c_void_p, c_int32]
+        L.pi_kv_len.argtypes = [c_void_p, POINTER(c_int32)]
+        L.pi_kv_raw.argtypes = [c_void_p, c_void_p, POINTER(c_int64)]
+        L.pi_stage_forward.argtypes = [c_void_p, c_void_p, POINTER(PiRunDesc), c_int32, c_int32, c_void_p,
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pi_verify_greedy.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+                                       c_void_p, c_void_p]
+        L.pi_kv_rollback.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
+        L.pi_strerror.argtypes = [c_int32]
+        L.pi_strerror.restype = ctypes.c_char_p
+        L.pi_debug_set_plan.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32]
+        for name in EXPORTS:
+            if name != "pi_strerror":
+                getattr(L, name).restype = c_int32
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().pi_strerror(status).decode()
+
+
+def _check(status, where):
+    if status < 0:
+        raise PiError(status, where)
+    return status
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None)."""
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _dtype_code(name: str) -> int:
+    return {"f32": PI_DTYPE_F32, "bf16": PI_DTYPE_BF16}[name]
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return c_void_p(stream.cuda_stream)
+
+
+class Model:
+    """pi_model handle.  `shape` is any object with the decoder shape attributes."""
+
+    def __init__(self, shape, max_pos: int = 4096):
+        self.shape = shape
+        cfg = PiModelConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
+                            shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps, shape.rope_base,
+                            _dtype_code(shape.dtype), max_pos)
+        h = c_void_p()
+        _check(lib().pi_model_load(byref(cfg), byref(h)), "pi_model_load")
+        self.handle = h
+
+    def set_tensor(self, kind: int, layer: int, src):
+        """src: numpy array (host; float32 or uint16 bf16 bits) or a torch device tensor
+        (float32, bfloat16, or int16/uint16 holding bf16 bits)."""
+        if isinstance(src, np.ndarray):
+            src = np.ascontiguousarray(src)
+            code = PI_DTYPE_F32 if src.dtype == np.float32 else PI_DTYPE_BF16
+            assert src.dtype in (np.float32, np.uint16)
+            st = lib().pi_model_set_tensor(self.handle, kind, layer, c_void_p(src.ctypes.data), code, PI_LOC_HOST)
+        else:
+            import torch
+            assert src.is_cuda and src.is_contiguous()
+            code = PI_DTYPE_F32 if src.dtype == torch.float32 else PI_DTYPE_BF16
+            st = lib().pi_model_set_tensor(self.handle, kind, layer, _ptr(src), code, PI_LOC_DEVICE)
+        _check(st, "pi_model_set_tensor")
+
+    def weight_bytes(self):
+        a, b = c_int64(), c_int64()
+        _check(lib().pi_model_weight_bytes(self.handle, byref(a), byref(b)), "pi_model_weight_bytes")
+        return a.value, b.value
+
+    def set_plan(self, phase, s_k=0, rbu=0, grid=0):
+        _check(lib().pi_debug_set_plan(self.handle, phase, s_k, rbu, grid), "pi_debug_set_plan")
+
+    def free(self):
+        if self.handle:
+            lib().pi_model_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class KVCache:
+    def __init__(self, model: Model, n_cells: int, dtype: str | None = None):
+        self.model = model
+        self.dtype = dtype or model.shape.dtype
+        self.n_cells = n_cells
+        h = c_void_p()
+        _check(lib().pi_kv_alloc(model.handle, n_cells, _dtype_code(self.dtype), byref(h)), "pi_kv_alloc")
+        self.handle = h
+
+    def set_cells(self, layer: int, cell_begin: int, k, v):
+        if isinstance(k, np.ndarray):
+            k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
+            code = PI_DTYPE_F32 if k.dtype == np.float32 else PI_DTYPE_BF16
+            st = lib().pi_kv_set_cells(self.handle, layer, cell_begin, k.shape[0], c_void_p(k.ctypes.data),
+                                       c_void_p(v.ctypes.data), code, PI_LOC_HOST)
+        else:
+            import torch
+            code = PI_DTYPE_F32 if k.dtype == torch.float32 else PI_DTYPE_BF16
+            st = lib().pi_kv_set_cells(self.handle, layer, cell_begin, k.shape[0], _ptr(k), _ptr(v), code,
+                                       PI_LOC_DEVICE)
+        _check(st, "pi_kv_set_cells")
+
+    def get_cells(self, layer: int, cell_begin: int, n: int):
+        sh = self.model.shape
+        k = np.empty((n, sh.n_kv_heads, sh.head_dim), dtype=np.float32)
+        v = np.empty_like(k)
+        _check(lib().pi_kv_get_cells(self.handle, layer, cell_begin, n, c_void_p(k.ctypes.data),
+                                     c_void_p(v.ctypes.data)), "pi_kv_get_cells")
+        return k, v
+
+    def set_len(self, n: int):
+        _check(lib().pi_kv_set_len(self.handle, n), "pi_kv_set_len")
+
+    def __len__(self):
+        out = c_int32()
+        _check(lib().pi_kv_len(self.handle, byref(out)), "pi_kv_len")
+        return out.value
+
+    def raw(self) -> np.ndarray:
+        nb = c_int64()
+        _check(lib().pi_kv_raw(self.handle, None, byref(nb)), "pi_kv_raw")
+        buf = np.empty(nb.value, dtype=np.uint8)
+        _check(lib().pi_kv_raw(self.handle, c_void_p(buf.ctypes.data), byref(nb)), "pi_kv_raw")
+        return buf
+
+    def free(self):
+        if self.handle:
+            lib().pi_kv_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Run:
+    """Device-side copy of one run's batch description (tokens, positions, slots, mask)."""
+
+    def __init__(self, tokens, positions, slots, mask, prefix_len: int, window_base: int, parent=None):
+        import torch
+        dev = "cuda"
+        self.n = len(positions)
+        self.tokens = None if tokens is None else torch.as_tensor(np.asarray(tokens, dtype=np.int32), device=dev)
+        self.positions = torch.as_tensor(np.asarray(positions, dtype=np.int32), device=dev)
+        self.slots = torch.as_tensor(np.asarray(slots, dtype=np.int32), device=dev)
+        self.mask = torch.as_tensor(np.asarray(mask, dtype=np.uint64).view(np.int64), device=dev)
+        self.parent = None if parent is None else torch.as_tensor(np.asarray(parent, dtype=np.int32), device=dev)
+        self.prefix_len = int(prefix_len)
+        self.window_base = int(window_base)
+
+    def desc(self) -> PiRunDesc:
+        return PiRunDesc(self.n, _ptr(self.tokens), _ptr(self.positions), _ptr(self.slots), _ptr(self.mask),
+                         self.prefix_len, self.window_base)
+
+
+def stage_forward(model: Model, kv: KVCache, run: Run, layer_begin: int, layer_end: int, hidden_in=None,
+                  hidden_out=None, logits_out=None, cancel_flag=None, run_status=None, stream=None,
+                  cancel_flag_ptr: int | None = None) -> int:
+    """Enqueue pi_stage_forward.  cancel_flag: torch int32 device tensor (or pass a raw
+    device-visible address with cancel_flag_ptr, e.g. mapped pinned host memory)."""
+    d = run.desc()
+    cf = c_void_p(cancel_flag_ptr) if cancel_flag_ptr is not None else _ptr(cancel_flag)
+    st = lib().pi_stage_forward(model.handle, kv.handle, byref(d), layer_begin, layer_end, _ptr(hidden_in),
+                                _ptr(hidden_out), _ptr(logits_out), cf, _ptr(run_status),
+                                _stream_handle(stream))
+    return _check(st, "pi_stage_forward")
+
+
+def verify_greedy(draft, parent, n: int, logits, vocab: int, root_expected: int, accepted_nodes, result,
+                  stream=None) -> int:
+    st = lib().pi_verify_greedy(_ptr(draft), _ptr(parent), n, _ptr(logits), vocab, root_expected,
+                                _ptr(accepted_nodes), _ptr(result), _stream_handle(stream))
+    return _check(st, "pi_verify_greedy")
+
+
+def kv_rollback(kv: KVCache, slots, n: int, accepted_nodes=None, result=None, stream=None) -> int:
+    st = lib().pi_kv_rollback(kv.handle, _ptr(slots), n, _ptr(accepted_nodes), _ptr(result),
+                              _stream_handle(stream))
+    return _check(st, "pi_kv_rollback")

@@ -1,0 +1,287 @@
+// Small kernels around the layer loop: run latch, embedding gather, stage output, greedy
+// verification (argmax + tree walk), KV commit/rollback, KV cell set/get.
+#include "pi_internal.h"
+
+namespace pi {
+namespace {
+
+// ---- run latch: validate the run's slots, probe the cancel flag once, arm the run state ----
+__global__ void latch_kernel(RunState* rs, const int32_t* cancel_flag, const int32_t* slots, int n,
+                             const int32_t* kv_len, int window_base, int n_cells, int layer_begin) {
+  if (threadIdx.x != 0) return;
+  int status = PI_OK, dead = 0;
+  const int len = *kv_len;
+  for (int i = 0; i < n; ++i) {
+    const int s = slots[i];
+    if (s < len || s < window_base || s >= window_base + PI_WINDOW || s >= n_cells) {
+      status = PI_E_SLOT_LIVE;
+      dead = 1;
+    }
+  }
+  if (!dead && cancel_flag &&
+      __hip_atomic_load(cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
+    status = PI_CANCELLED;
+    dead = 1;
+  }
+  rs->dead = dead;
+  rs->status = status;
+  rs->layers_done = layer_begin;
+}
+
+// ---- stage input: embedding rows (or the previous stage's activations) -> x, plus the
+// per-16-column partial sums of squares the first RMSNorm needs.  One thread per 4 columns.
+__global__ void __launch_bounds__(256) embed_kernel(const void* embed, int dtype,
+                                                    const int32_t* tokens, const float* hidden_in,
+                                                    int n, int d, int vocab, float* x, float* ssq,
+                                                    const RunState* rs) {
+  if (rs->dead) return;
+  const int per_row = d / 4;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = idx < n * per_row;
+  const int i = live ? idx / per_row : 0, c = live ? (idx % per_row) * 4 : 0;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (live) {
+    if (hidden_in) {
+      v = *(const float4*)(hidden_in + (size_t)i * d + c);
+    } else {
+      int tok = tokens[i];
+      tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+      if (dtype == PI_DTYPE_BF16) {
+        const uint2 p = *(const uint2*)((const uint16_t*)embed + (size_t)tok * d + c);
+        v = make_float4(__uint_as_float(p.x << 16), __uint_as_float(p.x & 0xffff0000u),
+                        __uint_as_float(p.y << 16), __uint_as_float(p.y & 0xffff0000u));
+      } else {
+        v = *(const float4*)((const float*)embed + (size_t)tok * d + c);
+      }
+    }
+    *(float4*)(x + (size_t)i * d + c) = v;
+  }
+  // 4 consecutive threads cover one 16-column block of one token
+  float s = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  if (live && (threadIdx.x & 3) == 0) ssq[(c / 16) * 16 + i] = s;
+}
+
+__global__ void __launch_bounds__(256) finish_kernel(const RunState* rs, int32_t* run_status,
+                                                     const float* x, float* hidden_out, int n, int d) {
+  if (blockIdx.x == 0 && threadIdx.x == 0 && run_status) {
+    run_status[0] = rs->status;
+    run_status[1] = rs->layers_done;
+  }
+  if (rs->dead || !hidden_out) return;
+  const int total = n * d / 4;
+  for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x)
+    ((float4*)hidden_out)[idx] = ((const float4*)x)[idx];
+}
+
+// ---- greedy verification -------------------------------------------------------------------
+// One block per logits row finds argmax (lowest id on ties); the last block to finish walks
+// the tree.
+__global__ void __launch_bounds__(256) verify_kernel(const int32_t* draft, const int32_t* parent, int n,
+                                                     const float* logits, int vocab, int root_expected,
+                                                     int32_t* accepted, int32_t* result,
+                                                     float* best_val, int32_t* best_idx, int* cnt) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  __shared__ int last;
+  const int row = blockIdx.x;
+  const float* lg = logits + (size_t)row * vocab;
+  float bv = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int v = threadIdx.x; v < vocab; v += blockDim.x) {
+    const float f = lg[v];
+    if (f > bv || (f == bv && v < bi)) { bv = f; bi = v; }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const float ov = __shfl_xor(bv, o);
+    const int oi = __shfl_xor(bi, o);
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+    best_val[row] = bv;
+    best_idx[row] = bi;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last = old == n - 1;
+    if (last) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      *cnt = 0;
+      int u = -1, expected = root_expected, a = 0;
+      for (;;) {
+        int nxt = -1;
+        for (int c = 0; c < n; ++c) {
+          const int p = parent ? parent[c] : c - 1;
+          if (p == u && draft[c] == expected) { nxt = c; break; }
+        }
+        if (nxt < 0) break;
+        accepted[a++] = nxt;
+        u = nxt;
+        expected = __hip_atomic_load(best_idx + nxt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      for (int j = a; j < n; ++j) accepted[j] = -1;
+      result[0] = a;
+      result[1] = expected;
+    }
+  }
+}
+
+// ---- KV commit / rollback ------------------------------------------------------------------
+// One thread per (layer, kv head, 16-byte piece of a cell row), for K and V: gather the
+// accepted path's pieces, zero every slot of the run, then write the path to cells
+// kv_len .. kv_len+a-1.  All of a thread's reads precede its writes and threads touch
+// disjoint columns, so overlapping source and destination cells are safe.
+__global__ void __launch_bounds__(256) rollback_kernel(char* kbuf, char* vbuf, int elem_size,
+                                                       int n_layers, int n_kv_heads, int n_cells,
+                                                       int head_dim, const int32_t* slots, int n,
+                                                       const int32_t* accepted, const int32_t* result,
+                                                       int32_t* kv_len, int* cnt) {
+  const int pieces = head_dim * elem_size / 16;
+  const size_t total = (size_t)n_layers * n_kv_heads * pieces * 2;
+  const int a = result ? result[0] : 0;
+  const int len = *kv_len;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < total) {
+    const int which = (int)(idx & 1);
+    size_t r = idx >> 1;
+    const int piece = (int)(r % pieces);
+    r /= pieces;
+    const size_t lh = r;  // layer * n_kv_heads + head
+    char* base = (which ? vbuf : kbuf) + lh * (size_t)n_cells * head_dim * elem_size + (size_t)piece * 16;
+    const size_t cell_stride = (size_t)head_dim * elem_size;
+    uint4 keep[PI_MAX_BATCH];
+#pragma unroll
+    for (int j = 0; j < PI_MAX_BATCH; ++j)
+      if (j < a) keep[j] = *(const uint4*)(base + (size_t)slots[accepted[j]] * cell_stride);
+    for (int i = 0; i < n; ++i) *(uint4*)(base + (size_t)slots[i] * cell_stride) = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < PI_MAX_BATCH; ++j)
+      if (j < a) *(uint4*)(base + (size_t)(len + j) * cell_stride) = keep[j];
+  }
+  // the last block to finish publishes the new canonical length
+  __shared__ int last;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last = old == (int)gridDim.x - 1;
+    if (last) {
+      *cnt = 0;
+      *kv_len = len + a;
+    }
+  }
+}
+
+// ---- KV cell set / get (prefill and read-back; not on the hot path) -------------------------
+__global__ void __launch_bounds__(256) kv_set_kernel(char* kbuf, char* vbuf, int kv_dtype, int n_kv_heads,
+                                                     int n_cells, int head_dim, int layer, int cell_begin,
+                                                     int n, const void* ksrc, const void* vsrc, int src_dtype) {
+  const size_t total = (size_t)n * n_kv_heads * head_dim;
+  const int es = kv_dtype == PI_DTYPE_BF16 ? 2 : 4;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const int d = (int)(e % head_dim);
+    const int h = (int)((e / head_dim) % n_kv_heads);
+    const int c = (int)(e / ((size_t)head_dim * n_kv_heads));
+    const size_t dst = (((size_t)layer * n_kv_heads + h) * n_cells + cell_begin + c) * head_dim + d;
+    for (int which = 0; which < 2; ++which) {
+      const void* src = which ? vsrc : ksrc;
+      char* buf = which ? vbuf : kbuf;
+      const float f = src_dtype == PI_DTYPE_BF16 ? bf16_to_f32(((const uint16_t*)src)[e]) : ((const float*)src)[e];
+      if (es == 2) ((uint16_t*)buf)[dst] = f32_to_bf16_rne(f);
+      else ((float*)buf)[dst] = f;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) kv_get_kernel(const char* kbuf, const char* vbuf, int kv_dtype,
+                                                     int n_kv_heads, int n_cells, int head_dim, int layer,
+                                                     int cell_begin, int n, float* kdst, float* vdst) {
+  const size_t total = (size_t)n * n_kv_heads * head_dim;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const int d = (int)(e % head_dim);
+    const int h = (int)((e / head_dim) % n_kv_heads);
+    const int c = (int)(e / ((size_t)head_dim * n_kv_heads));
+    const size_t src = (((size_t)layer * n_kv_heads + h) * n_cells + cell_begin + c) * head_dim + d;
+    if (kv_dtype == PI_DTYPE_BF16) {
+      kdst[e] = bf16_to_f32(((const uint16_t*)kbuf)[src]);
+      vdst[e] = bf16_to_f32(((const uint16_t*)vbuf)[src]);
+    } else {
+      kdst[e] = ((const float*)kbuf)[src];
+      vdst[e] = ((const float*)vbuf)[src];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_latch(RunState* rs, const int32_t* cancel_flag, const int32_t* slots, int n,
+                        const int32_t* kv_len, int window_base, int n_cells, int layer_begin,
+                        hipStream_t s) {
+  latch_kernel<<<dim3(1), dim3(64), 0, s>>>(rs, cancel_flag, slots, n, kv_len, window_base, n_cells, layer_begin);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed(const void* embed, int dtype, const int32_t* tokens, const float* hidden_in,
+                        int n, int d, int vocab, float* x, float* ssq, const RunState* rs,
+                        hipStream_t s) {
+  const int total = n * d / 4;
+  embed_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(embed, dtype, tokens, hidden_in,
+                                                                          n, d, vocab, x, ssq, rs);
+  return hipGetLastError();
+}
+
+hipError_t launch_finish(const RunState* rs, int32_t* run_status, const float* x, float* hidden_out,
+                         int n, int d, hipStream_t s) {
+  const int total = hidden_out ? n * d / 4 : 1;
+  int blocks = (total + 255) / 256;
+  if (blocks > 256) blocks = 256;
+  finish_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(rs, run_status, x, hidden_out, n, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
+                         int vocab, int root_expected, int32_t* accepted, int32_t* result,
+                         float* best_val, int32_t* best_idx, int* cnt, hipStream_t s) {
+  verify_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>(draft, parent, n, logits, vocab, root_expected,
+                                                        accepted, result, best_val, best_idx, cnt);
+  return hipGetLastError();
+}
+
+hipError_t launch_rollback(void* k, void* v, int kv_dtype, int n_layers, int n_kv_heads, int n_cells,
+                           int head_dim, const int32_t* slots, int n, const int32_t* accepted,
+                           const int32_t* result, int32_t* kv_len, int* cnt, hipStream_t s) {
+  const int es = kv_dtype == PI_DTYPE_BF16 ? 2 : 4;
+  const size_t total = (size_t)n_layers * n_kv_heads * (head_dim * es / 16) * 2;
+  rollback_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(
+      (char*)k, (char*)v, es, n_layers, n_kv_heads, n_cells, head_dim, slots, n, accepted, result, kv_len, cnt);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_set(void* k, void* v, int kv_dtype, int n_kv_heads, int n_cells, int head_dim,
+                         int layer, int cell_begin, int n, const void* ksrc, const void* vsrc,
+                         int src_dtype, hipStream_t s) {
+  const size_t total = (size_t)n * n_kv_heads * head_dim;
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  kv_set_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((char*)k, (char*)v, kv_dtype, n_kv_heads, n_cells,
+                                                             head_dim, layer, cell_begin, n, ksrc, vsrc, src_dtype);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_get(const void* k, const void* v, int kv_dtype, int n_kv_heads, int n_cells,
+                         int head_dim, int layer, int cell_begin, int n, float* kdst, float* vdst,
+                         hipStream_t s) {
+  const size_t total = (size_t)n * n_kv_heads * head_dim;
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  kv_get_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const char*)k, (const char*)v, kv_dtype, n_kv_heads,
+                                                             n_cells, head_dim, layer, cell_begin, n, kdst, vdst);
+  return hipGetLastError();
+}
+
+}  // namespace pi

@@ -1,0 +1,78 @@
+// Weight repacking: logical row-major tensor -> the 16x32-tile streaming layout (PackedMat).
+#include "pi_internal.h"
+
+namespace pi {
+namespace {
+
+__device__ __forceinline__ float load_src(const void* src, int src_dtype, size_t idx) {
+  if (src_dtype == PI_DTYPE_F32) return ((const float*)src)[idx];
+  return bf16_to_f32(((const uint16_t*)src)[idx]);
+}
+
+// One thread per (source row, chunk of 16 bytes of the destination row).
+__global__ void __launch_bounds__(256) repack_kernel(const void* src, int src_dtype, int rows,
+                                                     int cols, char* dst, int KT, int dst_dtype,
+                                                     int row_mul, int row_add) {
+  const int per_chunk = dst_dtype == PI_DTYPE_BF16 ? 8 : 4;
+  const int chunks_per_row = KT * kKTile / per_chunk;
+  const size_t total = (size_t)rows * chunks_per_row;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / chunks_per_row);
+    const int c = (int)(i % chunks_per_row);
+    const int pr = r * row_mul + row_add;
+    const int rb = pr / kRowBlock, lr = pr % kRowBlock;
+    const int k0 = c * per_chunk;
+    float v[8];
+    for (int j = 0; j < per_chunk; ++j)
+      v[j] = (k0 + j < cols) ? load_src(src, src_dtype, (size_t)r * cols + k0 + j) : 0.0f;
+    if (dst_dtype == PI_DTYPE_BF16) {
+      const int t = c / 4, g = c % 4;
+      const size_t off = ((size_t)rb * KT + t) * 1024 + (size_t)(g * 16 + lr) * 16;
+      uint32_t w[4];
+      for (int j = 0; j < 4; ++j)
+        w[j] = (uint32_t)f32_to_bf16_rne(v[2 * j]) | ((uint32_t)f32_to_bf16_rne(v[2 * j + 1]) << 16);
+      *(uint4*)(dst + off) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+      const int t = c / 8, q = c % 8, g = q / 2, h = q % 2;
+      const size_t off = ((size_t)rb * KT + t) * 2048 + (size_t)h * 1024 + (size_t)(g * 16 + lr) * 16;
+      *(float4*)(dst + off) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) convert_kernel(const void* src, int src_dtype, void* dst,
+                                                      int dst_dtype, size_t count) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const float f = load_src(src, src_dtype, i);
+    if (dst_dtype == PI_DTYPE_BF16) ((uint16_t*)dst)[i] = f32_to_bf16_rne(f);
+    else ((float*)dst)[i] = f;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t count,
+                          hipStream_t s) {
+  size_t blocks = (count + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) return hipSuccess;
+  convert_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(src, src_dtype, dst, dst_dtype, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, PackedMat dst,
+                         int dst_dtype, int row_mul, int row_add, hipStream_t s) {
+  const int per_chunk = dst_dtype == PI_DTYPE_BF16 ? 8 : 4;
+  const size_t total = (size_t)rows * (dst.KT * kKTile / per_chunk);
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) return hipSuccess;
+  repack_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(src, src_dtype, rows, cols,
+                                                             (char*)dst.data, dst.KT, dst_dtype,
+                                                             row_mul, row_add);
+  return hipGetLastError();
+}
+
+}  // namespace pi
