@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-verification hot path on one MI355X.
+
+A step = one verification run end to end: pi_stage_forward over all layers + LM head on a
+micro-batch of n speculated tokens, pi_verify_greedy, pi_kv_rollback.  Workload: the
+Llama-7B-shaped bf16 target with 512 prefilled KV positions (synthetic, seeded), speculative
+batches of 1, 4 and 8 tokens with a linear causal mask and uniform-random draft tokens.
+Prints ONE JSON line; `value` is verified tokens/s at the largest batch (n = 8), the other
+batch sizes are listed under "per_batch".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(shape, layer_bytes, lm_bytes, prefix_len, n):
+    """Bytes one forward must move: every weight once, the n embedding rows, every visible
+    KV cell once (the prefix; the n new cells are written and read once more)."""
+    es = shape.bytes_per_weight
+    kv = shape.n_layers * (prefix_len + n) * 2 * shape.n_kv_heads * shape.head_dim * es
+    return shape.n_layers * layer_bytes + lm_bytes + n * shape.d_model * es + kv
+
+
+def cpu_baseline(shape, prefix_len, n, seed):
+    """The CPU oracle timed on a bounded sample: a 1-layer and a 3-layer model of the same
+    layer shape (KV prefix included), extrapolated linearly to the full depth."""
+    import dataclasses
+    import numpy as np
+    import synth
+    import oracle
+    from oracle import from_synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    times = {}
+    for nl in (1, 3):
+        sh = dataclasses.replace(shape, n_layers=nl, name="%s_l%d" % (shape.name, nl))
+        om = from_synth.model_from_seed(sh, seed)
+        for name in ("embed", "final_norm", "lm_head"):
+            om.weights(name, 0)
+        for l in range(nl):
+            for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd"):
+                om.weights(name, l)          # generation is not part of the timed region
+        okv = from_synth.kv_synthetic(sh, seed, prefix_len + 64, prefix_len)
+        run = synth.linear_run(n, prefix_len)
+        toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT)
+        t0 = time.perf_counter()
+        out = oracle.stage_forward(om, okv, run, 0, nl, tokens=toks)
+        oracle.verify_greedy(toks, run["parent"], out["logits"].astype(np.float32), int(toks[0]))
+        times[nl] = time.perf_counter() - t0
+    per_layer = (times[3] - times[1]) / 2.0
+    full = times[1] + per_layer * (shape.n_layers - 1)
+    return {"value": n / full, "unit": "verified tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "n=%d, T=%d: timed 1-layer (%.2fs) and 3-layer (%.2fs) models of the same layer shape, "
+                      "extrapolated to %d layers (%.1fs per forward)" % (n, prefix_len, times[1], times[3],
+                                                                         shape.n_layers, full)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--shape", default="llama7b")
+    ap.add_argument("--prefix", type=int, default=512)
+    ap.add_argument("--batches", default="1,4,8")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (a pipeline stage is a layer slice on that GPU); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from synth import gpu_loader
+    import paper_2407_11798_amd as pi
+
+    shape = synth.SHAPES[args.shape]
+    batches = [int(b) for b in args.batches.split(",")]
+    T = args.prefix
+    torch.cuda.set_device(0)
+    model = gpu_loader.load_model(shape, args.seed)
+    n_cells = ((T + 64 + 15) // 16) * 16
+    kv = pi.KVCache(model, n_cells)
+    gpu_loader.prefill_kv_synthetic(kv, shape, args.seed, T)
+    layer_bytes, lm_bytes = model.weight_bytes()
+
+    per_batch = {}
+    for n in batches:
+        rd = synth.linear_run(n, T)
+        toks = synth.tokens_host(shape, args.seed, n, synth.T_DRAFT, salt=n)
+        run = gpu_loader.make_run(rd, toks)
+        root_expected = int(synth.tokens_host(shape, args.seed, 1, synth.T_MISC, salt=n)[0])
+        logits = torch.empty((n, shape.vocab), device="cuda")
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        acc = torch.zeros(n, dtype=torch.int32, device="cuda")
+        res = torch.zeros(2, dtype=torch.int32, device="cuda")
+
+        def step(ev0=None, ev1=None):
+            if ev0 is not None:
+                ev0.record()
+            pi.stage_forward(model, kv, run, 0, shape.n_layers, logits_out=logits, run_status=status)
+            if ev1 is not None:
+                ev1.record()
+            pi.verify_greedy(run.tokens, run.parent, n, logits, shape.vocab, root_expected, acc, res)
+            pi.kv_rollback(kv, run.slots, n, acc, res)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            step(e0, e1)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        fwd_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / args.steps
+        assert status.cpu().tolist() == [0, shape.n_layers]
+        kv.set_len(T)  # an accepted draft token would have advanced the prefix; keep the workload fixed
+        ms = wall * 1e3 / args.steps
+        ab = algorithmic_bytes(shape, layer_bytes, lm_bytes, T, n)
+        per_batch[str(n)] = {
+            "verified_tokens_per_s": n / (ms * 1e-3), "ms_per_step": ms, "forward_ms": fwd_ms,
+            "per_layer_us": fwd_ms * 1e3 / (shape.n_layers + lm_bytes / layer_bytes),
+            "algorithmic_GB": ab / 1e9, "achieved_GBps": ab / 1e9 / (fwd_ms * 1e-3),
+            "frac_of_peak": ab / 1e9 / (fwd_ms * 1e-3) / HBM_PEAK_GBS,
+        }
+
+    head = str(max(batches))
+    hb = per_batch[head]
+    out = {
+        "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
+        "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": hb["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shape.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s-shaped target, %s weights+KV, T=%d prefilled cells, speculative batches %s, "
+                               "linear causal mask, uniform-random drafts" % (shape.name, shape.dtype, T, args.batches),
+                   "step": "pi_stage_forward(all layers + LM head) + pi_verify_greedy + pi_kv_rollback"},
+        "per_batch": per_batch,
+        "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": hb["frac_of_peak"], "traffic": None,
+                     "kernel": "pi_stage_forward launch sequence (n=%s)" % head,
+                     "algorithmic_bytes_per_launch": hb["algorithmic_GB"] * 1e9},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, T, int(head), args.seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -188,11 +188,14 @@ int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t
 
 const char* pi_strerror(int32_t status);
 
-/* Tuning hook (not needed for correct use): override the work split of one projection phase
- * (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head): number of column slices, row blocks per work
- * unit, and grid size; 0 keeps the built-in choice.  Values outside what the scratch buffers
- * and LDS allow are ignored. */
-int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k, int32_t rbu, int32_t grid);
+/* Tuning hook (not needed for correct use): ask for at least `s_k` column slices in one
+ * projection phase (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head); 0 restores the built-in
+ * choice.  The library still rounds up to a split the tile count, grid and LDS allow. */
+int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
+/* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
+ * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],
+ * 3 SwiGLU output [n][ffn]).  Blocking. */
+int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64_t count);
 
 #ifdef __cplusplus
 }

@@ -12,11 +12,8 @@ using namespace pi;
 
 namespace {
 
-constexpr size_t kProjLdsBudget = 40 * 1024;
-
-struct Plan {
-  int S_k, RBU, grid;
-};
+constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS the staged activations may take
+constexpr unsigned long long kBarrierTimeoutTicks = 200000000ull;  // 2 s of the 100 MHz clock
 
 }  // namespace
 
@@ -27,14 +24,18 @@ struct pi_model {
   void* embed = nullptr;  // [vocab][d] row-major in cfg.dtype
   float* final_gain = nullptr;
   float2* rope = nullptr;  // [max_pos][hd/2]
+  LayerDev* layers_dev = nullptr;
   // activation scratch of the one run in flight
   float *x = nullptr, *q = nullptr, *o = nullptr, *a = nullptr, *ssq = nullptr, *part = nullptr;
-  int* cnt = nullptr;       // row-block arrival counters
-  int* done_cnt = nullptr;  // layer completion counter
+  int part_maxc = 1;
+  int* cnt = nullptr;  // row-block arrival counters
   RunState* rs = nullptr;
+  StageSync* sync = nullptr;
+  int grid = 0;  // workgroups of the stage kernel = compute units
+  size_t configured_lds[17] = {0};  // per ring size: dynamic LDS the kernel was configured for
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
-  int plan_override[5][3] = {{0}};  // debug: per phase {S_k, RBU, grid}; 0 = heuristic
+  int sk_override[5] = {0, 0, 0, 0, 0};
   int n_q_rows() const { return cfg.n_q_heads * cfg.head_dim; }
   int n_kv_rows() const { return cfg.n_kv_heads * cfg.head_dim; }
 };
@@ -47,6 +48,7 @@ struct pi_kv {
   int32_t* len_dev = nullptr;
   int* cnt = nullptr;
   float *attn_o = nullptr, *attn_ml = nullptr;
+  int* attn_cnt = nullptr;
 };
 
 namespace {
@@ -77,53 +79,59 @@ hipError_t dev_alloc(pi_model* m, T** p, size_t bytes, bool zero) {
   return e;
 }
 
-int lds_max_tiles(int n) { return (int)((kProjLdsBudget) / (128 * (size_t)n)); }
-
-// Smallest number of k slices whose staged activations fit in LDS, and the largest number
-// the planner may choose (at least 8 tiles per slice unless LDS forces more slices).
-int s_k_min(const PackedMat& w, int n) { return (w.KT + lds_max_tiles(n) - 1) / lds_max_tiles(n); }
-int s_k_cap(const PackedMat& w, int n) {
-  const int lo = s_k_min(w, n);
-  const int hi = w.KT / 8 > 0 ? w.KT / 8 : 1;
-  return lo > hi ? lo : hi;
-}
-
-// Heuristic split of one projection into (k slices) x (row chunks): enough k slices for the
-// staged activations to fit in LDS and for ~1000 work units, one row block per wave per unit.
-Plan make_plan(const pi_model* m, int phase, const PackedMat& w, int n) {
-  Plan p;
-  const int s_lds = s_k_min(w, n), s_cap = s_k_cap(w, n);
-  p.RBU = kProjThreads / 64;
-  const int s_par = (1024 * p.RBU + w.NRB - 1) / w.NRB;
-  p.S_k = s_lds > s_par ? s_lds : s_par;
-  if (p.S_k > s_cap) p.S_k = s_cap;
-  if (m->plan_override[phase][0] > 0) {
-    const int sk = m->plan_override[phase][0];
-    if (sk >= s_lds && sk <= s_cap) p.S_k = sk;
+// Column slices for one projection: the smallest power of two that divides the tile count and
+// the grid and lets the staged activations of n tokens fit the LDS budget.  0 = impossible.
+int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n) {
+  const int ov = m->sk_override[phase];
+  for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
+    if (w.KT % sk || m->grid % sk) continue;
+    if (stage_proj_lds_bytes(n, w.KT / sk) > kProjLdsBudget) continue;
+    if (ov > sk) continue;  // an override asks for at least this many slices
+    return sk;
   }
-  if (m->plan_override[phase][1] > 0) p.RBU = m->plan_override[phase][1];
-  const int units = p.S_k * ((w.NRB + p.RBU - 1) / p.RBU);
-  p.grid = units < 2048 ? units : 2048;
-  if (m->plan_override[phase][2] > 0 && m->plan_override[phase][2] < units) p.grid = m->plan_override[phase][2];
-  return p;
+  return 0;
 }
 
-int max_split_tiles(const pi_model* m) {
-  // upper bound of S_k * NRB over all phases and token counts (S_k never exceeds KT/8 or the
-  // LDS-driven minimum, whichever is larger)
-  size_t best = 0;
-  auto upd = [&](const PackedMat& w) {
-    for (int n = 1; n <= PI_MAX_BATCH; ++n) {
-      const size_t v = (size_t)s_k_cap(w, n) * w.NRB;
-      if (v > best) best = v;
-    }
-  };
-  upd(m->layers[0].qkv);
-  upd(m->layers[0].o);
-  upd(m->layers[0].gateup);
-  upd(m->layers[0].down);
-  upd(m->lm_head);
-  return (int)best;
+// Largest number of waves that can contribute to one row block within a slice.
+int max_contributors(const pi_model* m, const PackedMat& w, int sk) {
+  const int nt = w.KT / sk;
+  const long total = (long)w.NRB * nt;
+  const long nwaves = (long)(m->grid / sk) * (kStageThreads / 64);
+  const long share = (total + nwaves - 1) / nwaves;
+  return (int)((nt + share - 1) / share + 1);
+}
+
+struct StagePlan {
+  int sk[5];
+  int min_nt;
+  size_t lds;
+  int maxc;
+  size_t part_tiles;
+};
+
+bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
+  const PackedMat* mats[5] = {&m->layers[0].qkv, &m->layers[0].o, &m->layers[0].gateup, &m->layers[0].down,
+                              &m->lm_head};
+  p->min_nt = 1 << 30;
+  p->lds = attn_lds_bytes(m->cfg.head_dim);
+  p->maxc = 1;
+  p->part_tiles = 0;
+  for (int ph = 0; ph < 5; ++ph) {
+    const int sk = choose_sk(m, ph, *mats[ph], n);
+    if (sk == 0) return false;
+    p->sk[ph] = sk;
+    const int nt = mats[ph]->KT / sk;
+    if (nt < p->min_nt) p->min_nt = nt;
+    const size_t lds = stage_proj_lds_bytes(n, nt);
+    if (lds > p->lds) p->lds = lds;
+    const int mc = max_contributors(m, *mats[ph], sk);
+    if (mc > p->maxc) p->maxc = mc;
+  }
+  for (int ph = 0; ph < 5; ++ph) {
+    const size_t t = (size_t)p->sk[ph] * mats[ph]->NRB * p->maxc;
+    if (t > p->part_tiles) p->part_tiles = t;
+  }
+  return true;
 }
 
 bool is_layer_kind(int kind) { return kind >= PI_T_ATTN_NORM && kind <= PI_T_WD; }
@@ -210,9 +218,62 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     for (const PackedMat* p : {&m->layers[0].qkv, &m->layers[0].gateup}) max_nrb = p->NRB > max_nrb ? p->NRB : max_nrb;
     e = dev_alloc(m, &m->cnt, (size_t)max_nrb * sizeof(int), true);
   }
-  if (e == hipSuccess) e = dev_alloc(m, &m->part, (size_t)max_split_tiles(m) * 1024, false);
-  if (e == hipSuccess) e = dev_alloc(m, &m->done_cnt, sizeof(int), true);
+  if (e == hipSuccess) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess) m->grid = prop.multiProcessorCount;
+  }
+  if (e == hipSuccess) {
+    // split-k scratch for the largest plan over all token counts
+    size_t tiles = 1;
+    for (int n = 1; n <= PI_MAX_BATCH; ++n) {
+      StagePlan sp;
+      if (!make_stage_plan(m, n, &sp)) continue;
+      if (sp.part_tiles > tiles) tiles = sp.part_tiles;
+      if (sp.maxc > m->part_maxc) m->part_maxc = sp.maxc;
+    }
+    // part_maxc is shared by all plans: size for it
+    size_t worst = 0;
+    const PackedMat* mats[5] = {&m->layers[0].qkv, &m->layers[0].o, &m->layers[0].gateup, &m->layers[0].down,
+                                &m->lm_head};
+    for (int n = 1; n <= PI_MAX_BATCH; ++n) {
+      StagePlan sp;
+      if (!make_stage_plan(m, n, &sp)) continue;
+      for (int ph = 0; ph < 5; ++ph) {
+        const size_t t = (size_t)sp.sk[ph] * mats[ph]->NRB * m->part_maxc;
+        if (t > worst) worst = t;
+      }
+    }
+    if (worst < tiles) worst = tiles;
+    e = dev_alloc(m, &m->part, worst * 1024, false);
+  }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
+  if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);
+  if (e == hipSuccess) {
+    std::vector<LayerDev> ld(c.n_layers);
+    auto md = [](const PackedMat& p) {
+      MatDev r;
+      r.w = (const char*)p.data;
+      r.N = p.N;
+      r.K = p.K;
+      r.NRB = p.NRB;
+      r.KT = p.KT;
+      return r;
+    };
+    for (int l = 0; l < c.n_layers; ++l) {
+      const LayerWeights& L = m->layers[l];
+      ld[l].qkv = md(L.qkv);
+      ld[l].o = md(L.o);
+      ld[l].gateup = md(L.gateup);
+      ld[l].down = md(L.down);
+      ld[l].attn_gain = L.attn_gain;
+      ld[l].ffn_gain = L.ffn_gain;
+    }
+    e = dev_alloc(m, &m->layers_dev, ld.size() * sizeof(LayerDev), false);
+    if (e == hipSuccess) e = hipMemcpy(m->layers_dev, ld.data(), ld.size() * sizeof(LayerDev), hipMemcpyHostToDevice);
+  }
   if (e != hipSuccess) return fail(hip_status(e));
   // rotary table: angle = pos * base^(-2t/hd), evaluated in double on the host
   {
@@ -309,11 +370,18 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
   return PI_OK;
 }
 
-int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k, int32_t rbu, int32_t grid) {
-  if (!m || phase < 0 || phase > 4) return PI_E_ARG;
-  m->plan_override[phase][0] = s_k;
-  m->plan_override[phase][1] = rbu;
-  m->plan_override[phase][2] = grid;
+int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64_t count) {
+  if (!m || !dst_host || count < 0) return PI_E_ARG;
+  const float* src = which == 0 ? m->x : which == 1 ? m->q : which == 2 ? m->o : which == 3 ? m->a : nullptr;
+  if (!src) return PI_E_ARG;
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(dst_host, src, (size_t)count * sizeof(float), hipMemcpyDeviceToHost);
+  return hip_status(e);
+}
+
+int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
+  if (!m || phase < 0 || phase > 4 || s_k < 0) return PI_E_ARG;
+  m->sk_override[phase] = s_k;
   return PI_OK;
 }
 
@@ -336,7 +404,7 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
   kv->layer_bytes = (size_t)kv->n_kv_heads * n_cells * kv->head_dim * es;
   kv->bytes_each = kv->layer_bytes * kv->n_layers;
   const int G = m->cfg.n_q_heads / m->cfg.n_kv_heads;
-  const size_t max_units = (size_t)n_cells / attn_sub_chunk(kv_dtype) + 2;
+  const size_t max_units = (size_t)n_cells / 32 + 2;
   const size_t rows = (size_t)kv->n_kv_heads * max_units * G * PI_MAX_BATCH;
   hipError_t e = hipMalloc(&kv->k, kv->bytes_each);
   if (e == hipSuccess) e = hipMalloc(&kv->v, kv->bytes_each);
@@ -344,6 +412,8 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
   if (e == hipSuccess) e = hipMalloc((void**)&kv->cnt, sizeof(int));
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_o, rows * kv->head_dim * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_ml, rows * 2 * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_cnt, kv->n_kv_heads * sizeof(int));
+  if (e == hipSuccess) e = hipMemset(kv->attn_cnt, 0, kv->n_kv_heads * sizeof(int));
   if (e == hipSuccess) e = hipMemset(kv->k, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->v, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->len_dev, 0, sizeof(int32_t));
@@ -360,7 +430,7 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
 int32_t pi_kv_free(pi_kv* kv) {
   if (!kv) return PI_E_ARG;
   (void)hipDeviceSynchronize();
-  for (void* p : {kv->k, kv->v, (void*)kv->len_dev, (void*)kv->cnt, (void*)kv->attn_o, (void*)kv->attn_ml})
+  for (void* p : {kv->k, kv->v, (void*)kv->len_dev, (void*)kv->cnt, (void*)kv->attn_o, (void*)kv->attn_ml, (void*)kv->attn_cnt})
     if (p) (void)hipFree(p);
   delete kv;
   return PI_OK;
@@ -467,138 +537,87 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
         if (!m->set_flags[flag_index(m, kind, l)]) return PI_E_STATE;
     }
   }
-  hipStream_t s = (hipStream_t)stream;
-  const int d = c.d_model, nq = m->n_q_rows(), nkv = m->n_kv_rows();
-  hipError_t e = launch_latch(m->rs, cancel_flag, run->slots, n, kv->len_dev, run->window_base, kv->n_cells,
-                              layer_begin, s);
-  if (e != hipSuccess) return hip_status(e);
-  e = launch_embed(m->embed, c.dtype, run->tokens, layer_begin == 0 ? nullptr : hidden_in, n, d, c.vocab, m->x,
-                   m->ssq, m->rs, s);
-  if (e != hipSuccess) return hip_status(e);
-
-  ProjArgs base;
-  memset(&base, 0, sizeof(base));
-  base.n = n;
-  base.NP = n;
-  base.eps = c.rms_eps;
-  base.part = m->part;
-  base.cnt = m->cnt;
-  base.rs = m->rs;
-  base.n_ssq_blocks = d / 16;
-  auto fill = [&](ProjArgs& a, const PackedMat& w, int phase, int* grid) {
-    a.W = w.data;
-    a.N = w.N;
-    a.K = w.K;
-    a.NRB = w.NRB;
-    a.KT = w.KT;
-    const Plan p = make_plan(m, phase, w, n);
-    a.S_k = p.S_k;
-    a.RBU = p.RBU;
-    *grid = p.grid;
-  };
-  const size_t kv_layer_elems = (size_t)kv->n_kv_heads * kv->n_cells * kv->head_dim;
-  const size_t kv_es = kv->dtype == PI_DTYPE_BF16 ? 2 : 4;
-
-  for (int l = layer_begin; l < layer_end; ++l) {
-    const LayerWeights& W = m->layers[l];
-    int grid = 0;
-    char* kl = (char*)kv->k + (size_t)l * kv_layer_elems * kv_es;
-    char* vl = (char*)kv->v + (size_t)l * kv_layer_elems * kv_es;
-    {  // RMSNorm + QKV projection + RoPE + KV write
-      ProjArgs a = base;
-      fill(a, W.qkv, 0, &grid);
-      a.xin = m->x;
-      a.gain = W.attn_gain;
-      a.ssq_in = m->ssq;
-      a.out = m->q;
-      a.n_q_rows = nq;
-      a.n_kv_rows = nkv;
-      a.head_dim = c.head_dim;
-      a.kcache = kl;
-      a.vcache = vl;
-      a.n_cells = kv->n_cells;
-      a.kv_dtype = kv->dtype;
-      a.positions = run->positions;
-      a.slots = run->slots;
-      a.rope = m->rope;
-      e = launch_proj(a, EPI_QKV, c.dtype, grid, s);
-      if (e != hipSuccess) return hip_status(e);
-    }
-    {  // attention
-      AttnArgs t;
-      memset(&t, 0, sizeof(t));
-      t.q = m->q;
-      t.kcache = kl;
-      t.vcache = vl;
-      t.kv_dtype = kv->dtype;
-      t.n_cells = kv->n_cells;
-      t.n = n;
-      t.n_q_heads = c.n_q_heads;
-      t.n_kv_heads = c.n_kv_heads;
-      t.head_dim = c.head_dim;
-      t.prefix_len = run->prefix_len;
-      t.window_base = run->window_base;
-      t.mask = run->mask;
-      const int sc = attn_sub_chunk(kv->dtype);
-      int chunk = (int)(((int64_t)run->prefix_len * c.n_kv_heads + 383) / 384);
-      chunk = ((chunk + sc - 1) / sc) * sc;
-      if (chunk < sc) chunk = sc;
-      t.chunk_cells = chunk;
-      t.n_prefix_units = (run->prefix_len + chunk - 1) / chunk;
-      t.part_o = kv->attn_o;
-      t.part_ml = kv->attn_ml;
-      t.out = m->o;
-      t.rs = m->rs;
-      e = launch_attention(t, s);
-      if (e != hipSuccess) return hip_status(e);
-    }
-    {  // output projection + residual
-      ProjArgs a = base;
-      fill(a, W.o, 1, &grid);
-      a.xin = m->o;
-      a.out = m->x;
-      a.ssq_out = m->ssq;
-      e = launch_proj(a, EPI_RESID, c.dtype, grid, s);
-      if (e != hipSuccess) return hip_status(e);
-    }
-    {  // RMSNorm + gate/up projection + SwiGLU
-      ProjArgs a = base;
-      fill(a, W.gateup, 2, &grid);
-      a.xin = m->x;
-      a.gain = W.ffn_gain;
-      a.ssq_in = m->ssq;
-      a.out = m->a;
-      e = launch_proj(a, EPI_SWIGLU, c.dtype, grid, s);
-      if (e != hipSuccess) return hip_status(e);
-    }
-    {  // down projection + residual; layer boundary: record progress, probe the cancel flag
-      ProjArgs a = base;
-      fill(a, W.down, 3, &grid);
-      a.xin = m->a;
-      a.out = m->x;
-      a.ssq_out = m->ssq;
-      a.rs_mut = m->rs;
-      a.done_cnt = m->done_cnt;
-      a.cancel_flag = cancel_flag;
-      a.next_layer = l + 1;
-      a.probe = (l + 1 < layer_end) ? 1 : 0;
-      e = launch_proj(a, EPI_RESID, c.dtype, grid, s);
-      if (e != hipSuccess) return hip_status(e);
-    }
+  StagePlan sp;
+  if (!make_stage_plan(m, n, &sp)) return PI_E_SHAPE;
+  const int ring = stage_ring_size(c.dtype, sp.min_nt);
+  if (ring == 0) return PI_E_SHAPE;
+  if (sp.lds > m->configured_lds[ring]) {
+    int blocks = 0;
+    hipError_t ce = stage_configure(c.dtype, ring, sp.lds, &blocks);
+    if (ce != hipSuccess) return hip_status(ce);
+    if (blocks < 1) return PI_E_SHAPE;
+    m->configured_lds[ring] = sp.lds;
   }
-  if (layer_end == L) {  // final RMSNorm + LM head
-    int grid = 0;
-    ProjArgs a = base;
-    fill(a, m->lm_head, 4, &grid);
-    a.xin = m->x;
-    a.gain = m->final_gain;
-    a.ssq_in = m->ssq;
-    a.out = logits_out;
-    e = launch_proj(a, EPI_LOGITS, c.dtype, grid, s);
-    if (e != hipSuccess) return hip_status(e);
+  StageArgs a;
+  memset(&a, 0, sizeof(a));
+  a.layers = m->layers_dev;
+  a.lm_head.w = (const char*)m->lm_head.data;
+  a.lm_head.N = m->lm_head.N;
+  a.lm_head.K = m->lm_head.K;
+  a.lm_head.NRB = m->lm_head.NRB;
+  a.lm_head.KT = m->lm_head.KT;
+  a.final_gain = m->final_gain;
+  a.embed = m->embed;
+  a.rope = m->rope;
+  a.dtype = c.dtype;
+  a.d = c.d_model;
+  a.n_q_heads = c.n_q_heads;
+  a.n_kv_heads = c.n_kv_heads;
+  a.head_dim = c.head_dim;
+  a.ffn = c.ffn;
+  a.vocab = c.vocab;
+  a.n_layers = L;
+  a.eps = c.rms_eps;
+  a.n = n;
+  a.tokens = run->tokens;
+  a.positions = run->positions;
+  a.slots = run->slots;
+  a.mask = run->mask;
+  a.prefix_len = run->prefix_len;
+  a.window_base = run->window_base;
+  a.layer_begin = layer_begin;
+  a.layer_end = layer_end;
+  a.hidden_in = hidden_in;
+  a.hidden_out = hidden_out;
+  a.logits_out = logits_out;
+  a.cancel_flag = cancel_flag;
+  a.run_status = run_status;
+  a.kbase = (char*)kv->k;
+  a.vbase = (char*)kv->v;
+  a.kv_layer_bytes = kv->layer_bytes;
+  a.n_cells = kv->n_cells;
+  a.kv_dtype = kv->dtype;
+  a.kv_len = kv->len_dev;
+  a.x = m->x;
+  a.q = m->q;
+  a.o = m->o;
+  a.a = m->a;
+  a.ssq = m->ssq;
+  a.part = m->part;
+  a.part_maxc = m->part_maxc;
+  a.cnt = m->cnt;
+  a.attn_o = kv->attn_o;
+  a.attn_ml = kv->attn_ml;
+  a.attn_cnt = kv->attn_cnt;
+  a.rs = m->rs;
+  a.sync = m->sync;
+  for (int ph = 0; ph < 5; ++ph) a.sk[ph] = sp.sk[ph];
+  {
+    // attention work units: per kv head, the prefix in chunks (multiples of 32 cells) sized so
+    // that about one unit per workgroup exists; the last unit of a head also takes the window
+    const int sc = 32;
+    long per_head = m->grid / c.n_kv_heads;
+    if (per_head < 1) per_head = 1;
+    int chunk = (int)((run->prefix_len + per_head - 1) / per_head);
+    chunk = ((chunk + sc - 1) / sc) * sc;
+    if (chunk < sc) chunk = sc;
+    int units = (run->prefix_len + chunk - 1) / chunk;
+    if (units < 1) units = 1;
+    a.attn_chunk = chunk;
+    a.attn_units_per_head = units;
   }
-  e = launch_finish(m->rs, run_status, m->x, layer_end == L ? nullptr : hidden_out, n, d, s);
-  return hip_status(e);
+  a.timeout_ticks = kBarrierTimeoutTicks;
+  return hip_status(launch_stage(a, c.dtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
 
 int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,

@@ -1,79 +1,9 @@
-// Small kernels around the layer loop: run latch, embedding gather, stage output, greedy
-// verification (argmax + tree walk), KV commit/rollback, KV cell set/get.
+// Kernels beside the stage kernel: greedy verification (argmax + tree walk), KV
+// commit/rollback, KV cell set/get.
 #include "pi_internal.h"
 
 namespace pi {
 namespace {
-
-// ---- run latch: validate the run's slots, probe the cancel flag once, arm the run state ----
-__global__ void latch_kernel(RunState* rs, const int32_t* cancel_flag, const int32_t* slots, int n,
-                             const int32_t* kv_len, int window_base, int n_cells, int layer_begin) {
-  if (threadIdx.x != 0) return;
-  int status = PI_OK, dead = 0;
-  const int len = *kv_len;
-  for (int i = 0; i < n; ++i) {
-    const int s = slots[i];
-    if (s < len || s < window_base || s >= window_base + PI_WINDOW || s >= n_cells) {
-      status = PI_E_SLOT_LIVE;
-      dead = 1;
-    }
-  }
-  if (!dead && cancel_flag &&
-      __hip_atomic_load(cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
-    status = PI_CANCELLED;
-    dead = 1;
-  }
-  rs->dead = dead;
-  rs->status = status;
-  rs->layers_done = layer_begin;
-}
-
-// ---- stage input: embedding rows (or the previous stage's activations) -> x, plus the
-// per-16-column partial sums of squares the first RMSNorm needs.  One thread per 4 columns.
-__global__ void __launch_bounds__(256) embed_kernel(const void* embed, int dtype,
-                                                    const int32_t* tokens, const float* hidden_in,
-                                                    int n, int d, int vocab, float* x, float* ssq,
-                                                    const RunState* rs) {
-  if (rs->dead) return;
-  const int per_row = d / 4;
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  const bool live = idx < n * per_row;
-  const int i = live ? idx / per_row : 0, c = live ? (idx % per_row) * 4 : 0;
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (live) {
-    if (hidden_in) {
-      v = *(const float4*)(hidden_in + (size_t)i * d + c);
-    } else {
-      int tok = tokens[i];
-      tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
-      if (dtype == PI_DTYPE_BF16) {
-        const uint2 p = *(const uint2*)((const uint16_t*)embed + (size_t)tok * d + c);
-        v = make_float4(__uint_as_float(p.x << 16), __uint_as_float(p.x & 0xffff0000u),
-                        __uint_as_float(p.y << 16), __uint_as_float(p.y & 0xffff0000u));
-      } else {
-        v = *(const float4*)((const float*)embed + (size_t)tok * d + c);
-      }
-    }
-    *(float4*)(x + (size_t)i * d + c) = v;
-  }
-  // 4 consecutive threads cover one 16-column block of one token
-  float s = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-  s += __shfl_xor(s, 1);
-  s += __shfl_xor(s, 2);
-  if (live && (threadIdx.x & 3) == 0) ssq[(c / 16) * 16 + i] = s;
-}
-
-__global__ void __launch_bounds__(256) finish_kernel(const RunState* rs, int32_t* run_status,
-                                                     const float* x, float* hidden_out, int n, int d) {
-  if (blockIdx.x == 0 && threadIdx.x == 0 && run_status) {
-    run_status[0] = rs->status;
-    run_status[1] = rs->layers_done;
-  }
-  if (rs->dead || !hidden_out) return;
-  const int total = n * d / 4;
-  for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x)
-    ((float4*)hidden_out)[idx] = ((const float4*)x)[idx];
-}
 
 // ---- greedy verification -------------------------------------------------------------------
 // One block per logits row finds argmax (lowest id on ties); the last block to finish walks
@@ -218,31 +148,6 @@ __global__ void __launch_bounds__(256) kv_get_kernel(const char* kbuf, const cha
 }
 
 }  // namespace
-
-hipError_t launch_latch(RunState* rs, const int32_t* cancel_flag, const int32_t* slots, int n,
-                        const int32_t* kv_len, int window_base, int n_cells, int layer_begin,
-                        hipStream_t s) {
-  latch_kernel<<<dim3(1), dim3(64), 0, s>>>(rs, cancel_flag, slots, n, kv_len, window_base, n_cells, layer_begin);
-  return hipGetLastError();
-}
-
-hipError_t launch_embed(const void* embed, int dtype, const int32_t* tokens, const float* hidden_in,
-                        int n, int d, int vocab, float* x, float* ssq, const RunState* rs,
-                        hipStream_t s) {
-  const int total = n * d / 4;
-  embed_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(embed, dtype, tokens, hidden_in,
-                                                                          n, d, vocab, x, ssq, rs);
-  return hipGetLastError();
-}
-
-hipError_t launch_finish(const RunState* rs, int32_t* run_status, const float* x, float* hidden_out,
-                         int n, int d, hipStream_t s) {
-  const int total = hidden_out ? n * d / 4 : 1;
-  int blocks = (total + 255) / 256;
-  if (blocks > 256) blocks = 256;
-  finish_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(rs, run_status, x, hidden_out, n, d);
-  return hipGetLastError();
-}
 
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
                          int vocab, int root_expected, int32_t* accepted, int32_t* result,

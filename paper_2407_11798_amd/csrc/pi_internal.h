@@ -30,72 +30,83 @@ struct PackedMat {
   size_t bytes = 0;
 };
 
-// Device-visible state of the run in flight on a model.
-struct RunState {
-  int32_t dead;         // non-zero: every later kernel of the run falls through
-  int32_t status;       // PI_OK / PI_CANCELLED / PI_E_SLOT_LIVE
-  int32_t layers_done;  // first layer not evaluated
-  int32_t pad;
-};
-
 struct LayerWeights {
   PackedMat qkv, o, gateup, down;
   float* attn_gain = nullptr;
   float* ffn_gain = nullptr;
 };
 
-enum Epilogue { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+constexpr int kStageThreads = 512;  // 8 waves per workgroup, one workgroup per compute unit
 
-// Everything a projection launch needs.  Pointers are device pointers.
-struct ProjArgs {
-  const void* W;
-  int N, K, NRB, KT;
-  int S_k;  // k splits
-  int RBU;  // row blocks per work unit
-  int n;    // tokens
-  int NP;   // token slots staged in LDS (>= n, <= 16)
-  const float* xin;     // [n][K] fp32
-  const float* gain;    // [K] or nullptr
-  const float* ssq_in;  // [n_ssq_blocks][16] partial sums of squares of xin rows, or nullptr
-  int n_ssq_blocks;
-  float eps;
-  float* part;  // [S_k][NRB][256] split-k partial tiles
-  int* cnt;     // [NRB] arrival counters, zero between launches
-  const RunState* rs;
-  // --- epilogue outputs
-  float* out;          // RESID: x[n][N] (+=) ; SWIGLU: a[n][N/2] ; LOGITS: logits[n][N] ; QKV: q[n][n_q_rows]
-  float* ssq_out;      // RESID: [NRB][16]
-  // QKV only
-  int n_q_rows, n_kv_rows, head_dim;
-  void* kcache;        // this layer's K: [Hkv][cells][hd]
-  void* vcache;
-  int n_cells;
-  int kv_dtype;
-  const int32_t* positions;
-  const int32_t* slots;
-  const float2* rope;  // [max_pos][hd/2] (cos, sin)
-  // layer-boundary cancellation probe (RESID of the down projection only)
-  RunState* rs_mut;          // nullptr: no probe
-  int* done_cnt;             // counts finished row blocks of this launch
-  const int32_t* cancel_flag;
-  int next_layer;            // value for layers_done once this launch has finished
-  int probe;                 // 1: probe cancel_flag when the launch completes
+// Device-visible state of the run in flight on a model.
+struct RunState {
+  int32_t dead;         // non-zero: the run stops at the next layer boundary
+  int32_t status;       // PI_OK / PI_CANCELLED / PI_E_SLOT_LIVE
+  int32_t layers_done;  // first layer not evaluated
+  int32_t pad;
 };
 
-struct AttnArgs {
-  const float* q;   // [n][Hq*hd]
-  const void* kcache;  // [Hkv][cells][hd]
-  const void* vcache;
-  int kv_dtype, n_cells;
-  int n, n_q_heads, n_kv_heads, head_dim;
-  int prefix_len, window_base;
+// Grid barrier words; all zero between launches (the last workgroup to leave re-arms them).
+struct StageSync {
+  unsigned count, release, abort, exited;
+};
+
+struct MatDev {
+  const char* w;
+  int N, K, NRB, KT;
+};
+
+struct LayerDev {
+  MatDev qkv, o, gateup, down;
+  const float* attn_gain;
+  const float* ffn_gain;
+};
+
+enum Epilogue { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+
+// Kernel argument of the stage kernel.  All pointers are device pointers.
+struct StageArgs {
+  // model
+  const LayerDev* layers;
+  MatDev lm_head;
+  const float* final_gain;
+  const void* embed;
+  const float2* rope;  // [max_pos][hd/2] (cos, sin)
+  int dtype, d, n_q_heads, n_kv_heads, head_dim, ffn, vocab, n_layers;
+  float eps;
+  // run
+  int n;
+  const int32_t* tokens;
+  const int32_t* positions;
+  const int32_t* slots;
   const uint64_t* mask;
-  int chunk_cells;   // prefix cells per work unit (multiple of the sub-chunk size)
-  int n_prefix_units;
-  float* part_o;     // [Hkv][units][R][hd]
-  float* part_ml;    // [Hkv][units][R][2]
-  float* out;        // [n][Hq*hd]
-  const RunState* rs;
+  int prefix_len, window_base;
+  int layer_begin, layer_end;
+  const float* hidden_in;
+  float* hidden_out;
+  float* logits_out;
+  const int32_t* cancel_flag;
+  int32_t* run_status;
+  // kv cache: K and V each [L][Hkv][cells][hd]
+  char* kbase;
+  char* vbase;
+  size_t kv_layer_bytes;
+  int n_cells, kv_dtype;
+  const int32_t* kv_len;
+  // scratch
+  float *x, *q, *o, *a, *ssq;
+  float* part;   // [S_k][NRB][part_maxc][256] split-k partial tiles
+  int part_maxc;
+  int* cnt;      // [NRB] arrival counters, zero between phases
+  float* attn_o;   // [Hkv][units][R][hd]
+  float* attn_ml;  // [Hkv][units][R][2]
+  int* attn_cnt;   // [Hkv]
+  RunState* rs;
+  StageSync* sync;
+  // work split
+  int sk[5];  // column slices per projection phase: QKV, O, gate/up, down, LM head
+  int attn_chunk, attn_units_per_head;
+  unsigned long long timeout_ticks;  // 100 MHz ticks a barrier wait may last
 };
 
 // ---- launch wrappers (each defined next to its kernels) ---------------------------------
@@ -103,18 +114,11 @@ hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, Pac
                          int dst_dtype, int row_mul, int row_add, hipStream_t s);
 hipError_t launch_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t count,
                           hipStream_t s);
-hipError_t launch_proj(const ProjArgs& a, int epi, int dtype, int grid, hipStream_t s);
-size_t proj_lds_bytes(int NP, int k_tiles_per_split);
-hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
-int attn_sub_chunk(int kv_dtype);
-hipError_t launch_latch(RunState* rs, const int32_t* cancel_flag, const int32_t* slots, int n,
-                        const int32_t* kv_len, int window_base, int n_cells, int layer_begin,
-                        hipStream_t s);
-hipError_t launch_embed(const void* embed, int dtype, const int32_t* tokens, const float* hidden_in,
-                        int n, int d, int vocab, float* x, float* ssq, const RunState* rs,
-                        hipStream_t s);
-hipError_t launch_finish(const RunState* rs, int32_t* run_status, const float* x, float* hidden_out,
-                         int n, int d, hipStream_t s);
+size_t attn_lds_bytes(int head_dim);
+size_t stage_proj_lds_bytes(int n, int nt);
+int stage_ring_size(int dtype, int min_nt);
+hipError_t stage_configure(int dtype, int ring, size_t max_lds, int* max_blocks_per_cu);
+hipError_t launch_stage(const StageArgs& a, int dtype, int ring, int grid, size_t lds, hipStream_t s);
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
                          int vocab, int root_expected, int32_t* accepted, int32_t* result,
                          float* best_val, int32_t* best_idx, int* cnt, hipStream_t s);
