@@ -195,6 +195,10 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],
  * 3 SwiGLU output [n][ffn]).  Blocking. */
+/* Debug hook: device timestamps (100 MHz clock) taken by workgroup 0 each time it passes a grid
+ * barrier of the last run: [0] run latch, [1] stage input ready, then per layer QKV, attention,
+ * O, gate/up, down (layer boundary).  count <= 5 * n_layers + 8.  Blocking. */
+int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count);
 int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64_t count);
 
 #ifdef __cplusplus

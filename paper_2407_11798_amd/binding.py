@@ -27,7 +27,7 @@ EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
     "pi_stage_forward", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
-    "pi_debug_read_scratch",
+    "pi_debug_read_scratch", "pi_debug_read_trace",
 ]
 
 
@@ -78,6 +78,7 @@ def lib():
         L.pi_strerror.argtypes = [c_int32]
         L.pi_strerror.restype = ctypes.c_char_p
         L.pi_debug_set_plan.argtypes = [c_void_p, c_int32, c_int32]
+        L.pi_debug_read_trace.argtypes = [c_void_p, c_void_p, c_int32]
         L.pi_debug_read_scratch.argtypes = [c_void_p, c_int32, c_void_p, c_int64]
         for name in EXPORTS:
             if name != "pi_strerror":
@@ -146,6 +147,11 @@ class Model:
 
     def set_plan(self, phase, s_k=0):
         _check(lib().pi_debug_set_plan(self.handle, phase, s_k), "pi_debug_set_plan")
+
+    def read_trace(self, count: int):
+        out = np.zeros(count, dtype=np.uint64)
+        _check(lib().pi_debug_read_trace(self.handle, c_void_p(out.ctypes.data), count), "pi_debug_read_trace")
+        return out
 
     def read_scratch(self, which: int, shape):
         out = np.empty(shape, dtype=np.float32)

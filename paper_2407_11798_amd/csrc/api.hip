@@ -31,7 +31,12 @@ struct pi_model {
   int* cnt = nullptr;  // row-block arrival counters
   RunState* rs = nullptr;
   StageSync* sync = nullptr;
+  unsigned long long* trace = nullptr;  // timestamps of the barriers of the last run
+  int trace_cap = 0;
+  unsigned long long* wgtrace = nullptr;
+  int wgtrace_layer = -1;
   int grid = 0;  // workgroups of the stage kernel = compute units
+  unsigned epoch = 0;  // grid barriers reserved by earlier launches
   size_t configured_lds[17] = {0};  // per ring size: dynamic LDS the kernel was configured for
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
@@ -223,7 +228,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     hipDeviceProp_t prop;
     e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e == hipSuccess) m->grid = prop.multiProcessorCount;
+    if (e == hipSuccess) m->grid = prop.multiProcessorCount < kMaxGrid ? prop.multiProcessorCount : kMaxGrid;
   }
   if (e == hipSuccess) {
     // split-k scratch for the largest plan over all token counts
@@ -251,6 +256,9 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);
+  m->trace_cap = 5 * c.n_layers + 8;
+  if (e == hipSuccess) e = dev_alloc(m, &m->trace, (size_t)m->trace_cap * sizeof(unsigned long long), true);
+  if (e == hipSuccess) e = dev_alloc(m, &m->wgtrace, (size_t)1024 * 8 * sizeof(unsigned long long), true);
   if (e == hipSuccess) {
     std::vector<LayerDev> ld(c.n_layers);
     auto md = [](const PackedMat& p) {
@@ -376,6 +384,22 @@ int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64
   if (!src) return PI_E_ARG;
   hipError_t e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMemcpy(dst_host, src, (size_t)count * sizeof(float), hipMemcpyDeviceToHost);
+  return hip_status(e);
+}
+
+int32_t pi_debug_wgtrace(pi_model* m, int32_t layer, uint64_t* dst_host) {
+  if (!m) return PI_E_ARG;
+  m->wgtrace_layer = layer;
+  if (!dst_host) return PI_OK;
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(dst_host, m->wgtrace, (size_t)m->grid * 8 * sizeof(uint64_t), hipMemcpyDeviceToHost);
+  return hip_status(e);
+}
+
+int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
+  if (!m || !dst_host || count < 0 || count > m->trace_cap) return PI_E_ARG;
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess) e = hipMemcpy(dst_host, m->trace, (size_t)count * sizeof(uint64_t), hipMemcpyDeviceToHost);
   return hip_status(e);
 }
 
@@ -617,6 +641,12 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
     a.attn_units_per_head = units;
   }
   a.timeout_ticks = kBarrierTimeoutTicks;
+  a.epoch_base = m->epoch;
+  m->epoch += (unsigned)(5 * (layer_end - layer_begin) + 4);  // every barrier this launch can reach
+  a.trace = m->trace;
+  a.trace_cap = m->trace_cap;
+  a.wgtrace = m->wgtrace_layer >= 0 ? m->wgtrace : nullptr;
+  a.wgtrace_layer = m->wgtrace_layer;
   return hip_status(launch_stage(a, c.dtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
 

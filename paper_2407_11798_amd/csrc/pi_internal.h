@@ -46,9 +46,16 @@ struct RunState {
   int32_t pad;
 };
 
-// Grid barrier words; all zero between launches (the last workgroup to leave re-arms them).
+// Grid barrier state.  Every workgroup owns one arrival flag and publishes the (ever growing)
+// number of the barrier it has reached; a barrier is passed when every flag has reached it, so
+// there is no shared counter to contend on and nothing to reset between launches.
+constexpr int kMaxGrid = 1024;
 struct StageSync {
-  unsigned count, release, abort, exited;
+  unsigned flags[kMaxGrid];
+  unsigned decision;  // last layer-boundary barrier whose cancel decision workgroup 0 has published
+  unsigned abort;     // sticky: a barrier wait ran into its time limit
+  unsigned exited;
+  unsigned pad;
 };
 
 struct MatDev {
@@ -107,6 +114,11 @@ struct StageArgs {
   int sk[5];  // column slices per projection phase: QKV, O, gate/up, down, LM head
   int attn_chunk, attn_units_per_head;
   unsigned long long timeout_ticks;  // 100 MHz ticks a barrier wait may last
+  unsigned epoch_base;               // barriers used by earlier launches on this model
+  unsigned long long* trace;  // optional: 100 MHz timestamps, one per barrier passed by workgroup 0
+  int trace_cap;
+  unsigned long long* wgtrace;  // optional debug: [grid][8] timestamps of workgroup events in one layer
+  int wgtrace_layer;
 };
 
 // ---- launch wrappers (each defined next to its kernels) ---------------------------------

@@ -45,54 +45,102 @@ __device__ __forceinline__ void st_ag_u32(uint32_t* p, uint32_t v) {
 __device__ __forceinline__ void st_ag4(float* p, float a, float b, float c, float d) {
   st_ag(p, a); st_ag(p + 1, b); st_ag(p + 2, c); st_ag(p + 3, d);
 }
+// 128/64-bit agent-scope accesses through a raw buffer (cache policy sc1: coherent across XCDs)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+constexpr int kAgent = 16;  // sc1
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ f32x4 ld_ag4(__amdgpu_buffer_rsrc_t r, int byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kAgent));
+}
+__device__ __forceinline__ void st_ag4(__amdgpu_buffer_rsrc_t r, int byte_off, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, byte_off, 0, kAgent);
+}
+__device__ __forceinline__ void st_ag2(__amdgpu_buffer_rsrc_t r, int byte_off, float a, float b) {
+  u32x2 v = {__float_as_uint(a), __float_as_uint(b)};
+  __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, 0, kAgent);
+}
 // all earlier memory operations of this wave have completed (stores are visible at agent scope
 // because they were issued with agent scope)
-__device__ __forceinline__ void wave_drain() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+__device__ __forceinline__ void wave_drain() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void wg_mark(const StageArgs& A, int l, int ev) {
+  if (A.wgtrace && l == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + ev] = wall_clock64();
+}
 
 // ---- grid barrier ---------------------------------------------------------------------------
 // Every workgroup calls it the same number of times.  Returns false when the grid must stop
 // (a wait ran into its time limit somewhere): callers then leave the kernel at once.
 // probe_layer >= 0: layer boundary; the last arriver records progress and probes the cancel flag.
 struct BarrierCtx {
-  unsigned epoch;
-  int* sh;  // 2 ints of LDS: {ok, dead}
+  unsigned epoch;  // absolute number of the last barrier passed
+  int* sh;         // 2 ints of LDS: {ok, dead}
 };
 
+// Every workgroup calls it the same number of times.  Returns false when the grid must stop (a
+// wait ran into its time limit): callers then leave the kernel at once.  layers_done >= 0 marks
+// a layer boundary: workgroup 0 records progress, probes the cancel flag when `probe` is set
+// and publishes the decision, which every workgroup reads before going on.
 __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe) {
-  __syncthreads();  // every wave of this workgroup is past its stores (each drained itself)
+  __syncthreads();  // every wave of this workgroup has drained its stores
   bc.epoch += 1;
-  if (threadIdx.x == 0) {
-    StageSync* sy = A.sync;
-    const unsigned target = bc.epoch * gridDim.x;
-    const unsigned old = __hip_atomic_fetch_add(&sy->count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  StageSync* sy = A.sync;
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const __amdgpu_buffer_rsrc_t fr = rsrc_of(sy->flags);
+    const int G = gridDim.x;
+    const unsigned long long t0 = wall_clock64();
     int ok = 1;
-    if (old == target - 1) {
-      if (layers_done >= 0) {
-        __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (probe && A.cancel_flag &&
-            __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
-          __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(&A.rs->dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        wave_drain();
+    for (unsigned spin = 0;; ++spin) {
+      bool all = true;
+      for (int base = 0; base < G; base += 256) {
+        const int idx = base + lane * 4;
+        u32x4 f = {bc.epoch, bc.epoch, bc.epoch, bc.epoch};
+        if (idx < G) f = __builtin_amdgcn_raw_buffer_load_b128(fr, idx * 4, 0, kAgent);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (int)(f[q] - bc.epoch) >= 0);
       }
-      __hip_atomic_store(&sy->release, bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      const unsigned long long t0 = wall_clock64();
-      while (__hip_atomic_load(&sy->release, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bc.epoch) {
-        __builtin_amdgcn_s_sleep(1);
-        if (__hip_atomic_load(&sy->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ok = 0; break; }
-        if (wall_clock64() - t0 > A.timeout_ticks) {
-          __hip_atomic_store(&sy->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          ok = 0;
-          break;
-        }
+      if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
+      __builtin_amdgcn_s_sleep(1);
+      if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+        ok = 0;
+        break;
       }
     }
-    bc.sh[0] = ok;
-    bc.sh[1] = (layers_done >= 0 && ok)
-                   ? __hip_atomic_load(&A.rs->dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                   : 0;
+    int dead = 0;
+    if (ok && layers_done >= 0) {
+      if (blockIdx.x == 0) {
+        if (lane == 0) {
+          __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (probe && A.cancel_flag &&
+              __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
+            __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&A.rs->dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+        wave_drain();
+        if (lane == 0) __hip_atomic_store(&sy->decision, bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        for (unsigned spin = 0;; ++spin) {
+          const unsigned d = __hip_atomic_load(&sy->decision, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if ((int)(d - bc.epoch) >= 0) break;
+          __builtin_amdgcn_s_sleep(1);
+          if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+            ok = 0;
+            break;
+          }
+        }
+      }
+      if (ok) dead = __hip_atomic_load(&A.rs->dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane == 0) {
+      if (!ok) __hip_atomic_store(&sy->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (A.trace && blockIdx.x == 0 && (int)(bc.epoch - A.epoch_base) <= A.trace_cap)
+        A.trace[bc.epoch - A.epoch_base - 1] = wall_clock64();
+      bc.sh[0] = ok;
+      bc.sh[1] = dead;
+    }
   }
   __syncthreads();
   return __builtin_amdgcn_readfirstlane(bc.sh[0]) != 0;
@@ -104,7 +152,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
 // cut into equal contiguous ranges, one per wave of the group: flat index f -> row block f / nt,
 // k tile t0 + f % nt.
 struct WaveStream {
-  const char* base;
+  __amdgpu_buffer_rsrc_t rsrc;  // the whole matrix as a raw buffer
   int KT, nt, t0, NRB;
   int f0, f1, share;
   int slice, gw;  // slice index, wave index within the slice group
@@ -144,9 +192,15 @@ __device__ __forceinline__ LayerDev uni_layer(const LayerDev& l) {
   return r;
 }
 
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+template <int DT>
 __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int S_k, int wave) {
   const int wg = blockIdx.x, G = gridDim.x;
-  S.base = M.w;
+  constexpr int kTileBytes = DT == PI_DTYPE_BF16 ? 1024 : 2048;
+  S.rsrc = make_rsrc(M.w, (uint32_t)M.NRB * (uint32_t)M.KT * kTileBytes);
   S.KT = M.KT;
   S.NRB = M.NRB;
   S.nt = uni(M.KT / S_k);
@@ -163,16 +217,6 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   S.lt = S.f0 - S.lrb * S.nt;
 }
 
-// Re-assert that the stream state is wave-uniform (values that crossed a branch the compiler
-// could not prove uniform would otherwise be kept in vector registers).
-__device__ __forceinline__ void stream_uniform(WaveStream& S) {
-  S.base = uni_ptr(S.base);
-  S.KT = uni(S.KT); S.nt = uni(S.nt); S.t0 = uni(S.t0); S.NRB = uni(S.NRB);
-  S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
-  S.slice = uni(S.slice); S.gw = uni(S.gw);
-  S.lf = uni(S.lf); S.lrb = uni(S.lrb); S.lt = uni(S.lt);
-}
-
 // The ring of outstanding weight tiles: UR tiles, each 1 KiB (bf16: one 16-byte load per lane)
 // or 2 KiB (fp32: two loads per lane).  Slot indices are compile-time, so it lives in registers.
 template <int DT, int UR>
@@ -183,20 +227,25 @@ struct Ring {
   u32x4 r[kRegs];
 };
 
+// Issue the load of the next tile of the wave's range into slot J.  Branch-free: past the end
+// of the range every lane re-reads the first 16 bytes of the matrix (one cached line) and the
+// consumer discards the slot, so the steady-state loop is a single basic block and the loads
+// stay in flight (a branch around a load makes the compiler wait for it at the join).
 template <int DT, int UR, int J>
 __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int lane) {
-  if (S.lf < S.f1) {
-    const char* p = S.base + ((size_t)S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes + lane * 16;
-    if constexpr (DT == PI_DTYPE_BF16) {
-      R.r[J] = __builtin_nontemporal_load((gptr_u32x4)p);
-    } else {
-      R.r[2 * J] = __builtin_nontemporal_load((gptr_u32x4)p);
-      R.r[2 * J + 1] = __builtin_nontemporal_load((gptr_u32x4)(p + 1024));
-    }
-    S.lf += 1;
-    S.lt += 1;
-    if (S.lt == S.nt) { S.lt = 0; S.lrb += 1; }
+  const bool valid = S.lf < S.f1;
+  const int soff = valid ? (S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes : 0;
+  const int voff = valid ? lane * 16 : 0;
+  if constexpr (DT == PI_DTYPE_BF16) {
+    R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff, 2);
+  } else {
+    R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff, 2);
+    R.r[2 * J + 1] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff + (valid ? 1024 : 0), 2);
   }
+  S.lf += 1;
+  const bool wrap = S.lt + 1 == S.nt;
+  S.lt = wrap ? 0 : S.lt + 1;
+  S.lrb += wrap ? 1 : 0;
 }
 
 template <int DT, int UR, int J = 0>
@@ -214,6 +263,7 @@ template <int DT>
 __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds) {
   const int items = nt * n * 4;
   const int n_slots = nt * 4 * n;
+  const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
   for (int id = threadIdx.x; id < items; id += kThreads) {
     const int cl = id & 3;
     const int i = (id >> 2) % n;
@@ -221,9 +271,10 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
     const int k0 = (t0 + tt) * kKTile + cl * 8;
     float v[8];
     if (k0 < K) {
-      const float* px = xin + (size_t)i * K + k0;
+      const int off = (i * K + k0) * 4;
+      const f32x4 p0 = ld_ag4(xr, off), p1 = ld_ag4(xr, off + 16);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = ld_ag(px + j);
+      for (int j = 0; j < 4; ++j) { v[j] = p0[j]; v[4 + j] = p1[j]; }
       if (gain) {
         const f32x4 g0 = *(gptr_f32x4)(gain + k0);
         const f32x4 g1 = *(gptr_f32x4)(gain + k0 + 4);
@@ -287,12 +338,13 @@ struct EpiCtx {
 };
 
 __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem_idx, const float* v) {
+  const __amdgpu_buffer_rsrc_t r = rsrc_of(cache);
   if (kv_dtype == PI_DTYPE_BF16) {
-    uint32_t* p = (uint32_t*)(cache + elem_idx * 2);
-    st_ag_u32(p, (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16));
-    st_ag_u32(p + 1, (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16));
+    u32x2 p = {(uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16),
+               (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16)};
+    __builtin_amdgcn_raw_buffer_store_b64(p, r, (int)(elem_idx * 2), 0, kAgent);
   } else {
-    st_ag4((float*)cache + elem_idx, v[0], v[1], v[2], v[3]);
+    st_ag4(r, (int)(elem_idx * 4), f32x4{v[0], v[1], v[2], v[3]});
   }
 }
 
@@ -316,7 +368,7 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
       v[0] = a0; v[1] = a1; v[2] = a2; v[3] = a3;
     }
     if (row < e.n_q_rows) {
-      st_ag4(e.out + (size_t)i * e.n_q_rows + row, v[0], v[1], v[2], v[3]);
+      st_ag4(rsrc_of(e.out), (i * e.n_q_rows + row) * 4, f32x4{v[0], v[1], v[2], v[3]});
     } else if (row < e.n_q_rows + 2 * e.n_kv_rows) {
       const bool is_k = row < e.n_q_rows + e.n_kv_rows;
       const int kr = row - e.n_q_rows - (is_k ? 0 : e.n_kv_rows);
@@ -327,11 +379,11 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
   } else if (EPI == EPI_RESID) {
     float s = 0.0f;
     if (live && row < e.N) {
-      float* px = e.out + (size_t)i * e.N + row;
-      const float x0 = ld_ag(px) + acc[0], x1 = ld_ag(px + 1) + acc[1];
-      const float x2 = ld_ag(px + 2) + acc[2], x3 = ld_ag(px + 3) + acc[3];
-      st_ag4(px, x0, x1, x2, x3);
-      s = x0 * x0 + x1 * x1 + x2 * x2 + x3 * x3;
+      const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
+      const int off = (i * e.N + row) * 4;
+      const f32x4 x = ld_ag4(xr, off) + acc;
+      st_ag4(xr, off, x);
+      s = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
     }
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
@@ -340,9 +392,8 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
     if (!live || row >= e.N) return;
     const float r = rscale[i];
     const float g0 = acc[0] * r, u0 = acc[1] * r, g1 = acc[2] * r, u1 = acc[3] * r;
-    float* po = e.out + (size_t)i * (e.N / 2) + row / 2;
-    st_ag(po, g0 / (1.0f + expf(-g0)) * u0);
-    st_ag(po + 1, g1 / (1.0f + expf(-g1)) * u1);
+    st_ag2(rsrc_of(e.out), (i * (e.N / 2) + row / 2) * 4, g0 / (1.0f + expf(-g0)) * u0,
+           g1 / (1.0f + expf(-g1)) * u1);
   } else {  // EPI_LOGITS: read by later kernels only
     if (!live || row >= e.N) return;
     const float r = rscale[i];
@@ -363,22 +414,20 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
   if (expected > 1) {
     const int i = lane & 15;
     const int maxc = A.part_maxc;
-    float* mine = A.part + ((((size_t)S.slice * S.NRB + rb) * maxc + (S.gw - first)) * 64 + lane) * 4;
-    if (i < e.n) st_ag4(mine, acc[0], acc[1], acc[2], acc[3]);
+    const __amdgpu_buffer_rsrc_t pr = rsrc_of(A.part);
+    const int mine = (((S.slice * S.NRB + rb) * maxc + (S.gw - first)) * 64 + lane) * 16;
+    if (i < e.n) st_ag4(pr, mine, acc);
     wave_drain();
     int old = 0;
     if (lane == 0)
       old = __hip_atomic_fetch_add(A.cnt + rb, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __shfl(old, 0);
     if (old != expected - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     acc = f32x4{0.f, 0.f, 0.f, 0.f};
     if (i < e.n) {
       for (int s2 = 0; s2 < S_k; ++s2)
-        for (int j = 0; j < c; ++j) {
-          const float* p = A.part + ((((size_t)s2 * S.NRB + rb) * maxc + j) * 64 + lane) * 4;
-          acc[0] += ld_ag(p); acc[1] += ld_ag(p + 1); acc[2] += ld_ag(p + 2); acc[3] += ld_ag(p + 3);
-        }
+        for (int j = 0; j < c; ++j)
+          acc += ld_ag4(pr, (((s2 * S.NRB + rb) * maxc + j) * 64 + lane) * 16);
     }
     if (lane == 0) __hip_atomic_store(A.cnt + rb, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -412,27 +461,30 @@ struct ConsumeState {
   f32x4 pacc;
 };
 
-// One pass over the ring.  The host guarantees nt >= UR, so at most one row block ends inside a
-// pass; its tile is set aside and flushed after the pass, outside the unrolled body.
+// One pass over the ring, branch-free.  The host guarantees nt >= UR, so at most one row block
+// ends inside a pass; its tile is set aside (pacc) and flushed after the pass.
 template <int DT, int UR, int J>
 __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, ConsumeState& C, const char* lds,
                                              int n, int lane) {
   if constexpr (J < UR) {
-    if (C.f < S.f1) {
-      const int g = lane >> 4, ln = min(lane & 15, n - 1);
-      mma_tile<DT, UR, J>(R, lds, S.nt * 4 * n, (C.t * 4 + g) * n + ln, C.acc);
-      ring_issue<DT, UR, J>(R, S, lane);
-      C.f += 1;
-      C.t += 1;
-      if (C.t == S.nt) {
-        C.pending = true;
-        C.prb = C.rb;
-        C.pacc = C.acc;
-        C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
-        C.t = 0;
-        C.rb += 1;
-      }
+    const bool valid = C.f < S.f1;
+    const int g = lane >> 4, ln = min(lane & 15, n - 1);
+    f32x4 acc2 = C.acc;
+    mma_tile<DT, UR, J>(R, lds, S.nt * 4 * n, (C.t * 4 + g) * n + ln, acc2);
+    ring_issue<DT, UR, J>(R, S, lane);
+    const int t1 = C.t + 1;
+    const bool end_rb = valid && t1 == S.nt;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float a = valid ? acc2[q] : C.acc[q];
+      C.pacc[q] = end_rb ? a : C.pacc[q];
+      C.acc[q] = end_rb ? 0.0f : a;
     }
+    C.prb = end_rb ? C.rb : C.prb;
+    C.pending = C.pending || end_rb;
+    C.f += valid ? 1 : 0;
+    C.t = end_rb ? 0 : (valid ? t1 : C.t);
+    C.rb += end_rb ? 1 : 0;
     consume_step<DT, UR, J + 1>(R, S, C, lds, n, lane);
   }
 }
@@ -441,8 +493,7 @@ __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, Con
 template <int DT, int UR, int EPI>
 __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                               const char* lds, int n, int lane, const EpiCtx& e,
-                                              const float* rscale) {
-  stream_uniform(S);
+                                              const float* rscale, const MatDev* next, int next_sk, int wave) {
   ConsumeState C;
   C.f = S.f0;
   C.rb = uni(S.f0 / S.nt);
@@ -452,13 +503,23 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   C.prb = 0;
   C.pacc = C.acc;
   while (C.f < S.f1) {
-    consume_step<DT, UR, 0>(R, S, C, lds, n, lane);
+    do {  // hot loop: passes without a row-block end
+      consume_step<DT, UR, 0>(R, S, C, lds, n, lane);
+    } while (!C.pending && C.f < S.f1);
     if (C.pending) {
       flush_rowblock<EPI>(A, S, S_k, C.prb, C.pacc, lane, e, rscale);
       C.pending = false;
     }
   }
+  // The ring is free: start the next phase's weight stream before the last (slow) flush, so HBM
+  // stays busy while this wave waits on its reduction round trips and on the grid barrier.
+  WaveStream Sn = S;
+  if (next) {
+    stream_init<DT>(Sn, *next, next_sk, wave);
+    ring_prefetch<DT, UR>(R, Sn, lane);
+  }
   if (C.t > 0) flush_rowblock<EPI>(A, S, S_k, C.rb, C.acc, lane, e, rscale);  // range ends inside a row block
+  S = Sn;
 }
 
 // ---- attention phase ----------------------------------------------------------------------------
@@ -731,7 +792,7 @@ __device__ void embed_phase(const StageArgs& A) {
           v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
         }
       }
-      st_ag4(A.x + (size_t)i * A.d + c, v[0], v[1], v[2], v[3]);
+      st_ag4(rsrc_of(A.x), (i * A.d + c) * 4, f32x4{v[0], v[1], v[2], v[3]});
     }
     float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
     s += __shfl_xor(s, 1);
@@ -751,7 +812,8 @@ __device__ void hidden_out_phase(const StageArgs& A) {
 template <int DT, int UR, int EPI>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                            const float* xin, const float* gain, bool scaled, int K,
-                                           const EpiCtx& e, char* lds, int lane) {
+                                           const EpiCtx& e, char* lds, int lane, const MatDev* next, int next_sk,
+                                           int wave, int trace_layer = -1) {
   const size_t xbytes = (size_t)S.nt * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
@@ -761,7 +823,9 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   } else {
     __syncthreads();
   }
-  consume_phase<DT, UR, EPI>(A, R, S, S_k, lds, A.n, lane, e, rscale);
+  wg_mark(A, trace_layer, 1);
+  consume_phase<DT, UR, EPI>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);
+  wg_mark(A, trace_layer, 2);
   wave_drain();
 }
 
@@ -772,7 +836,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: keep it scalar
   BarrierCtx bc;
-  bc.epoch = 0;
+  bc.epoch = A.epoch_base;
   bc.sh = bar_sh;
   const int L = A.n_layers;
 
@@ -803,7 +867,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   bool dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
   if (ok && !dead) {
     embed_phase(A);
-    stream_init(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
+    stream_init<DT>(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
     ring_prefetch<DT, UR>(R, S, lane);
     ok = grid_barrier(A, bc, -1, false);
   }
@@ -825,37 +889,43 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     // RMSNorm + QKV projection + RoPE + KV write
     e.N = W.qkv.N;
     e.out = A.q;
-    proj_phase<DT, UR, EPI_QKV>(A, R, S, A.sk[0], A.x, W.attn_gain, true, A.d, e, lds, lane);
+    proj_phase<DT, UR, EPI_QKV>(A, R, S, A.sk[0], A.x, W.attn_gain, true, A.d, e, lds, lane, nullptr, 0, wave);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
     // attention
     attention_phase(A, e.kcache, e.vcache, lds);
-    stream_init(S, W.o, A.sk[1], wave);
+    stream_init<DT>(S, W.o, A.sk[1], wave);
     ring_prefetch<DT, UR>(R, S, lane);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
     // output projection + residual
     e.N = W.o.N;
     e.out = A.x;
-    proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[1], A.o, nullptr, false, W.o.K, e, lds, lane);
-    stream_init(S, W.gateup, A.sk[2], wave);
-    ring_prefetch<DT, UR>(R, S, lane);
+    proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[1], A.o, nullptr, false, W.o.K, e, lds, lane, &W.gateup, A.sk[2],
+                                  wave);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
     // RMSNorm + gate/up + SwiGLU
     e.N = W.gateup.N;
     e.out = A.a;
-    proj_phase<DT, UR, EPI_SWIGLU>(A, R, S, A.sk[2], A.x, W.ffn_gain, true, A.d, e, lds, lane);
-    stream_init(S, W.down, A.sk[3], wave);
-    ring_prefetch<DT, UR>(R, S, lane);
+    wg_mark(A, l, 0);
+    proj_phase<DT, UR, EPI_SWIGLU>(A, R, S, A.sk[2], A.x, W.ffn_gain, true, A.d, e, lds, lane, &W.down, A.sk[3],
+                                   wave, l);
+    wg_mark(A, l, 3);
+    wg_mark(A, l, 4);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
+    wg_mark(A, l, 5);
     // down projection + residual
     e.N = W.down.N;
     e.out = A.x;
-    proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[3], A.a, nullptr, false, W.down.K, e, lds, lane);
-    if (l + 1 < A.layer_end) {
-      stream_init(S, uni_mat(A.layers[l + 1].qkv), A.sk[0], wave);
-      ring_prefetch<DT, UR>(R, S, lane);
-    } else if (A.layer_end == L) {
-      stream_init(S, A.lm_head, A.sk[4], wave);
-      ring_prefetch<DT, UR>(R, S, lane);
+    {
+      MatDev nxt = A.lm_head;
+      int nsk = A.sk[4];
+      bool has_next = A.layer_end == L;
+      if (l + 1 < A.layer_end) {
+        nxt = uni_mat(A.layers[l + 1].qkv);
+        nsk = A.sk[0];
+        has_next = true;
+      }
+      proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[3], A.a, nullptr, false, W.down.K, e, lds, lane,
+                                    has_next ? &nxt : nullptr, nsk, wave);
     }
     // layer boundary: record progress; probe the cancel flag unless the stage is complete
     if (!(ok = grid_barrier(A, bc, l + 1, l + 1 < A.layer_end))) break;
@@ -867,7 +937,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       e.n = A.n;
       e.N = A.lm_head.N;
       e.out = A.logits_out;
-      proj_phase<DT, UR, EPI_LOGITS>(A, R, S, A.sk[4], A.x, A.final_gain, true, A.d, e, lds, lane);
+      proj_phase<DT, UR, EPI_LOGITS>(A, R, S, A.sk[4], A.x, A.final_gain, true, A.d, e, lds, lane, nullptr, 0, wave);
     } else {
       hidden_out_phase(A);
     }
@@ -884,8 +954,6 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
                                   : __hip_atomic_load(&A.rs->status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         A.run_status[1] = __hip_atomic_load(&A.rs->layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      __hip_atomic_store(&sy->count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&sy->release, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(&sy->exited, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
