@@ -118,7 +118,7 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
   const PackedMat* mats[5] = {&m->layers[0].qkv, &m->layers[0].o, &m->layers[0].gateup, &m->layers[0].down,
                               &m->lm_head};
   p->min_nt = 1 << 30;
-  p->lds = attn_lds_bytes(m->cfg.head_dim);
+  p->lds = 0;
   p->maxc = 1;
   p->part_tiles = 0;
   for (int ph = 0; ph < 5; ++ph) {
@@ -561,10 +561,32 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
         if (!m->set_flags[flag_index(m, kind, l)]) return PI_E_STATE;
     }
   }
+  if (kv->dtype != c.dtype) return PI_E_SHAPE;  // the attention kernels read the cache in the model's type
   StagePlan sp;
   if (!make_stage_plan(m, n, &sp)) return PI_E_SHAPE;
   const int ring = stage_ring_size(c.dtype, sp.min_nt);
   if (ring == 0) return PI_E_SHAPE;
+  // attention work units: per kv head, the prefix in chunks (multiples of 32 cells) sized so that
+  // about one unit per workgroup exists and a unit's K/V (chunk + window) fits in LDS; the last
+  // unit of a head also takes the window
+  int attn_chunk, attn_units;
+  {
+    constexpr size_t kAttnLdsBudget = 140 * 1024;
+    long per_head = m->grid / c.n_kv_heads;
+    if (per_head < 1) per_head = 1;
+    int chunk = (int)((run->prefix_len + per_head - 1) / per_head);
+    chunk = ((chunk + 31) / 32) * 32;
+    if (chunk < 32) chunk = 32;
+    while (chunk > 32 && (attn_lds_bytes(c.head_dim, c.dtype, chunk + PI_WINDOW) > kAttnLdsBudget ||
+                          chunk + PI_WINDOW > 256))
+      chunk -= 32;
+    if (attn_lds_bytes(c.head_dim, c.dtype, chunk + PI_WINDOW) > kAttnLdsBudget) return PI_E_SHAPE;
+    attn_chunk = chunk;
+    attn_units = (run->prefix_len + chunk - 1) / chunk;
+    if (attn_units < 1) attn_units = 1;
+    const size_t al = attn_lds_bytes(c.head_dim, c.dtype, chunk + PI_WINDOW);
+    if (al > sp.lds) sp.lds = al;
+  }
   if (sp.lds > m->configured_lds[ring]) {
     int blocks = 0;
     hipError_t ce = stage_configure(c.dtype, ring, sp.lds, &blocks);
@@ -626,20 +648,8 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.rs = m->rs;
   a.sync = m->sync;
   for (int ph = 0; ph < 5; ++ph) a.sk[ph] = sp.sk[ph];
-  {
-    // attention work units: per kv head, the prefix in chunks (multiples of 32 cells) sized so
-    // that about one unit per workgroup exists; the last unit of a head also takes the window
-    const int sc = 32;
-    long per_head = m->grid / c.n_kv_heads;
-    if (per_head < 1) per_head = 1;
-    int chunk = (int)((run->prefix_len + per_head - 1) / per_head);
-    chunk = ((chunk + sc - 1) / sc) * sc;
-    if (chunk < sc) chunk = sc;
-    int units = (run->prefix_len + chunk - 1) / chunk;
-    if (units < 1) units = 1;
-    a.attn_chunk = chunk;
-    a.attn_units_per_head = units;
-  }
+  a.attn_chunk = attn_chunk;
+  a.attn_units_per_head = attn_units;
   a.timeout_ticks = kBarrierTimeoutTicks;
   a.epoch_base = m->epoch;
   m->epoch += (unsigned)(5 * (layer_end - layer_begin) + 4);  // every barrier this launch can reach

@@ -523,211 +523,301 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
 }
 
 // ---- attention phase ----------------------------------------------------------------------------
-constexpr int kSC = 32;  // cells per sub-chunk
-constexpr int kRT = 32;  // query rows per row tile
+// Work unit = (kv head, range of prefix cells); the last unit of a head also takes the run's
+// window cells.  The unit's K rows and V columns are staged in LDS once (one round trip), then
+//   S = K Q^T      MFMA, K rows as A operand straight from LDS, Q split into bf16 hi + lo
+//   P = exp(S - rowmax), row sums          (whole unit at once: no running rescale)
+//   O = P V        MFMA, V stored transposed in LDS so cells are the contraction index
+// for all G*n query rows of the kv head, 32 rows at a time.  Each unit parks (max, sum, O); the
+// last unit of a head to arrive merges them in unit order.
+constexpr int kRG = 32;  // query rows per pass
 
-__device__ __forceinline__ void ld_cache8(const char* base, int dt, size_t elem, bool agent, float* out) {
-  // 8 consecutive cache elements starting at `elem` (a multiple of 8)
-  if (dt == PI_DTYPE_BF16) {
-    uint32_t w[4];
-    const uint32_t* p = (const uint32_t*)(base + elem * 2);
-    if (agent) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) w[j] = ld_ag_u32(p + j);
-    } else {
-      const uint4 q = *(const uint4*)p;
-      w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      out[2 * j] = __uint_as_float(w[j] << 16);
-      out[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
-    }
-  } else {
-    const float* p = (const float*)base + elem;
-    if (agent) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) out[j] = ld_ag(p + j);
-    } else {
-      const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
-      out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-      out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
-    }
+struct AttnLds {
+  int cp;       // cells of the unit padded to a multiple of 32
+  int kstride;  // bytes per K / Q row
+  int vstride;  // bytes per V^T / P row
+  int k_off[2], v_off[2], q_off[2], p_off[2], max_off, sum_off, flag_off;
+  int total;
+};
+
+__host__ __device__ inline AttnLds attn_lds_layout(int hd, int cp, int n_split) {
+  AttnLds L;
+  L.cp = cp;
+  L.kstride = hd * 2 + 16;
+  L.vstride = cp * 2 + 16;
+  int off = 0;
+  for (int s = 0; s < 2; ++s) {
+    L.k_off[s] = off;
+    if (s < n_split) off += cp * L.kstride;
   }
+  for (int s = 0; s < 2; ++s) {
+    L.v_off[s] = off;
+    if (s < n_split) off += hd * L.vstride;
+  }
+  for (int s = 0; s < 2; ++s) {
+    L.q_off[s] = off;
+    off += kRG * L.kstride;
+  }
+  for (int s = 0; s < 2; ++s) {
+    L.p_off[s] = off;
+    off += kRG * L.vstride;
+  }
+  L.max_off = off;
+  off += kWaves * kRG * 4;
+  L.sum_off = off;
+  off += kWaves * kRG * 4;
+  L.flag_off = off;
+  off += 16;
+  L.total = off;
+  return L;
 }
 
-// One work unit = (kv head h, unit u): prefix cells [u*chunk, ...) and, for the last unit of a
-// head, also the speculative window.  All G*n query rows of the kv head pass over the unit's
-// cells in sub-chunks of 32 with a running (max, sum) softmax.
-template <int HD>
-__device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds_raw) {
-  constexpr int KS = HD + 4;
-  constexpr int PAIRS = HD / 2;
-  constexpr int PV_GROUPS = kThreads / PAIRS;
-  constexpr int PV_RPT = (kRT + PV_GROUPS - 1) / PV_GROUPS;
-  constexpr int SC_GROUPS = kThreads / kSC;
-  constexpr int SC_RPT = kRT / SC_GROUPS;
-  float* Qs = (float*)lds_raw;        // [kRT][HD]
-  float* Ks = Qs + kRT * HD;          // [kSC][KS]
-  float* Vs = Ks + kSC * KS;          // [kSC][HD]
-  float* Ps = Vs + kSC * HD;          // [kRT][kSC]
-  float* m_s = Ps + kRT * kSC;        // [kRT]
-  float* l_s = m_s + kRT;
-  float* alpha_s = l_s + kRT;
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
+}
 
+template <int HD, int DT>
+__device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds) {
+  constexpr int NS = DT == PI_DTYPE_BF16 ? 1 : 2;  // bf16 terms per cache value
+  constexpr int ES = DT == PI_DTYPE_BF16 ? 2 : 4;
+  constexpr int KSTEPS = HD / 32;
+  constexpr int DTILES = HD / 16;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, l16 = lane & 15;
   const int G = A.n_q_heads / A.n_kv_heads;
   const int R = G * A.n;
   const int upH = A.attn_units_per_head;
   const bool has_window = u == upH - 1;
   const int p_begin = min(A.prefix_len, u * A.attn_chunk);
   const int p_end = min(A.prefix_len, p_begin + A.attn_chunk);
-  const int n_psub = (p_end - p_begin + kSC - 1) / kSC;
-  const int w_end = min(A.window_base + PI_WINDOW, A.n_cells);
-  const int n_wsub = has_window ? (w_end - A.window_base + kSC - 1) / kSC : 0;
+  const int npc = p_end - p_begin;
+  uint64_t any = 0;
+  for (int i = 0; i < A.n; ++i) any |= A.mask[i];
+  const int wcells = has_window ? min(64 - (int)__builtin_clzll(any | 1ull), A.n_cells - A.window_base) : 0;
+  const int cells = npc + wcells;
+  const int CP = (cells + 31) & ~31;
+  const AttnLds L = attn_lds_layout(HD, CP, NS);
   const float scale = 1.0f / sqrtf((float)HD);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const size_t head_base = (size_t)h * A.n_cells * HD;
+  const size_t head_elems = (size_t)h * A.n_cells * HD;
 
-  for (int r0 = 0; r0 < R; r0 += kRT) {
-    const int rows = min(kRT, R - r0);
-    __syncthreads();
-    for (int e = tid; e < kRT * (HD / 4); e += kThreads) {
-      const int rr = e / (HD / 4), d4 = e % (HD / 4);
-      float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (rr < rows) {
-        const int r = r0 + rr, gq = r / A.n, i = r % A.n;
-        const float* pq = A.q + ((size_t)i * A.n_q_heads + h * G + gq) * HD + d4 * 4;
-        qv = make_float4(ld_ag(pq) * scale, ld_ag(pq + 1) * scale, ld_ag(pq + 2) * scale, ld_ag(pq + 3) * scale);
-      }
-      *(float4*)(Qs + rr * HD + d4 * 4) = qv;
-    }
-    if (tid < kRT) { m_s[tid] = -INFINITY; l_s[tid] = 0.0f; }
-    float acc[PV_RPT][2];
+  __syncthreads();  // LDS of the previous unit / phase is free
+  // ---- stage K rows and V columns (as bf16 terms) ----
+  {
+    const __amdgpu_buffer_rsrc_t kr = rsrc_of(kl), vr = rsrc_of(vl);
+    const int items = CP * (HD / 8);
+    for (int it0 = 0; it0 < items; it0 += kThreads * 2) {
+      u32x4 kraw[2][2], vraw[2][2];
+      int lc[2], d8[2];
+      bool live[2];
 #pragma unroll
-    for (int j = 0; j < PV_RPT; ++j) acc[j][0] = acc[j][1] = 0.0f;
-
-    for (int sc = 0; sc < n_psub + n_wsub; ++sc) {
-      const bool window = sc >= n_psub;
-      const int c0 = window ? A.window_base + (sc - n_psub) * kSC : p_begin + sc * kSC;
-      const int cend = window ? w_end : p_end;
-      const int ncell = min(kSC, cend - c0);
-      if (window) {  // skip window sub-chunks no query of this run can see
-        uint64_t any = 0;
-        for (int i = 0; i < A.n; ++i) any |= A.mask[i];
-        const int sh = c0 - A.window_base;
-        if (((any >> sh) & 0xffffffffull) == 0) continue;
-      }
-      __syncthreads();
-      for (int e = tid; e < kSC * (HD / 8); e += kThreads) {
-        const int cc = e / (HD / 8), d8 = (e % (HD / 8)) * 8;
-        float kv[8], vv[8];
-        if (cc < ncell) {
-          const size_t idx = head_base + (size_t)(c0 + cc) * HD + d8;
-          ld_cache8(kl, A.kv_dtype, idx, window, kv);
-          ld_cache8(vl, A.kv_dtype, idx, window, vv);
-        } else {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) kv[j] = vv[j] = 0.0f;
-        }
-        *(float4*)(Ks + cc * KS + d8) = make_float4(kv[0], kv[1], kv[2], kv[3]);
-        *(float4*)(Ks + cc * KS + d8 + 4) = make_float4(kv[4], kv[5], kv[6], kv[7]);
-        *(float4*)(Vs + cc * HD + d8) = make_float4(vv[0], vv[1], vv[2], vv[3]);
-        *(float4*)(Vs + cc * HD + d8 + 4) = make_float4(vv[4], vv[5], vv[6], vv[7]);
-      }
-      __syncthreads();
-      {  // scores: thread = (cell, row group)
-        const int cc = tid % kSC, rg = tid / kSC;
-        float s[SC_RPT];
-#pragma unroll
-        for (int j = 0; j < SC_RPT; ++j) s[j] = 0.0f;
-        for (int d = 0; d < HD; d += 4) {
-          const float4 kk = *(const float4*)(Ks + cc * KS + d);
-#pragma unroll
-          for (int j = 0; j < SC_RPT; ++j) {
-            const float4 qq = *(const float4*)(Qs + (rg + SC_GROUPS * j) * HD + d);
-            s[j] += qq.x * kk.x + qq.y * kk.y + qq.z * kk.z + qq.w * kk.w;
+      for (int q = 0; q < 2; ++q) {
+        const int it = it0 + q * kThreads + tid;
+        lc[q] = it / (HD / 8);
+        d8[q] = (it % (HD / 8)) * 8;
+        live[q] = it < items && lc[q] < cells;
+        if (live[q]) {
+          const bool win = lc[q] >= npc;
+          const int cell = win ? A.window_base + (lc[q] - npc) : p_begin + lc[q];
+          const int off = (int)((head_elems + (size_t)cell * HD + d8[q]) * ES);
+          const int aux = win ? kAgent : 0;
+          if (win) {
+            kraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(kr, off, 0, kAgent);
+            vraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(vr, off, 0, kAgent);
+            if (NS == 2) {
+              kraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(kr, off + 16, 0, kAgent);
+              vraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(vr, off + 16, 0, kAgent);
+            }
+          } else {
+            kraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(kr, off, 0, 0);
+            vraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(vr, off, 0, 0);
+            if (NS == 2) {
+              kraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(kr, off + 16, 0, 0);
+              vraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(vr, off + 16, 0, 0);
+            }
           }
-        }
-#pragma unroll
-        for (int j = 0; j < SC_RPT; ++j) {
-          const int rr = rg + SC_GROUPS * j;
-          bool vis = cc < ncell && rr < rows;
-          if (vis && window) {
-            const int i = (r0 + rr) % A.n;
-            vis = (A.mask[i] >> (c0 + cc - A.window_base)) & 1ull;
-          }
-          Ps[rr * kSC + cc] = vis ? s[j] : -INFINITY;
+          (void)aux;
         }
       }
-      __syncthreads();
-      for (int rr = wave; rr < kRT; rr += kWaves) {  // running softmax, one wave per row
-        const float sv = lane < kSC ? Ps[rr * kSC + lane] : -INFINITY;
-        float mx = sv;
 #pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        const float m_old = m_s[rr];
-        const float m_new = fmaxf(m_old, mx);
-        const float p = (sv == -INFINITY) ? 0.0f : expf(sv - m_new);
-        float sum = p;
+      for (int q = 0; q < 2; ++q) {
+        const int it = it0 + q * kThreads + tid;
+        if (it >= items) continue;
+        uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, vw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        if (live[q]) {
+          if (NS == 1) {
 #pragma unroll
-        for (int o = 16; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-        const float alpha = (m_old == -INFINITY) ? 0.0f : expf(m_old - m_new);
-        if (lane < kSC) Ps[rr * kSC + lane] = p;
-        if (lane == 0) {
-          m_s[rr] = m_new;
-          l_s[rr] = l_s[rr] * alpha + sum;
-          alpha_s[rr] = alpha;
-        }
-      }
-      __syncthreads();
-      {  // O += P V : thread = (pair of head dims, row group)
-        const int dp = tid % PAIRS, rg = tid / PAIRS;
+            for (int j = 0; j < 4; ++j) { kw[0][j] = kraw[q][0][j]; vw[0][j] = vraw[q][0][j]; }
+          } else {
 #pragma unroll
-        for (int j = 0; j < PV_RPT; ++j) {
-          const int rr = rg + PV_GROUPS * j;
-          const float al = rr < kRT ? alpha_s[rr] : 0.0f;
-          acc[j][0] *= al;
-          acc[j][1] *= al;
-        }
-        for (int cc = 0; cc < kSC; cc += 4) {
-          float2 v[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = *(const float2*)(Vs + (cc + q) * HD + 2 * dp);
-#pragma unroll
-          for (int j = 0; j < PV_RPT; ++j) {
-            const int rr = rg + PV_GROUPS * j;
-            if (rr < kRT) {
-              const float4 p = *(const float4*)(Ps + rr * kSC + cc);
-              acc[j][0] += p.x * v[0].x + p.y * v[1].x + p.z * v[2].x + p.w * v[3].x;
-              acc[j][1] += p.x * v[0].y + p.y * v[1].y + p.z * v[2].y + p.w * v[3].y;
+            for (int j = 0; j < 4; ++j) {
+              const float k0 = __uint_as_float(kraw[q][j >> 1][(2 * j) & 3]), k1 = __uint_as_float(kraw[q][j >> 1][(2 * j + 1) & 3]);
+              const float v0 = __uint_as_float(vraw[q][j >> 1][(2 * j) & 3]), v1 = __uint_as_float(vraw[q][j >> 1][(2 * j + 1) & 3]);
+              kw[0][j] = pack_bf16(k0, k1);
+              vw[0][j] = pack_bf16(v0, v1);
+              kw[1][j] = pack_bf16(k0 - bf16_to_f32((uint16_t)kw[0][j]), k1 - bf16_to_f32((uint16_t)(kw[0][j] >> 16)));
+              vw[1][j] = pack_bf16(v0 - bf16_to_f32((uint16_t)vw[0][j]), v1 - bf16_to_f32((uint16_t)(vw[0][j] >> 16)));
             }
           }
         }
-      }
-    }
-    __syncthreads();
-    {  // park this unit's partial result for the row tile
-      const int dp = tid % PAIRS, rg = tid / PAIRS;
-      const size_t ubase = ((size_t)h * upH + u) * R;
 #pragma unroll
-      for (int j = 0; j < PV_RPT; ++j) {
-        const int rr = rg + PV_GROUPS * j;
-        if (rr < rows) {
-          float* po = A.attn_o + (ubase + r0 + rr) * HD + 2 * dp;
-          st_ag(po, acc[j][0]);
-          st_ag(po + 1, acc[j][1]);
+        for (int s = 0; s < NS; ++s) {
+          *(uint4*)(lds + L.k_off[s] + lc[q] * L.kstride + d8[q] * 2) = make_uint4(kw[s][0], kw[s][1], kw[s][2], kw[s][3]);
+          uint16_t* vt = (uint16_t*)(lds + L.v_off[s]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            vt[(d8[q] + 2 * j) * (L.vstride / 2) + lc[q]] = (uint16_t)vw[s][j];
+            vt[(d8[q] + 2 * j + 1) * (L.vstride / 2) + lc[q]] = (uint16_t)(vw[s][j] >> 16);
+          }
         }
       }
-      if (tid < rows) {
-        st_ag(A.attn_ml + (ubase + r0 + tid) * 2, m_s[tid]);
-        st_ag(A.attn_ml + (ubase + r0 + tid) * 2 + 1, l_s[tid]);
+    }
+  }
+  const int n_ct = CP / 16;  // cell tiles
+  float* rowmax = (float*)(lds + L.max_off);
+  float* rowsum = (float*)(lds + L.sum_off);
+  const size_t ubase = ((size_t)h * upH + u) * R;
+  const __amdgpu_buffer_rsrc_t qr = rsrc_of(A.q), por = rsrc_of(A.attn_o);
+
+  for (int r0 = 0; r0 < R; r0 += kRG) {
+    const int rows = min(kRG, R - r0);
+    __syncthreads();
+    // ---- stage the query rows as bf16 hi + lo ----
+    for (int it = tid; it < kRG * (HD / 4); it += kThreads) {
+      const int rr = it / (HD / 4), d4 = (it % (HD / 4)) * 4;
+      f32x4 qv = {0.f, 0.f, 0.f, 0.f};
+      if (rr < rows) {
+        const int r = r0 + rr, gq = r / A.n, i = r % A.n;
+        qv = ld_ag4(qr, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4);
       }
+      const uint32_t h0 = pack_bf16(qv[0], qv[1]), h1 = pack_bf16(qv[2], qv[3]);
+      const uint32_t l0 = pack_bf16(qv[0] - bf16_to_f32((uint16_t)h0), qv[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
+      const uint32_t l1 = pack_bf16(qv[2] - bf16_to_f32((uint16_t)h1), qv[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
+      *(uint2*)(lds + L.q_off[0] + rr * L.kstride + d4 * 2) = make_uint2(h0, h1);
+      *(uint2*)(lds + L.q_off[1] + rr * L.kstride + d4 * 2) = make_uint2(l0, l1);
+    }
+    __syncthreads();
+    // ---- scores: this wave's cell tiles x both row tiles ----
+    f32x4 sacc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) sacc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const int ct = wave + a * kWaves;
+      if (ct < n_ct) {
+#pragma unroll
+        for (int j = 0; j < KSTEPS; ++j) {
+          bf16x8 kop[NS];
+#pragma unroll
+          for (int s = 0; s < NS; ++s)
+            kop[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.k_off[s] + (ct * 16 + l16) * L.kstride + j * 64 + g * 16));
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const bf16x8 qh = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.q_off[0] + (b * 16 + l16) * L.kstride + j * 64 + g * 16));
+            const bf16x8 ql = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.q_off[1] + (b * 16 + l16) * L.kstride + j * 64 + g * 16));
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0], qh, sacc[a][b], 0, 0, 0);
+            sacc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[0], ql, sacc[a][b], 0, 0, 0);
+            if (NS == 2) sacc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[NS - 1], qh, sacc[a][b], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // scale, mask, per-wave row maxima.  Lane (l16, g) holds cells ct*16 + 4g + 0..3 of row b*16 + l16.
+    float wmax[2] = {-INFINITY, -INFINITY};
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int rr = b * 16 + l16;
+      const bool row_live = rr < rows;
+      const uint64_t mword = row_live ? A.mask[(r0 + rr) % A.n] : 0ull;
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int ct = wave + a * kWaves;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lc = ct * 16 + 4 * g + q;
+          bool vis = row_live && ct < n_ct && lc < cells;
+          if (vis && lc >= npc) vis = (mword >> (lc - npc)) & 1ull;
+          const float sv = vis ? sacc[a][b][q] * scale : -INFINITY;
+          sacc[a][b][q] = sv;
+          wmax[b] = fmaxf(wmax[b], sv);
+        }
+      }
+      wmax[b] = fmaxf(wmax[b], __shfl_xor(wmax[b], 16));
+      wmax[b] = fmaxf(wmax[b], __shfl_xor(wmax[b], 32));
+      if (g == 0) rowmax[wave * kRG + rr] = wmax[b];
+    }
+    __syncthreads();
+    float M[2], wsum[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int rr = b * 16 + l16;
+      float m = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) m = fmaxf(m, rowmax[w * kRG + rr]);
+      M[b] = m;
+      wsum[b] = 0.0f;
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int ct = wave + a * kWaves;
+        if (ct < n_ct) {
+          float p[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            p[q] = sacc[a][b][q] == -INFINITY ? 0.0f : expf(sacc[a][b][q] - m);
+            wsum[b] += p[q];
+          }
+          const uint32_t h0 = pack_bf16(p[0], p[1]), h1 = pack_bf16(p[2], p[3]);
+          const uint32_t l0 = pack_bf16(p[0] - bf16_to_f32((uint16_t)h0), p[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
+          const uint32_t l1 = pack_bf16(p[2] - bf16_to_f32((uint16_t)h1), p[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
+          *(uint2*)(lds + L.p_off[0] + rr * L.vstride + (ct * 16 + 4 * g) * 2) = make_uint2(h0, h1);
+          *(uint2*)(lds + L.p_off[1] + rr * L.vstride + (ct * 16 + 4 * g) * 2) = make_uint2(l0, l1);
+        }
+      }
+      wsum[b] += __shfl_xor(wsum[b], 16);
+      wsum[b] += __shfl_xor(wsum[b], 32);
+      if (g == 0) rowsum[wave * kRG + rr] = wsum[b];
+    }
+    __syncthreads();
+    // ---- O = P V : wave w owns head-dim tile w ----
+    if (wave < DTILES) {
+      f32x4 oacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+      for (int cpair = 0; cpair < CP / 32; ++cpair) {
+        bf16x8 vop[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+          vop[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.v_off[s] + (wave * 16 + l16) * L.vstride + (cpair * 32 + 8 * g) * 2));
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const bf16x8 ph = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.p_off[0] + (b * 16 + l16) * L.vstride + (cpair * 32 + 8 * g) * 2));
+          const bf16x8 pl = __builtin_bit_cast(bf16x8, *(const u32x4*)(lds + L.p_off[1] + (b * 16 + l16) * L.vstride + (cpair * 32 + 8 * g) * 2));
+          oacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[0], ph, oacc[b], 0, 0, 0);
+          oacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[0], pl, oacc[b], 0, 0, 0);
+          if (NS == 2) oacc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[NS - 1], ph, oacc[b], 0, 0, 0);
+        }
+      }
+      // lane (l16, g) holds O[row b*16 + l16][d = wave*16 + 4g + 0..3]
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int rr = b * 16 + l16;
+        if (rr < rows) st_ag4(por, (int)(((ubase + r0 + rr) * HD + wave * 16 + 4 * g) * 4), oacc[b]);
+      }
+    }
+    if (tid < rows) {
+      float m = -INFINITY, sum = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) m = fmaxf(m, rowmax[w * kRG + tid]);
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) sum += rowsum[w * kRG + tid];
+      st_ag(A.attn_ml + (ubase + r0 + tid) * 2, m);
+      st_ag(A.attn_ml + (ubase + r0 + tid) * 2 + 1, sum);
     }
   }
   // arrival count of this kv head; the last unit merges all units of the head, in unit order
   wave_drain();
   __syncthreads();
-  int* flag = (int*)(alpha_s + kRT);
+  int* flag = (int*)(lds + L.flag_off);
   if (tid == 0) {
     const int old = __hip_atomic_fetch_add(A.attn_cnt + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     *flag = old == upH - 1;
@@ -735,33 +825,37 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
   }
   __syncthreads();
   if (*flag) {
-    for (int e = tid; e < R * HD; e += kThreads) {
-      const int r = e / HD, d = e % HD;
+    const __amdgpu_buffer_rsrc_t oor = rsrc_of(A.o);
+    for (int e = tid; e < R * (HD / 4); e += kThreads) {
+      const int r = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
       const size_t hb = (size_t)h * upH;
-      float M = -INFINITY;
-      for (int uu = 0; uu < upH; ++uu) M = fmaxf(M, ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2));
-      float L = 0.0f, o = 0.0f;
+      float Mx = -INFINITY;
+      for (int uu = 0; uu < upH; ++uu) Mx = fmaxf(Mx, ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2));
+      float Ls = 0.0f;
+      f32x4 o = {0.f, 0.f, 0.f, 0.f};
       for (int uu = 0; uu < upH; ++uu) {
         const float m = ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2);
         if (m == -INFINITY) continue;
-        const float w = expf(m - M);
-        L += w * ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2 + 1);
-        o += w * ld_ag(A.attn_o + ((hb + uu) * R + r) * HD + d);
+        const float w = expf(m - Mx);
+        Ls += w * ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2 + 1);
+        o += w * ld_ag4(por, (int)((((hb + uu) * R + r) * HD + d4) * 4));
       }
       const int gq = r / A.n, i = r % A.n;
-      st_ag(A.o + ((size_t)i * A.n_q_heads + h * G + gq) * HD + d, o / L);
+      const float inv = 1.0f / Ls;
+      st_ag4(oor, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4, o * inv);
     }
   }
 }
 
+template <int DT>
 __device__ void attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds) {
   const int units = A.n_kv_heads * A.attn_units_per_head;
   for (int w = blockIdx.x; w < units; w += gridDim.x) {
     const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
     switch (A.head_dim) {
-      case 32: attn_unit<32>(A, kl, vl, h, u, lds); break;
-      case 64: attn_unit<64>(A, kl, vl, h, u, lds); break;
-      default: attn_unit<128>(A, kl, vl, h, u, lds); break;
+      case 32: attn_unit<32, DT>(A, kl, vl, h, u, lds); break;
+      case 64: attn_unit<64, DT>(A, kl, vl, h, u, lds); break;
+      default: attn_unit<128, DT>(A, kl, vl, h, u, lds); break;
     }
   }
 }
@@ -892,7 +986,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     proj_phase<DT, UR, EPI_QKV>(A, R, S, A.sk[0], A.x, W.attn_gain, true, A.d, e, lds, lane, nullptr, 0, wave);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
     // attention
-    attention_phase(A, e.kcache, e.vcache, lds);
+    attention_phase<DT>(A, e.kcache, e.vcache, lds);
     stream_init<DT>(S, W.o, A.sk[1], wave);
     ring_prefetch<DT, UR>(R, S, lane);
     if (!(ok = grid_barrier(A, bc, -1, false))) break;
@@ -961,9 +1055,9 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
 
 }  // namespace
 
-size_t attn_lds_bytes(int head_dim) {
-  return ((size_t)kRT * head_dim + (size_t)kSC * (head_dim + 4) + (size_t)kSC * head_dim + (size_t)kRT * kSC +
-          3 * kRT + 4) * sizeof(float);
+size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
+  const int cp = (max_unit_cells + 31) & ~31;
+  return (size_t)attn_lds_layout(head_dim, cp, dtype == PI_DTYPE_BF16 ? 1 : 2).total;
 }
 
 size_t stage_proj_lds_bytes(int n, int nt) { return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float); }

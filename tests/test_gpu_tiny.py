@@ -69,9 +69,10 @@ def test_planted_draft_verify_and_rollback(shape_name, gain_sigma):
     # cache contents agree (prefill itself is a parity test)
     for l in range(sh.n_layers):
         k, v = gkv.get_cells(l, 0, 64)
-        tol = 1e-5 if sh.dtype == "f32" else 2.0 ** -7
-        assert np.max(np.abs(k - okv.K[l, :64]) / (1e-3 + np.abs(okv.K[l, :64]))) < tol * 50
-        assert np.max(np.abs(v - okv.V[l, :64]) / (1e-3 + np.abs(okv.V[l, :64]))) < tol * 50
+        # fp32 cache: arithmetic error only; bf16 cache: at most one rounding step of a value of this size
+        tol = 5e-5 if sh.dtype == "f32" else 2.0 ** -7 * max(np.abs(okv.K[l, :64]).max(), np.abs(okv.V[l, :64]).max())
+        assert np.max(np.abs(k - okv.K[l, :64])) <= tol
+        assert np.max(np.abs(v - okv.V[l, :64])) <= tol
     root_expected = int(np.argmax(pre_o[-1]))
     d = np.zeros(4, dtype=np.int32)
     d[0] = root_expected
