@@ -53,7 +53,8 @@ struct pi_kv {
   int32_t* len_dev = nullptr;
   int* cnt = nullptr;
   float *attn_o = nullptr, *attn_ml = nullptr;
-  int* attn_cnt = nullptr;
+  unsigned* attn_flags = nullptr;
+  int attn_flag_stride = 0;
 };
 
 namespace {
@@ -436,8 +437,9 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
   if (e == hipSuccess) e = hipMalloc((void**)&kv->cnt, sizeof(int));
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_o, rows * kv->head_dim * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_ml, rows * 2 * sizeof(float));
-  if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_cnt, kv->n_kv_heads * sizeof(int));
-  if (e == hipSuccess) e = hipMemset(kv->attn_cnt, 0, kv->n_kv_heads * sizeof(int));
+  kv->attn_flag_stride = (int)max_units;
+  if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_flags, kv->n_kv_heads * max_units * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(kv->attn_flags, 0, kv->n_kv_heads * max_units * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(kv->k, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->v, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->len_dev, 0, sizeof(int32_t));
@@ -454,7 +456,7 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
 int32_t pi_kv_free(pi_kv* kv) {
   if (!kv) return PI_E_ARG;
   (void)hipDeviceSynchronize();
-  for (void* p : {kv->k, kv->v, (void*)kv->len_dev, (void*)kv->cnt, (void*)kv->attn_o, (void*)kv->attn_ml, (void*)kv->attn_cnt})
+  for (void* p : {kv->k, kv->v, (void*)kv->len_dev, (void*)kv->cnt, (void*)kv->attn_o, (void*)kv->attn_ml, (void*)kv->attn_flags})
     if (p) (void)hipFree(p);
   delete kv;
   return PI_OK;
@@ -644,7 +646,8 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.cnt = m->cnt;
   a.attn_o = kv->attn_o;
   a.attn_ml = kv->attn_ml;
-  a.attn_cnt = kv->attn_cnt;
+  a.attn_flags = kv->attn_flags;
+  a.attn_flag_stride = kv->attn_flag_stride;
   a.rs = m->rs;
   a.sync = m->sync;
   for (int ph = 0; ph < 5; ++ph) a.sk[ph] = sp.sk[ph];

@@ -107,7 +107,8 @@ struct StageArgs {
   int* cnt;      // [NRB] arrival counters, zero between phases
   float* attn_o;   // [Hkv][units][R][hd]
   float* attn_ml;  // [Hkv][units][R][2]
-  int* attn_cnt;   // [Hkv]
+  unsigned* attn_flags;  // [Hkv][attn_flag_stride]: barrier number at which a unit last published
+  int attn_flag_stride;
   RunState* rs;
   StageSync* sync;
   // work split

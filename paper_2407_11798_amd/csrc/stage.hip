@@ -65,7 +65,7 @@ __device__ __forceinline__ void st_ag2(__amdgpu_buffer_rsrc_t r, int byte_off, f
 // because they were issued with agent scope)
 __device__ __forceinline__ void wave_drain() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void wg_mark(const StageArgs& A, int l, int ev) {
-  if (A.wgtrace && l == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + ev] = wall_clock64();
+  if (A.wgtrace && l == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + ev] = wall_clock64();  // l: layer * 8 + phase kind
 }
 
 // ---- grid barrier ---------------------------------------------------------------------------
@@ -81,8 +81,9 @@ struct BarrierCtx {
 // wait ran into its time limit): callers then leave the kernel at once.  layers_done >= 0 marks
 // a layer boundary: workgroup 0 records progress, probes the cancel flag when `probe` is set
 // and publishes the decision, which every workgroup reads before going on.
-__device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe) {
+__device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
   __syncthreads();  // every wave of this workgroup has drained its stores
+  if (A.wgtrace && mark == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + 4] = wall_clock64();
   bc.epoch += 1;
   StageSync* sy = A.sync;
   if (threadIdx.x < 64) {
@@ -259,71 +260,104 @@ __device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, in
 // ---- activation staging (once per phase and workgroup) ---------------------------------------
 // LDS slot (tt, g, i) holds x[i][32(t0+tt) + 8g + 0..7] (times the gain): bf16 model: 16 B of hi
 // parts at the slot, 16 B of lo parts n_slots further; fp32 model: 32 B of floats.
+// Also computes 1/sqrt(mean x^2 + eps) per token (scaled phases) from the per-16-column partial
+// sums of squares, summed in a fixed order; its loads are issued together with the activation
+// loads so the whole staging costs one memory round trip.  Ends with a workgroup barrier.
 template <int DT>
-__device__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds) {
+__device__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
+                        const float* ssq, int n_blocks, float eps, float* red, float* rscale) {
   const int items = nt * n * 4;
   const int n_slots = nt * 4 * n;
   const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
-  for (int id = threadIdx.x; id < items; id += kThreads) {
-    const int cl = id & 3;
-    const int i = (id >> 2) % n;
-    const int tt = (id >> 2) / n;
-    const int k0 = (t0 + tt) * kKTile + cl * 8;
-    float v[8];
-    if (k0 < K) {
-      const int off = (i * K + k0) * 4;
-      const f32x4 p0 = ld_ag4(xr, off), p1 = ld_ag4(xr, off + 16);
+  constexpr int kGroups = kThreads / 16;
+  float ssum = 0.0f;
+  if (ssq) {
+    const int i = threadIdx.x & 15, b0 = threadIdx.x >> 4;
+    constexpr int kMaxPer = 16;  // up to 16 * 32 = 512 blocks of 16 columns (d_model <= 8192) in one batch
+    float part[kMaxPer];
+    const __amdgpu_buffer_rsrc_t sr = rsrc_of(ssq);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) { v[j] = p0[j]; v[4 + j] = p1[j]; }
-      if (gain) {
-        const f32x4 g0 = *(gptr_f32x4)(gain + k0);
-        const f32x4 g1 = *(gptr_f32x4)(gain + k0 + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { v[j] *= g0[j]; v[4 + j] *= g1[j]; }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+    for (int q = 0; q < kMaxPer; ++q) {  // plain (non-atomic) agent-scope loads: all in flight at once
+      const int b = min(b0 + q * kGroups, n_blocks - 1);
+      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, (b * 16 + i) * 4, 0, kAgent));
     }
-    const int slot = (tt * 4 + cl) * n + i;
-    if (DT == PI_DTYPE_BF16) {
-      uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint16_t h0 = f32_to_bf16_rne(v[2 * j]), h1 = f32_to_bf16_rne(v[2 * j + 1]);
-        const uint16_t l0 = f32_to_bf16_rne(v[2 * j] - bf16_to_f32(h0));
-        const uint16_t l1 = f32_to_bf16_rne(v[2 * j + 1] - bf16_to_f32(h1));
-        hi[j] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        lo[j] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    for (int q = 0; q < kMaxPer; ++q)
+      if (b0 + q * kGroups >= n_blocks) part[q] = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) ssum += part[q];
+    for (int b = b0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + i);
+  }
+  for (int id0 = 0; id0 < items; id0 += 2 * kThreads) {
+    f32x4 p[2][2];
+    int slot[2], k0[2];
+    bool in_k[2], in_items[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int id = id0 + q * kThreads + threadIdx.x;
+      const int cl = id & 3;
+      const int i = (id >> 2) % n;
+      const int tt = (id >> 2) / n;
+      k0[q] = (t0 + tt) * kKTile + cl * 8;
+      slot[q] = (tt * 4 + cl) * n + i;
+      in_items[q] = id < items;
+      in_k[q] = in_items[q] && k0[q] < K;
+      if (in_k[q]) {
+        const int off = (i * K + k0[q]) * 4;
+        p[q][0] = ld_ag4(xr, off);
+        p[q][1] = ld_ag4(xr, off + 16);
       }
-      ((uint4*)lds)[slot] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-      ((uint4*)lds)[slot + n_slots] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    } else {
-      ((float4*)lds)[2 * slot] = make_float4(v[0], v[1], v[2], v[3]);
-      ((float4*)lds)[2 * slot + 1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      if (!in_items[q]) continue;
+      float v[8];
+      if (in_k[q]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { v[j] = p[q][0][j]; v[4 + j] = p[q][1][j]; }
+        if (gain) {
+          const f32x4 g0 = *(gptr_f32x4)(gain + k0[q]);
+          const f32x4 g1 = *(gptr_f32x4)(gain + k0[q] + 4);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { v[j] *= g0[j]; v[4 + j] *= g1[j]; }
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+      }
+      if (DT == PI_DTYPE_BF16) {
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint16_t h0 = f32_to_bf16_rne(v[2 * j]), h1 = f32_to_bf16_rne(v[2 * j + 1]);
+          const uint16_t l0 = f32_to_bf16_rne(v[2 * j] - bf16_to_f32(h0));
+          const uint16_t l1 = f32_to_bf16_rne(v[2 * j + 1] - bf16_to_f32(h1));
+          hi[j] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          lo[j] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+        }
+        ((uint4*)lds)[slot[q]] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        ((uint4*)lds)[slot[q] + n_slots] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      } else {
+        ((float4*)lds)[2 * slot[q]] = make_float4(v[0], v[1], v[2], v[3]);
+        ((float4*)lds)[2 * slot[q] + 1] = make_float4(v[4], v[5], v[6], v[7]);
+      }
     }
   }
-}
-
-// 1/sqrt(mean x^2 + eps) per token from the per-16-column partial sums of squares, summed in a
-// fixed order.  red: kThreads floats of LDS, rscale: 16 floats of LDS.  Ends with a barrier.
-__device__ void compute_rscale(const float* ssq, int n_blocks, int K, float eps, float* red, float* rscale) {
-  const int i = threadIdx.x & 15, b0 = threadIdx.x >> 4;
-  constexpr int kGroups = kThreads / 16;
-  float s = 0.0f;
-  for (int b = b0; b < n_blocks; b += kGroups) s += ld_ag(ssq + b * 16 + i);
-  red[b0 * 16 + i] = s;
-  __syncthreads();
-  if (threadIdx.x < 16) {
-    float t = 0.0f;
-    for (int b = 0; b < kGroups; ++b) t += red[b * 16 + threadIdx.x];
-    rscale[threadIdx.x] = 1.0f / sqrtf(t / (float)K + eps);
+  if (ssq) {
+    red[threadIdx.x] = ssum;  // red[b0 * 16 + i]
+    __syncthreads();
+    if (threadIdx.x < 16) {
+      float t = 0.0f;
+      for (int b = 0; b < kGroups; ++b) t += red[b * 16 + threadIdx.x];
+      rscale[threadIdx.x] = 1.0f / sqrtf(t / (float)K + eps);
+    }
   }
   __syncthreads();
 }
 
 // ---- epilogues --------------------------------------------------------------------------------
 struct EpiCtx {
+  int epi;  // Epilogue kind
   int n;
   int N;               // logical rows of the matrix
   float* out;          // RESID: x[n][N] ; SWIGLU: a[n][N/2] ; LOGITS: logits[n][N] ; QKV: q[n][n_q_rows]
@@ -349,8 +383,8 @@ __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem
 }
 
 // The accumulator tile of a wave: lane l holds rows 16rb + 4(l>>4) + 0..3 for token l & 15.
-template <int EPI>
 __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int lane, const float* rscale) {
+  const int EPI = e.epi;
   const int i = lane & 15, g = lane >> 4;
   const int row = rb * kRowBlock + g * 4;
   const bool live = i < e.n;
@@ -404,7 +438,6 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
 // One wave has finished its part of row block rb (slice S.slice).  If other waves contribute to
 // the row block, park the partial tile and count arrivals; the last arriver adds all partial
 // tiles in a fixed order (slice-major, then wave order) and runs the epilogue.
-template <int EPI>
 __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
                                                f32x4 acc, int lane, const EpiCtx& e, const float* rscale) {
   const int first = uni((rb * S.nt) / S.share);
@@ -431,7 +464,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
     }
     if (lane == 0) __hip_atomic_store(A.cnt + rb, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  epilogue<EPI>(e, rb, acc, lane, rscale);
+  epilogue(e, rb, acc, lane, rscale);
 }
 
 // ---- the MFMA inner step ----------------------------------------------------------------------
@@ -490,7 +523,7 @@ __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, Con
 }
 
 // Stream this wave's range of the phase; the ring already holds its first tiles.
-template <int DT, int UR, int EPI>
+template <int DT, int UR>
 __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                               const char* lds, int n, int lane, const EpiCtx& e,
                                               const float* rscale, const MatDev* next, int next_sk, int wave) {
@@ -507,7 +540,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
       consume_step<DT, UR, 0>(R, S, C, lds, n, lane);
     } while (!C.pending && C.f < S.f1);
     if (C.pending) {
-      flush_rowblock<EPI>(A, S, S_k, C.prb, C.pacc, lane, e, rscale);
+      flush_rowblock(A, S, S_k, C.prb, C.pacc, lane, e, rscale);
       C.pending = false;
     }
   }
@@ -518,7 +551,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     stream_init<DT>(Sn, *next, next_sk, wave);
     ring_prefetch<DT, UR>(R, Sn, lane);
   }
-  if (C.t > 0) flush_rowblock<EPI>(A, S, S_k, C.rb, C.acc, lane, e, rscale);  // range ends inside a row block
+  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale);  // range ends inside a row block
   S = Sn;
 }
 
@@ -577,7 +610,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 template <int HD, int DT>
-__device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds) {
+__device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds, unsigned tag) {
   constexpr int NS = DT == PI_DTYPE_BF16 ? 1 : 2;  // bf16 terms per cache value
   constexpr int ES = DT == PI_DTYPE_BF16 ? 2 : 4;
   constexpr int KSTEPS = HD / 32;
@@ -814,50 +847,104 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
       st_ag(A.attn_ml + (ubase + r0 + tid) * 2 + 1, sum);
     }
   }
-  // arrival count of this kv head; the last unit merges all units of the head, in unit order
+  // publish: this unit's partial results are in memory
   wave_drain();
   __syncthreads();
-  int* flag = (int*)(lds + L.flag_off);
-  if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(A.attn_cnt + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *flag = old == upH - 1;
-    if (old == upH - 1) __hip_atomic_store(A.attn_cnt + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  __syncthreads();
-  if (*flag) {
-    const __amdgpu_buffer_rsrc_t oor = rsrc_of(A.o);
-    for (int e = tid; e < R * (HD / 4); e += kThreads) {
-      const int r = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
-      const size_t hb = (size_t)h * upH;
-      float Mx = -INFINITY;
-      for (int uu = 0; uu < upH; ++uu) Mx = fmaxf(Mx, ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2));
-      float Ls = 0.0f;
-      f32x4 o = {0.f, 0.f, 0.f, 0.f};
-      for (int uu = 0; uu < upH; ++uu) {
-        const float m = ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2);
-        if (m == -INFINITY) continue;
-        const float w = expf(m - Mx);
-        Ls += w * ld_ag(A.attn_ml + ((hb + uu) * R + r) * 2 + 1);
-        o += w * ld_ag4(por, (int)((((hb + uu) * R + r) * HD + d4) * 4));
-      }
-      const int gq = r / A.n, i = r % A.n;
-      const float inv = 1.0f / Ls;
-      st_ag4(oor, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4, o * inv);
-    }
-  }
+  if (tid == 0) __hip_atomic_store(A.attn_flags + h * A.attn_flag_stride + u, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Merge step of unit (h, u): wait (bounded) until every unit of kv head h has published, then
+// combine the units, in unit order, for this unit's share of the head's query rows.
+template <int HD>
+__device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* sh) {
+  const int tid = threadIdx.x;
+  const int G = A.n_q_heads / A.n_kv_heads;
+  const int R = G * A.n;
+  const int upH = A.attn_units_per_head;
+  if (u >= R) return true;  // no row for this unit
+  if (tid < 64) {
+    const unsigned long long t0 = wall_clock64();
+    int ok = 1;
+    for (unsigned spin = 0;; ++spin) {
+      bool all = true;
+      for (int b = tid; b < upH; b += 64) {
+        const unsigned f = __hip_atomic_load(A.attn_flags + h * A.attn_flag_stride + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        all = all && (int)(f - tag) >= 0;
+      }
+      if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
+      __builtin_amdgcn_s_sleep(1);
+      if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+        ok = 0;
+        break;
+      }
+    }
+    if (tid == 0) {
+      if (!ok) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sh[0] = ok;
+    }
+  }
+  __syncthreads();
+  if (!__builtin_amdgcn_readfirstlane(sh[0])) return false;
+  const __amdgpu_buffer_rsrc_t oor = rsrc_of(A.o), por = rsrc_of(A.attn_o), mlr = rsrc_of(A.attn_ml);
+  const int my_rows = (R - u + upH - 1) / upH;
+  for (int e = tid; e < my_rows * (HD / 4); e += kThreads) {
+    const int r = u + (e / (HD / 4)) * upH, d4 = (e % (HD / 4)) * 4;
+    const int hb = h * upH;
+    // running merge in unit order, eight units' loads in flight at a time
+    float Mx = -INFINITY, Ls = 0.0f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int u0 = 0; u0 < upH; u0 += 8) {
+      u32x2 ml[8];
+      f32x4 po[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int uu = min(u0 + q, upH - 1);
+        ml[q] = __builtin_amdgcn_raw_buffer_load_b64(mlr, (int)(((hb + uu) * R + r) * 8), 0, kAgent);
+        po[q] = ld_ag4(por, (int)((((hb + uu) * R + r) * HD + d4) * 4));
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (u0 + q >= upH) continue;
+        const float m = __uint_as_float(ml[q][0]), l = __uint_as_float(ml[q][1]);
+        if (m == -INFINITY) continue;
+        const float mn = fmaxf(Mx, m);
+        const float a = Mx == -INFINITY ? 0.0f : expf(Mx - mn), b = expf(m - mn);
+        Ls = Ls * a + l * b;
+        o = o * a + po[q] * b;
+        Mx = mn;
+      }
+    }
+    const int gq = r / A.n, i = r % A.n;
+    const float inv = 1.0f / Ls;
+    st_ag4(oor, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4, o * inv);
+  }
+  return true;
+}
+
+// All units first, then all merges: a workgroup never waits while it still owes a unit, so the
+// waits in the merge step cannot deadlock even when a workgroup serves several units.
 template <int DT>
-__device__ void attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds) {
+__device__ bool attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds, unsigned tag, int* sh) {
   const int units = A.n_kv_heads * A.attn_units_per_head;
   for (int w = blockIdx.x; w < units; w += gridDim.x) {
     const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
     switch (A.head_dim) {
-      case 32: attn_unit<32, DT>(A, kl, vl, h, u, lds); break;
-      case 64: attn_unit<64, DT>(A, kl, vl, h, u, lds); break;
-      default: attn_unit<128, DT>(A, kl, vl, h, u, lds); break;
+      case 32: attn_unit<32, DT>(A, kl, vl, h, u, lds, tag); break;
+      case 64: attn_unit<64, DT>(A, kl, vl, h, u, lds, tag); break;
+      default: attn_unit<128, DT>(A, kl, vl, h, u, lds, tag); break;
     }
   }
+  bool ok = true;
+  for (int w = blockIdx.x; ok && w < units; w += gridDim.x) {
+    const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
+    switch (A.head_dim) {
+      case 32: ok = attn_merge<32>(A, h, u, tag, sh); break;
+      case 64: ok = attn_merge<64>(A, h, u, tag, sh); break;
+      default: ok = attn_merge<128>(A, h, u, tag, sh); break;
+    }
+  }
+  wave_drain();
+  return ok;
 }
 
 // ---- stage input / output ---------------------------------------------------------------------
@@ -903,7 +990,7 @@ __device__ void hidden_out_phase(const StageArgs& A) {
 }
 
 // ---- one projection phase: stage activations, stream, flush ----------------------------------------
-template <int DT, int UR, int EPI>
+template <int DT, int UR>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                            const float* xin, const float* gain, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int lane, const MatDev* next, int next_sk,
@@ -911,14 +998,9 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   const size_t xbytes = (size_t)S.nt * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
-  stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds);
-  if (scaled) {
-    compute_rscale(A.ssq, A.d / 16, K, A.eps, red, rscale);
-  } else {
-    __syncthreads();
-  }
+  stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
-  consume_phase<DT, UR, EPI>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);
   wg_mark(A, trace_layer, 2);
   wave_drain();
 }
@@ -965,8 +1047,26 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     ring_prefetch<DT, UR>(R, S, lane);
     ok = grid_barrier(A, bc, -1, false);
   }
-  for (int l = A.layer_begin; ok && !dead && l < A.layer_end; ++l) {
-    const LayerDev W = uni_layer(A.layers[l]);
+  // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
+  // O, gate/up, down), phase 1 is attention, and a final pass after the last layer is the LM
+  // head.  A single copy of the projection code serves all of them.
+  const int n_ph = (A.layer_end - A.layer_begin) * 5 + (A.layer_end == L ? 1 : 0);
+  for (int ph = 0; ok && !dead && ph < n_ph; ++ph) {
+    const int l = A.layer_begin + ph / 5;
+    const int k = l < A.layer_end ? ph % 5 : 5;  // 5: LM head
+    if (k == 1) {
+      wg_mark(A, l * 8 + 1, 0);
+      if (!(ok = attention_phase<DT>(A, A.kbase + (size_t)l * A.kv_layer_bytes, A.vbase + (size_t)l * A.kv_layer_bytes, lds,
+                                     bc.epoch + 1, bar_sh)))
+        break;
+      wg_mark(A, l * 8 + 1, 2);
+      stream_init<DT>(S, uni_mat(A.layers[l].o), A.sk[1], wave);
+      ring_prefetch<DT, UR>(R, S, lane);
+      wg_mark(A, l * 8 + 1, 3);
+      if (!(ok = grid_barrier(A, bc, -1, false, l * 8 + 1))) break;
+      wg_mark(A, l * 8 + 1, 5);
+      continue;
+    }
     EpiCtx e;
     e.n = A.n;
     e.n_q_rows = A.n_q_heads * A.head_dim;
@@ -980,62 +1080,47 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.slots = A.slots;
     e.rope = A.rope;
     e.ssq_out = A.ssq;
-    // RMSNorm + QKV projection + RoPE + KV write
-    e.N = W.qkv.N;
-    e.out = A.q;
-    proj_phase<DT, UR, EPI_QKV>(A, R, S, A.sk[0], A.x, W.attn_gain, true, A.d, e, lds, lane, nullptr, 0, wave);
-    if (!(ok = grid_barrier(A, bc, -1, false))) break;
-    // attention
-    attention_phase<DT>(A, e.kcache, e.vcache, lds);
-    stream_init<DT>(S, W.o, A.sk[1], wave);
-    ring_prefetch<DT, UR>(R, S, lane);
-    if (!(ok = grid_barrier(A, bc, -1, false))) break;
-    // output projection + residual
-    e.N = W.o.N;
-    e.out = A.x;
-    proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[1], A.o, nullptr, false, W.o.K, e, lds, lane, &W.gateup, A.sk[2],
-                                  wave);
-    if (!(ok = grid_barrier(A, bc, -1, false))) break;
-    // RMSNorm + gate/up + SwiGLU
-    e.N = W.gateup.N;
-    e.out = A.a;
-    wg_mark(A, l, 0);
-    proj_phase<DT, UR, EPI_SWIGLU>(A, R, S, A.sk[2], A.x, W.ffn_gain, true, A.d, e, lds, lane, &W.down, A.sk[3],
-                                   wave, l);
-    wg_mark(A, l, 3);
-    wg_mark(A, l, 4);
-    if (!(ok = grid_barrier(A, bc, -1, false))) break;
-    wg_mark(A, l, 5);
-    // down projection + residual
-    e.N = W.down.N;
-    e.out = A.x;
-    {
-      MatDev nxt = A.lm_head;
-      int nsk = A.sk[4];
-      bool has_next = A.layer_end == L;
-      if (l + 1 < A.layer_end) {
-        nxt = uni_mat(A.layers[l + 1].qkv);
-        nsk = A.sk[0];
-        has_next = true;
-      }
-      proj_phase<DT, UR, EPI_RESID>(A, R, S, A.sk[3], A.a, nullptr, false, W.down.K, e, lds, lane,
-                                    has_next ? &nxt : nullptr, nsk, wave);
-    }
-    // layer boundary: record progress; probe the cancel flag unless the stage is complete
-    if (!(ok = grid_barrier(A, bc, l + 1, l + 1 < A.layer_end))) break;
-    dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
-  }
-  if (ok && !dead) {
-    if (A.layer_end == L) {  // final RMSNorm + LM head
-      EpiCtx e;
-      e.n = A.n;
-      e.N = A.lm_head.N;
-      e.out = A.logits_out;
-      proj_phase<DT, UR, EPI_LOGITS>(A, R, S, A.sk[4], A.x, A.final_gain, true, A.d, e, lds, lane, nullptr, 0, wave);
+    MatDev M, nxt;
+    const float* xin;
+    const float* gain = nullptr;
+    bool scaled = false, has_next = true;
+    int sk, nsk = 1;
+    if (k == 5) {  // final RMSNorm + LM head
+      M = A.lm_head; sk = A.sk[4]; xin = A.x; gain = A.final_gain; scaled = true;
+      e.epi = EPI_LOGITS; e.out = A.logits_out; has_next = false; nxt = M;
     } else {
-      hidden_out_phase(A);
+      const LayerDev W = uni_layer(A.layers[l]);
+      if (k == 0) {  // RMSNorm + QKV projection + RoPE + KV write
+        M = W.qkv; sk = A.sk[0]; xin = A.x; gain = W.attn_gain; scaled = true;
+        e.epi = EPI_QKV; e.out = A.q; has_next = false; nxt = M;
+      } else if (k == 2) {  // output projection + residual
+        M = W.o; sk = A.sk[1]; xin = A.o; e.epi = EPI_RESID; e.out = A.x; nxt = W.gateup; nsk = A.sk[2];
+      } else if (k == 3) {  // RMSNorm + gate/up + SwiGLU
+        M = W.gateup; sk = A.sk[2]; xin = A.x; gain = W.ffn_gain; scaled = true;
+        e.epi = EPI_SWIGLU; e.out = A.a; nxt = W.down; nsk = A.sk[3];
+      } else {  // down projection + residual; then the next layer's QKV or the LM head
+        M = W.down; sk = A.sk[3]; xin = A.a; e.epi = EPI_RESID; e.out = A.x;
+        if (l + 1 < A.layer_end) {
+          nxt = uni_mat(A.layers[l + 1].qkv); nsk = A.sk[0];
+        } else if (A.layer_end == L) {
+          nxt = A.lm_head; nsk = A.sk[4];
+        } else {
+          has_next = false; nxt = M;
+        }
+      }
     }
+    e.N = M.N;
+    wg_mark(A, l * 8 + k, 0);
+    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, lane, has_next ? &nxt : nullptr, nsk, wave,
+                       l * 8 + k);
+    wg_mark(A, l * 8 + k, 3);
+    if (k == 5) break;
+    const bool boundary = k == 4;
+    if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
+    wg_mark(A, l * 8 + k, 5);
+    if (boundary) dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
   }
+  if (ok && !dead && A.layer_end < L) hidden_out_phase(A);
   // Exit: the last workgroup to leave re-arms the barrier for the next launch and reports.
   __syncthreads();
   if (threadIdx.x == 0) {

@@ -1,0 +1,114 @@
+#!/usr/bin/env python3
+"""Writes the stored expected values under tests/golden/ by running the CPU oracle only.
+
+Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_runs)
+Every value comes from oracle/ on the seeded synthetic inputs of synth/; nothing here touches
+the HIP library.  The files are small JSON: per logits row the argmax, the top-2 gap, the row's
+max |logit| and the logits at a fixed sample of columns.
+"""
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+
+import synth
+import oracle
+from oracle import from_synth
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+N_SAMPLE_COLS = 48
+
+
+def sample_cols(vocab, seed):
+    return sorted(set(int(c) for c in synth.uniform_int_host(N_SAMPLE_COLS, seed, synth.stream_id(synth.T_MISC, 77), vocab)))
+
+
+def row_record(logits_row, cols):
+    lr = np.asarray(logits_row, dtype=np.float64)
+    return {"argmax": int(np.argmax(lr)), "gap": oracle.top2_gap(lr), "maxabs": float(np.max(np.abs(lr))),
+            "sample": [float(lr[c]) for c in cols]}
+
+
+def llama7b_linear():
+    """Llama-7B-shaped bf16 target, 512 synthetic prefix cells, linear runs of 1, 4 and 8 draft tokens."""
+    sh = synth.SHAPES["llama7b"]
+    seed, T = 0, 512
+    om = from_synth.model_from_seed(sh, seed)
+    base = from_synth.kv_synthetic(sh, seed, T + 64, T)
+    cols = sample_cols(sh.vocab, seed)
+    out = {"shape": sh.name, "seed": seed, "prefix": T, "cols": cols, "runs": {}}
+    for n in (1, 4, 8):
+        t0 = time.time()
+        run = synth.linear_run(n, T)
+        toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT, salt=n)
+        lg = oracle.stage_forward(om, base.clone(), run, 0, sh.n_layers, tokens=toks)["logits"]
+        out["runs"][str(n)] = {"tokens": [int(t) for t in toks], "rows": [row_record(lg[i], cols) for i in range(n)]}
+        print("llama7b_linear n=%d done in %.0fs" % (n, time.time() - t0), flush=True)
+    return out
+
+
+def llama7b_runs():
+    """Eight in-flight runs of 4-token trees over a shared 1024-cell prefix with a seeded cancel
+    schedule (half of the runs are cancelled before a uniform-random layer).  The draft tokens
+    along each tree's first root-to-leaf path are planted to agree with the oracle's own choices
+    for a seeded number of steps, so accepted counts are not all zero."""
+    sh = synth.SHAPES["llama7b"]
+    seed, T, n_runs, n = 0, 1024, 8, 4
+    om = from_synth.model_from_seed(sh, seed)
+    base = from_synth.kv_synthetic(sh, seed, T + 64, T)
+    cols = sample_cols(sh.vocab, seed)
+    cancel = synth.cancel_schedule(seed, n_runs, sh.n_layers)
+    root_expected = int(synth.tokens_host(sh, seed, 1, synth.T_MISC, salt=1)[0])
+    plant = [int(v) % (n + 1) for v in synth.uniform_int_host(n_runs, seed, synth.stream_id(synth.T_MISC, 5), 1 << 20)]
+    out = {"shape": sh.name, "seed": seed, "prefix": T, "cols": cols, "root_expected": root_expected,
+           "cancel_before_layer": cancel, "runs": []}
+    for r in range(n_runs):
+        t0 = time.time()
+        parent = synth.random_tree(seed, r, n)
+        toks = synth.sibling_distinct_tokens(sh, seed, r, parent)
+        rd = synth.tree_run(parent, T, T, offset=n * r)
+        # first root-to-leaf path: follow the lowest-index child
+        path, u = [], -1
+        while True:
+            ch = [c for c in range(n) if parent[c] == u]
+            if not ch:
+                break
+            path.append(ch[0])
+            u = ch[0]
+        k = min(plant[r], len(path))
+        lg = None
+        for step in range(k + 1):
+            lg = oracle.stage_forward(om, base.clone(), rd, 0, sh.n_layers, tokens=toks)["logits"]
+            if step == k:
+                break
+            node = path[step]
+            want = root_expected if step == 0 else int(np.argmax(lg[path[step - 1]]))
+            if int(toks[node]) == want:
+                continue
+            toks = toks.copy()
+            toks[node] = want
+            # keep siblings distinct
+            for c in range(n):
+                if c != node and parent[c] == parent[node] and int(toks[c]) == want:
+                    toks[c] = (want + 1) % sh.vocab
+        a, acc, bonus = oracle.verify_greedy(toks, parent, lg.astype(np.float32), root_expected)
+        out["runs"].append({"parent": [int(p) for p in parent], "tokens": [int(t) for t in toks],
+                            "accepted": a, "accepted_nodes": acc, "bonus": bonus,
+                            "rows": [row_record(lg[i], cols) for i in range(n)]})
+        print("llama7b_runs run %d (planted %d, accepted %d) done in %.0fs" % (r, k, a, time.time() - t0), flush=True)
+    return out
+
+
+CASES = {"llama7b_linear": llama7b_linear, "llama7b_runs": llama7b_runs}
+
+if __name__ == "__main__":
+    for name in (sys.argv[1:] or list(CASES)):
+        data = CASES[name]()
+        with open(os.path.join(HERE, name + ".json"), "w") as f:
+            json.dump(data, f)
+        print("wrote", name)
