@@ -143,6 +143,54 @@ def main():
 
     head = str(max(batches))
     hb = per_batch[head]
+
+    # Early Inference Cancellation latency: the host raises a mapped flag at a random moment of a
+    # run and polls a mapped status word; latency = status visible - flag written (host clock).
+    import ctypes
+    import random
+    hip = ctypes.CDLL("libamdhip64.so")
+    flag_h = torch.zeros(1, dtype=torch.int32, pin_memory=True)
+    stat_h = torch.zeros(2, dtype=torch.int32, pin_memory=True)
+    fptr, sptr = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipHostGetDevicePointer(ctypes.byref(fptr), ctypes.c_void_p(flag_h.data_ptr()), 0) == 0
+    assert hip.hipHostGetDevicePointer(ctypes.byref(sptr), ctypes.c_void_p(stat_h.data_ptr()), 0) == 0
+    n = int(head)
+    run = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(shape, args.seed, n, synth.T_DRAFT, salt=n))
+    logits = torch.empty((n, shape.vocab), device="cuda")
+    lat, stopped_at = [], []
+    rnd = random.Random(args.seed)
+    fwd_s = hb["forward_ms"] * 1e-3
+    sv = stat_h.numpy()
+    fv = flag_h.numpy()
+    for trial in range(16):
+        fv[0] = 0
+        sv[0] = -99
+        torch.cuda.synchronize()
+        pi.binding.lib().pi_stage_forward(model.handle, kv.handle, ctypes.byref(run.desc()), 0, shape.n_layers, None,
+                                          None, ctypes.c_void_p(logits.data_ptr()), fptr, sptr,
+                                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        delay = rnd.uniform(0.1, 0.8) * fwd_s
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < delay:
+            pass
+        fv[0] = 1
+        t_set = time.perf_counter()
+        while sv[0] == -99 and time.perf_counter() - t_set < 1.0:
+            pass
+        t_seen = time.perf_counter()
+        torch.cuda.synchronize()
+        if sv[0] == 1:
+            lat.append((t_seen - t_set) * 1e6)
+            stopped_at.append(int(sv[1]))
+        pi.kv_rollback(kv, run.slots, n)
+    torch.cuda.synchronize()
+    layer_us = hb["per_layer_us"]
+    cancel = {"trials": 16, "cancelled": len(lat),
+              "latency_us_mean": float(np.mean(lat)) if lat else None,
+              "latency_us_max": float(np.max(lat)) if lat else None,
+              "latency_layers_max": float(np.max(lat)) / layer_us if lat else None,
+              "layers_done": stopped_at}
+
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
         "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
@@ -153,9 +201,10 @@ def main():
                                "linear causal mask, uniform-random drafts" % (shape.name, shape.dtype, T, args.batches),
                    "step": "pi_stage_forward(all layers + LM head) + pi_verify_greedy + pi_kv_rollback"},
         "per_batch": per_batch,
+        "cancellation": cancel,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": hb["frac_of_peak"], "traffic": None,
-                     "kernel": "pi_stage_forward launch sequence (n=%s)" % head,
+                     "kernel": "stage_kernel (one launch per forward, n=%s)" % head,
                      "algorithmic_bytes_per_launch": hb["algorithmic_GB"] * 1e9},
     }
     if not args.no_cpu_baseline:
