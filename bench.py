@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per stage_kernel launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated
+# against a device copy (profiles/stage_kernel_llama7b_n8_T512.md).  Keyed by (shape, prefix, n).
+MEASURED_TRAFFIC_BYTES = {("llama7b", 512, 8): 14.481e9}
 
 
 def algorithmic_bytes(shape, layer_bytes, lm_bytes, prefix_len, n):
@@ -76,6 +79,9 @@ def main():
     ap.add_argument("--batches", default="1,4,8")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cancel", action="store_true", help="skip the cancellation latency trials")
+    ap.add_argument("--calibrate-copy", type=int, default=0,
+                    help="only run a device copy of this many MiB (known traffic for counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (a pipeline stage is a layer slice on that GPU); "
@@ -88,6 +94,15 @@ def main():
     from synth import gpu_loader
     import paper_2407_11798_amd as pi
 
+    if args.calibrate_copy:
+        nbytes = args.calibrate_copy << 20
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": nbytes, "calibrate_copy_bytes_written": nbytes, "copies": 3}))
+        return
     shape = synth.SHAPES[args.shape]
     batches = [int(b) for b in args.batches.split(",")]
     T = args.prefix
@@ -162,7 +177,7 @@ def main():
     fwd_s = hb["forward_ms"] * 1e-3
     sv = stat_h.numpy()
     fv = flag_h.numpy()
-    for trial in range(16):
+    for trial in range(0 if args.no_cancel else 16):
         fv[0] = 0
         sv[0] = -99
         torch.cuda.synchronize()
@@ -203,7 +218,8 @@ def main():
         "per_batch": per_batch,
         "cancellation": cancel,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": hb["frac_of_peak"], "traffic": None,
+                     "frac": hb["frac_of_peak"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((shape.name, T, int(head))),
                      "kernel": "stage_kernel (one launch per forward, n=%s)" % head,
                      "algorithmic_bytes_per_launch": hb["algorithmic_GB"] * 1e9},
     }

@@ -1,0 +1,135 @@
+"""Full-size parity: the Llama-7B-shaped bf16 configuration in the launch shape bench.py times,
+compared with values the CPU oracle stored under tests/golden/ (written by make_golden.py, which
+calls only oracle/).  Sampled logits per row, the row argmax and the accepted counts are checked."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from synth import gpu_loader
+import paper_2407_11798_amd as pi
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _load(name):
+    path = os.path.join(GOLDEN, name + ".json")
+    if not os.path.exists(path):
+        pytest.skip("golden file %s missing (run tests/golden/make_golden.py)" % name)
+    with open(path) as f:
+        return json.load(f)
+
+
+@pytest.fixture(scope="module")
+def llama7b():
+    sh = synth.SHAPES["llama7b"]
+    m = gpu_loader.load_model(sh, 0)
+    yield sh, m
+    m.free()
+
+
+def _check_rows(gpu_logits, rows, cols, dtype_tol=2e-2):
+    worst = 0.0
+    for i, rec in enumerate(rows):
+        got = gpu_logits[i]
+        ref = np.asarray(rec["sample"])
+        err = np.max(np.abs(got[cols] - ref)) / rec["maxabs"]
+        worst = max(worst, err)
+        assert err <= dtype_tol, "row %d: sampled logit error %g of the row's max |logit|" % (i, err)
+        assert abs(float(np.max(np.abs(got))) - rec["maxabs"]) <= dtype_tol * rec["maxabs"]
+        if rec["gap"] >= 1e-3:
+            assert int(np.argmax(got)) == rec["argmax"], "row %d argmax" % i
+    return worst
+
+
+def test_llama7b_linear_runs_match_oracle(llama7b):
+    sh, m = llama7b
+    g = _load("llama7b_linear")
+    T = g["prefix"]
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    for n_str, rec in g["runs"].items():
+        n = int(n_str)
+        toks = np.asarray(rec["tokens"], dtype=np.int32)
+        assert np.array_equal(toks, synth.tokens_host(sh, g["seed"], n, synth.T_DRAFT, salt=n))
+        run = gpu_loader.make_run(synth.linear_run(n, T), toks)
+        logits = torch.zeros((n, sh.vocab), device="cuda")
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+        worst = _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+        print("n=%d worst sampled logit error / row max: %.2e" % (n, worst))
+        pi.kv_rollback(kv, run.slots, n)
+    torch.cuda.synchronize()
+    assert len(kv) == T
+
+
+def test_llama7b_concurrent_runs_with_cancellation(llama7b):
+    """Eight 4-token tree runs over a shared 1024-cell prefix; half are cancelled before a seeded
+    layer (stack issued as two stage calls with the flag stored in between).  Survivors must match
+    the oracle's logits, accepted counts and bonus tokens; the best run is committed, the others
+    rolled back, and cancelled runs leave no trace in the cache."""
+    sh, m = llama7b
+    g = _load("llama7b_runs")
+    T, n = g["prefix"], 4
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    snapshot = kv.raw().copy()
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    results = []
+    for r, rec in enumerate(g["runs"]):
+        parent = np.asarray(rec["parent"], dtype=np.int32)
+        toks = np.asarray(rec["tokens"], dtype=np.int32)
+        rd = synth.tree_run(parent, T, T, offset=n * r)
+        run = gpu_loader.make_run(rd, toks)
+        logits = torch.zeros((n, sh.vocab), device="cuda")
+        hidden = torch.zeros((n, sh.d_model), device="cuda")
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        stop = g["cancel_before_layer"][r]
+        flag.zero_()
+        if stop < 0:
+            pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, cancel_flag=flag, run_status=status)
+        else:
+            if stop > 0:
+                pi.stage_forward(m, kv, run, 0, stop, hidden_out=hidden, cancel_flag=flag, run_status=status)
+            flag.fill_(1)
+            pi.stage_forward(m, kv, run, stop, sh.n_layers, hidden_in=hidden if stop > 0 else None,
+                             logits_out=logits, cancel_flag=flag, run_status=status)
+        torch.cuda.synchronize()
+        if stop >= 0:
+            assert status.cpu().tolist() == [pi.PI_CANCELLED, stop]
+            pi.kv_rollback(kv, run.slots, n)
+            results.append((r, -1, None, run))
+            continue
+        assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+        _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+        acc = torch.zeros(n, dtype=torch.int32, device="cuda")
+        res = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pi.verify_greedy(run.tokens, run.parent, n, logits, sh.vocab, g["root_expected"], acc, res)
+        torch.cuda.synchronize()
+        if all(rec["rows"][i]["gap"] >= 1e-3 for i in rec["accepted_nodes"]):
+            assert res.cpu().tolist() == [rec["accepted"], rec["bonus"]]
+            assert acc.cpu().tolist()[:rec["accepted"]] == rec["accepted_nodes"]
+        results.append((r, int(res[0].item()), (acc, res), run))
+    # commit the best surviving run (ties: lowest run index), discard the others
+    best = max((x for x in results if x[1] >= 0), key=lambda x: (x[1], -x[0]))
+    for r, a, ar, run in results:
+        if a >= 0 and r != best[0]:
+            pi.kv_rollback(kv, run.slots, n)
+    pi.kv_rollback(kv, best[3].slots, n, best[2][0], best[2][1])
+    torch.cuda.synchronize()
+    assert len(kv) == T + best[1]
+    after = kv.raw()
+    # everything except the committed cells equals the pre-run image
+    es = 2
+    img = after.copy().reshape(2, sh.n_layers, sh.n_kv_heads, T + 64, sh.head_dim * es)
+    ref = snapshot.reshape(img.shape)
+    assert np.array_equal(np.delete(img, np.s_[T:T + best[1]], axis=3), np.delete(ref, np.s_[T:T + best[1]], axis=3))
+    assert best[1] == 0 or img[:, :, :, T:T + best[1]].any()
