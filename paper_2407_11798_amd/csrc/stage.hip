@@ -544,15 +544,15 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
       C.pending = false;
     }
   }
-  // The ring is free: start the next phase's weight stream before the last (slow) flush, so HBM
-  // stays busy while this wave waits on its reduction round trips and on the grid barrier.
-  WaveStream Sn = S;
-  if (next) {
-    stream_init<DT>(Sn, *next, next_sk, wave);
-    ring_prefetch<DT, UR>(R, Sn, lane);
-  }
   if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale);  // range ends inside a row block
-  S = Sn;
+  wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
+  // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
+  // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
+  // starts its stream after the barrier instead (those loads overlap the activation staging).
+  if (next) {
+    stream_init<DT>(S, *next, next_sk, wave);
+    if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
+  }
 }
 
 // ---- attention phase ----------------------------------------------------------------------------
@@ -1000,9 +1000,8 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   float* rscale = red + kThreads;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
-  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);  // drains its stores
   wg_mark(A, trace_layer, 2);
-  wave_drain();
 }
 
 template <int DT, int UR>
@@ -1044,8 +1043,9 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   if (ok && !dead) {
     embed_phase(A);
     stream_init<DT>(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
-    ring_prefetch<DT, UR>(R, S, lane);
+    if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
     ok = grid_barrier(A, bc, -1, false);
+    if (wave == 0) ring_prefetch<DT, UR>(R, S, lane);
   }
   // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
   // O, gate/up, down), phase 1 is attention, and a final pass after the last layer is the LM
@@ -1061,9 +1061,10 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
         break;
       wg_mark(A, l * 8 + 1, 2);
       stream_init<DT>(S, uni_mat(A.layers[l].o), A.sk[1], wave);
-      ring_prefetch<DT, UR>(R, S, lane);
+      if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
       wg_mark(A, l * 8 + 1, 3);
       if (!(ok = grid_barrier(A, bc, -1, false, l * 8 + 1))) break;
+      if (wave == 0) ring_prefetch<DT, UR>(R, S, lane);
       wg_mark(A, l * 8 + 1, 5);
       continue;
     }
@@ -1117,6 +1118,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     if (k == 5) break;
     const bool boundary = k == 4;
     if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
+    if (wave == 0 && has_next) ring_prefetch<DT, UR>(R, S, lane);
     wg_mark(A, l * 8 + k, 5);
     if (boundary) dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
   }
