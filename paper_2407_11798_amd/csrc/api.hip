@@ -254,6 +254,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     }
     if (worst < tiles) worst = tiles;
     e = dev_alloc(m, &m->part, worst * 1024, false);
+    if (e == hipSuccess) e = hipMemset(m->part, 0xFF, worst * 1024);  // every partial tile starts "empty"
   }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);

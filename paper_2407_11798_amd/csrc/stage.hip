@@ -436,8 +436,14 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
 }
 
 // One wave has finished its part of row block rb (slice S.slice).  If other waves contribute to
-// the row block, park the partial tile and count arrivals; the last arriver adds all partial
-// tiles in a fixed order (slice-major, then wave order) and runs the epilogue.
+// the row block, every contributor but one simply stores its partial tile (fire and forget).
+// The one exception is the contributor that reaches the row block last in its own range (slice
+// 0, first wave of the row block): it keeps its tile in registers, polls the others' tiles --
+// a tile is "empty" while it holds the all-ones pattern, which no sum can produce -- adds them
+// in a fixed order (slice-major, then wave order), marks them empty again for the next use and
+// runs the epilogue.  No arrival counters, no waiting between a store and a counter bump.
+constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;
+
 __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
                                                f32x4 acc, int lane, const EpiCtx& e, const float* rscale) {
   const int first = uni((rb * S.nt) / S.share);
@@ -445,24 +451,44 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
   const int c = last - first + 1;  // contributors per slice (same for every slice)
   const int expected = c * S_k;
   if (expected > 1) {
-    const int i = lane & 15;
+    const bool live = (lane & 15) < e.n;
     const int maxc = A.part_maxc;
     const __amdgpu_buffer_rsrc_t pr = rsrc_of(A.part);
-    const int mine = (((S.slice * S.NRB + rb) * maxc + (S.gw - first)) * 64 + lane) * 16;
-    if (i < e.n) st_ag4(pr, mine, acc);
-    wave_drain();
-    int old = 0;
-    if (lane == 0)
-      old = __hip_atomic_fetch_add(A.cnt + rb, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    old = __shfl(old, 0);
-    if (old != expected - 1) return;
-    acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (i < e.n) {
-      for (int s2 = 0; s2 < S_k; ++s2)
-        for (int j = 0; j < c; ++j)
-          acc += ld_ag4(pr, (((s2 * S.NRB + rb) * maxc + j) * 64 + lane) * 16);
+    if (S.slice != 0 || S.gw != first) {
+      if (live) st_ag4(pr, (((S.slice * S.NRB + rb) * maxc + (S.gw - first)) * 64 + lane) * 16, acc);
+      return;
     }
-    if (lane == 0) __hip_atomic_store(A.cnt + rb, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
+    const unsigned long long t0 = wall_clock64();
+    for (int base = 1; base < expected; base += 8) {  // contributor 0 is this wave
+      u32x4 t[8];
+      int off[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int k = min(base + q, expected - 1);
+        off[q] = (((k / c * S.NRB + rb) * maxc + k % c) * 64 + lane) * 16;
+      }
+      for (unsigned spin = 0;; ++spin) {
+        bool ready = true;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) t[q] = __builtin_amdgcn_raw_buffer_load_b128(pr, off[q], 0, kAgent);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) ready = ready && (t[q][0] != kEmptyWord || t[q][1] != kEmptyWord);
+        if (__builtin_amdgcn_ballot_w64(live && !ready) == 0) break;
+        __builtin_amdgcn_s_sleep(1);
+        if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+          if (lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        if (base + q < expected && live) {
+          acc += __builtin_bit_cast(f32x4, t[q]);
+          __builtin_amdgcn_raw_buffer_store_b128(empty, pr, off[q], 0, kAgent);
+        }
+      }
+    }
   }
   epilogue(e, rb, acc, lane, rscale);
 }
