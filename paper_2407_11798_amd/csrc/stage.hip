@@ -153,7 +153,8 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
 // cut into equal contiguous ranges, one per wave of the group: flat index f -> row block f / nt,
 // k tile t0 + f % nt.
 struct WaveStream {
-  __amdgpu_buffer_rsrc_t rsrc;  // the whole matrix as a raw buffer
+  const char* w;   // the whole matrix, read through a raw buffer of `bytes` bytes
+  uint32_t bytes;
   int KT, nt, t0, NRB;
   int f0, f1, share;
   int slice, gw;  // slice index, wave index within the slice group
@@ -197,11 +198,25 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
 
+// The stream state is carried across phases and around the phase loop, where the compiler has to
+// assume it differs between lanes; it does not, and the streaming loop needs it in scalar
+// registers (a raw buffer load with per-lane descriptor or offset operands is wrapped in a loop
+// over the distinct values).
+__device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
+  S.w = uni_ptr(S.w);
+  S.bytes = (uint32_t)uni((int)S.bytes);
+  S.KT = uni(S.KT); S.nt = uni(S.nt); S.t0 = uni(S.t0); S.NRB = uni(S.NRB);
+  S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
+  S.slice = uni(S.slice); S.gw = uni(S.gw);
+  S.lf = uni(S.lf); S.lrb = uni(S.lrb); S.lt = uni(S.lt);
+}
+
 template <int DT>
 __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int S_k, int wave) {
   const int wg = blockIdx.x, G = gridDim.x;
   constexpr int kTileBytes = DT == PI_DTYPE_BF16 ? 1024 : 2048;
-  S.rsrc = make_rsrc(M.w, (uint32_t)M.NRB * (uint32_t)M.KT * kTileBytes);
+  S.w = M.w;
+  S.bytes = (uint32_t)M.NRB * (uint32_t)M.KT * kTileBytes;
   S.KT = M.KT;
   S.NRB = M.NRB;
   S.nt = uni(M.KT / S_k);
@@ -216,6 +231,7 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   S.lf = S.f0;
   S.lrb = uni(S.f0 / S.nt);
   S.lt = S.f0 - S.lrb * S.nt;
+  stream_make_uniform(S);
 }
 
 // The ring of outstanding weight tiles: UR tiles, each 1 KiB (bf16: one 16-byte load per lane)
@@ -234,19 +250,24 @@ struct Ring {
 // stay in flight (a branch around a load makes the compiler wait for it at the join).
 template <int DT, int UR, int J>
 __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int lane) {
-  const bool valid = S.lf < S.f1;
-  const int soff = valid ? (S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes : 0;
-  const int voff = valid ? lane * 16 : 0;
+  // 0/1 integers in scalar registers rather than booleans: a boolean that also steers a per-lane
+  // select becomes a lane mask, and the cursor arithmetic that depends on it would move to the
+  // vector unit (and the load's scalar operands with it).
+  const int valid = uni(S.lf < S.f1 ? 1 : 0);
+  const int mask = -valid;
+  const int soff = ((S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes) & mask;
+  const int voff = (lane * 16) & mask;
+  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(S.w, S.bytes);
   if constexpr (DT == PI_DTYPE_BF16) {
-    R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff, 2);
+    R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
   } else {
-    R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff, 2);
-    R.r[2 * J + 1] = __builtin_amdgcn_raw_buffer_load_b128(S.rsrc, voff, soff + (valid ? 1024 : 0), 2);
+    R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
+    R.r[2 * J + 1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff + (1024 & mask), 2);
   }
   S.lf += 1;
-  const bool wrap = S.lt + 1 == S.nt;
-  S.lt = wrap ? 0 : S.lt + 1;
-  S.lrb += wrap ? 1 : 0;
+  const int wrap = uni(S.lt + 1 == S.nt ? 1 : 0);
+  S.lt = (S.lt + 1) * (1 - wrap);
+  S.lrb += wrap;
 }
 
 template <int DT, int UR, int J = 0>
@@ -526,13 +547,12 @@ template <int DT, int UR, int J>
 __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, ConsumeState& C, const char* lds,
                                              int n, int lane) {
   if constexpr (J < UR) {
-    const bool valid = C.f < S.f1;
+    const int valid = uni(C.f < S.f1 ? 1 : 0);
     const int g = lane >> 4, ln = min(lane & 15, n - 1);
     f32x4 acc2 = C.acc;
     mma_tile<DT, UR, J>(R, lds, S.nt * 4 * n, (C.t * 4 + g) * n + ln, acc2);
     ring_issue<DT, UR, J>(R, S, lane);
-    const int t1 = C.t + 1;
-    const bool end_rb = valid && t1 == S.nt;
+    const int end_rb = uni(valid && C.t + 1 == S.nt ? 1 : 0);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const float a = valid ? acc2[q] : C.acc[q];
@@ -541,9 +561,9 @@ __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, Con
     }
     C.prb = end_rb ? C.rb : C.prb;
     C.pending = C.pending || end_rb;
-    C.f += valid ? 1 : 0;
-    C.t = end_rb ? 0 : (valid ? t1 : C.t);
-    C.rb += end_rb ? 1 : 0;
+    C.f += valid;
+    C.t = (C.t + valid) * (1 - end_rb);
+    C.rb += end_rb;
     consume_step<DT, UR, J + 1>(R, S, C, lds, n, lane);
   }
 }
@@ -1021,6 +1041,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            const float* xin, const float* gain, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int lane, const MatDev* next, int next_sk,
                                            int wave, int trace_layer = -1) {
+  stream_make_uniform(S);
   const size_t xbytes = (size_t)S.nt * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
