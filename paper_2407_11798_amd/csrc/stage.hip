@@ -685,41 +685,32 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
   {
     const __amdgpu_buffer_rsrc_t kr = rsrc_of(kl), vr = rsrc_of(vl);
     const int items = CP * (HD / 8);
-    for (int it0 = 0; it0 < items; it0 += kThreads * 2) {
-      u32x4 kraw[2][2], vraw[2][2];
-      int lc[2], d8[2];
-      bool live[2];
+    constexpr int KB = 4;  // items per thread whose loads are in flight together
+    for (int it0 = 0; it0 < items; it0 += kThreads * KB) {
+      u32x4 kraw[KB][NS], vraw[KB][NS];
+      int lc[KB], d8[KB];
+      bool live[KB];
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < KB; ++q) {
         const int it = it0 + q * kThreads + tid;
         lc[q] = it / (HD / 8);
         d8[q] = (it % (HD / 8)) * 8;
         live[q] = it < items && lc[q] < cells;
-        if (live[q]) {
-          const bool win = lc[q] >= npc;
-          const int cell = win ? A.window_base + (lc[q] - npc) : p_begin + lc[q];
-          const int off = (int)((head_elems + (size_t)cell * HD + d8[q]) * ES);
-          const int aux = win ? kAgent : 0;
-          if (win) {
-            kraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(kr, off, 0, kAgent);
-            vraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(vr, off, 0, kAgent);
-            if (NS == 2) {
-              kraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(kr, off + 16, 0, kAgent);
-              vraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(vr, off + 16, 0, kAgent);
-            }
-          } else {
-            kraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(kr, off, 0, 0);
-            vraw[q][0] = __builtin_amdgcn_raw_buffer_load_b128(vr, off, 0, 0);
-            if (NS == 2) {
-              kraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(kr, off + 16, 0, 0);
-              vraw[q][1] = __builtin_amdgcn_raw_buffer_load_b128(vr, off + 16, 0, 0);
-            }
-          }
-          (void)aux;
+        // Branch-free so that all loads of the batch are in flight together (a branch around a
+        // load makes the compiler wait for it at the join); a dead item re-reads the head's first
+        // bytes.  Every cell is read once per layer, and the window cells were written by other
+        // workgroups in this launch, so all loads bypass the per-XCD L2.
+        const bool win = lc[q] >= npc;
+        const int cell = !live[q] ? 0 : (win ? A.window_base + (lc[q] - npc) : p_begin + lc[q]);
+        const int off = (int)((head_elems + (size_t)cell * HD + (live[q] ? d8[q] : 0)) * ES);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          kraw[q][s] = __builtin_amdgcn_raw_buffer_load_b128(kr, off + 16 * s, 0, kAgent);
+          vraw[q][s] = __builtin_amdgcn_raw_buffer_load_b128(vr, off + 16 * s, 0, kAgent);
         }
       }
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < KB; ++q) {
         const int it = it0 + q * kThreads + tid;
         if (it >= items) continue;
         uint32_t kw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, vw[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
