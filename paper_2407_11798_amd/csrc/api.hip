@@ -27,8 +27,6 @@ struct pi_model {
   LayerDev* layers_dev = nullptr;
   // activation scratch of the one run in flight
   float *x = nullptr, *q = nullptr, *o = nullptr, *a = nullptr, *ssq = nullptr, *part = nullptr;
-  int part_maxc = 1;
-  int* cnt = nullptr;  // row-block arrival counters
   RunState* rs = nullptr;
   StageSync* sync = nullptr;
   unsigned long long* trace = nullptr;  // timestamps of the barriers of the last run
@@ -98,21 +96,11 @@ int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n) {
   return 0;
 }
 
-// Largest number of waves that can contribute to one row block within a slice.
-int max_contributors(const pi_model* m, const PackedMat& w, int sk) {
-  const int nt = w.KT / sk;
-  const long total = (long)w.NRB * nt;
-  const long nwaves = (long)(m->grid / sk) * (kStageThreads / 64);
-  const long share = (total + nwaves - 1) / nwaves;
-  return (int)((nt + share - 1) / share + 1);
-}
-
 struct StagePlan {
   int sk[5];
   int min_nt;
   size_t lds;
-  int maxc;
-  size_t part_tiles;
+  size_t part_tiles;  // 1 KiB tiles that cross slices
 };
 
 bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
@@ -120,8 +108,7 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
                               &m->lm_head};
   p->min_nt = 1 << 30;
   p->lds = 0;
-  p->maxc = 1;
-  p->part_tiles = 0;
+  p->part_tiles = 1;
   for (int ph = 0; ph < 5; ++ph) {
     const int sk = choose_sk(m, ph, *mats[ph], n);
     if (sk == 0) return false;
@@ -130,12 +117,7 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
     if (nt < p->min_nt) p->min_nt = nt;
     const size_t lds = stage_proj_lds_bytes(n, nt);
     if (lds > p->lds) p->lds = lds;
-    const int mc = max_contributors(m, *mats[ph], sk);
-    if (mc > p->maxc) p->maxc = mc;
-  }
-  for (int ph = 0; ph < 5; ++ph) {
-    const size_t t = (size_t)p->sk[ph] * mats[ph]->NRB * p->maxc;
-    if (t > p->part_tiles) p->part_tiles = t;
+    if (sk > 1 && (size_t)sk * mats[ph]->NRB > p->part_tiles) p->part_tiles = (size_t)sk * mats[ph]->NRB;
   }
   return true;
 }
@@ -220,11 +202,6 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (e == hipSuccess) e = dev_alloc(m, &m->a, (size_t)PI_MAX_BATCH * c.ffn * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->ssq, (size_t)(d / 16) * 16 * sizeof(float), true);
   if (e == hipSuccess) {
-    int max_nrb = m->lm_head.NRB;
-    for (const PackedMat* p : {&m->layers[0].qkv, &m->layers[0].gateup}) max_nrb = p->NRB > max_nrb ? p->NRB : max_nrb;
-    e = dev_alloc(m, &m->cnt, (size_t)max_nrb * sizeof(int), true);
-  }
-  if (e == hipSuccess) {
     int dev = 0;
     hipDeviceProp_t prop;
     e = hipGetDevice(&dev);
@@ -232,29 +209,14 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     if (e == hipSuccess) m->grid = prop.multiProcessorCount < kMaxGrid ? prop.multiProcessorCount : kMaxGrid;
   }
   if (e == hipSuccess) {
-    // split-k scratch for the largest plan over all token counts
+    // tiles that cross slices, for the largest plan over all token counts; every tile starts "empty"
     size_t tiles = 1;
     for (int n = 1; n <= PI_MAX_BATCH; ++n) {
       StagePlan sp;
-      if (!make_stage_plan(m, n, &sp)) continue;
-      if (sp.part_tiles > tiles) tiles = sp.part_tiles;
-      if (sp.maxc > m->part_maxc) m->part_maxc = sp.maxc;
+      if (make_stage_plan(m, n, &sp) && sp.part_tiles > tiles) tiles = sp.part_tiles;
     }
-    // part_maxc is shared by all plans: size for it
-    size_t worst = 0;
-    const PackedMat* mats[5] = {&m->layers[0].qkv, &m->layers[0].o, &m->layers[0].gateup, &m->layers[0].down,
-                                &m->lm_head};
-    for (int n = 1; n <= PI_MAX_BATCH; ++n) {
-      StagePlan sp;
-      if (!make_stage_plan(m, n, &sp)) continue;
-      for (int ph = 0; ph < 5; ++ph) {
-        const size_t t = (size_t)sp.sk[ph] * mats[ph]->NRB * m->part_maxc;
-        if (t > worst) worst = t;
-      }
-    }
-    if (worst < tiles) worst = tiles;
-    e = dev_alloc(m, &m->part, worst * 1024, false);
-    if (e == hipSuccess) e = hipMemset(m->part, 0xFF, worst * 1024);  // every partial tile starts "empty"
+    e = dev_alloc(m, &m->part, tiles * 1024, false);
+    if (e == hipSuccess) e = hipMemset(m->part, 0xFF, tiles * 1024);
   }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);
@@ -643,8 +605,6 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.a = m->a;
   a.ssq = m->ssq;
   a.part = m->part;
-  a.part_maxc = m->part_maxc;
-  a.cnt = m->cnt;
   a.attn_o = kv->attn_o;
   a.attn_ml = kv->attn_ml;
   a.attn_flags = kv->attn_flags;

@@ -102,9 +102,7 @@ struct StageArgs {
   const int32_t* kv_len;
   // scratch
   float *x, *q, *o, *a, *ssq;
-  float* part;   // [S_k][NRB][part_maxc][256] split-k partial tiles
-  int part_maxc;
-  int* cnt;      // [NRB] arrival counters, zero between phases
+  float* part;   // [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
   float* attn_o;   // [Hkv][units][R][hd]
   float* attn_ml;  // [Hkv][units][R][2]
   unsigned* attn_flags;  // [Hkv][attn_flag_stride]: barrier number at which a unit last published

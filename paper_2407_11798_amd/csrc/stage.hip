@@ -149,16 +149,19 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
 
 // ---- per-wave weight stream -----------------------------------------------------------------
 // In a projection with S_k column slices, workgroup wg serves slice wg % S_k together with the
-// other gridDim/S_k workgroups of its group.  The slice's tiles, ordered row-block-major, are
-// cut into equal contiguous ranges, one per wave of the group: flat index f -> row block f / nt,
-// k tile t0 + f % nt.
+// other gridDim/S_k workgroups of its group.  The group's workgroups own whole row blocks (an
+// even split of the matrix's row blocks); the workgroup's tiles of the slice, ordered
+// row-block-major, are cut into equal contiguous ranges, one per wave: flat index f -> row block
+// rb0 + f / nt, k tile t0 + f % nt.  A row block is therefore reduced inside one workgroup,
+// through LDS; only the S_k slices of a row block meet through memory.
 struct WaveStream {
   const char* w;   // the whole matrix, read through a raw buffer of `bytes` bytes
   uint32_t bytes;
   int KT, nt, t0, NRB;
-  int f0, f1, share;
-  int slice, gw;  // slice index, wave index within the slice group
-  // loader cursor
+  int rb0, R;         // this workgroup's row blocks [rb0, rb0 + R)
+  int f0, f1, share;  // this wave's flat range of the workgroup's R * nt tiles; tiles per wave
+  int slice, wave;
+  // loader cursor: flat index, absolute row block, tile within the slice
   int lf, lrb, lt;
 };
 
@@ -207,7 +210,7 @@ __device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
   S.bytes = (uint32_t)uni((int)S.bytes);
   S.KT = uni(S.KT); S.nt = uni(S.nt); S.t0 = uni(S.t0); S.NRB = uni(S.NRB);
   S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
-  S.slice = uni(S.slice); S.gw = uni(S.gw);
+  S.slice = uni(S.slice); S.wave = uni(S.wave); S.rb0 = uni(S.rb0); S.R = uni(S.R);
   S.lf = uni(S.lf); S.lrb = uni(S.lrb); S.lt = uni(S.lt);
 }
 
@@ -222,15 +225,18 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   S.nt = uni(M.KT / S_k);
   S.slice = uni(wg % S_k);
   S.t0 = S.slice * S.nt;
-  const int nwaves = uni((G / S_k) * kWaves);
-  S.gw = uni((wg / S_k) * kWaves + wave);
-  const int total = M.NRB * S.nt;
-  S.share = uni((total + nwaves - 1) / nwaves);
-  S.f0 = min(total, S.gw * S.share);
+  S.wave = wave;
+  const int Gs = uni(G / S_k), gwg = uni(wg / S_k);
+  S.rb0 = uni((int)((long)gwg * M.NRB / Gs));
+  S.R = uni((int)((long)(gwg + 1) * M.NRB / Gs)) - S.rb0;
+  const int total = S.R * S.nt;
+  S.share = max(1, uni((total + kWaves - 1) / kWaves));
+  S.f0 = min(total, wave * S.share);
   S.f1 = min(total, S.f0 + S.share);
   S.lf = S.f0;
-  S.lrb = uni(S.f0 / S.nt);
-  S.lt = S.f0 - S.lrb * S.nt;
+  const int q = uni(S.f0 / S.nt);
+  S.lrb = S.rb0 + q;
+  S.lt = S.f0 - q * S.nt;
   stream_make_uniform(S);
 }
 
@@ -456,39 +462,64 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
   }
 }
 
-// One wave has finished its part of row block rb (slice S.slice).  If other waves contribute to
-// the row block, every contributor but one simply stores its partial tile (fire and forget).
-// The one exception is the contributor that reaches the row block last in its own range (slice
-// 0, first wave of the row block): it keeps its tile in registers, polls the others' tiles --
-// a tile is "empty" while it holds the all-ones pattern, which no sum can produce -- adds them
-// in a fixed order (slice-major, then wave order), marks them empty again for the next use and
-// runs the epilogue.  No arrival counters, no waiting between a store and a counter bump.
+// One wave has finished its part of row block rb.  Inside the workgroup: a wave contributes to a
+// row block it does not start only at the beginning of its own range, so each wave parks at most
+// one partial tile per phase (LDS slot = wave) and raises its flag to the phase's tag; the wave
+// that holds the row block's first tile reaches the row block last in its own range, waits
+// (bounded) for those flags and adds the tiles in wave order.  Across slices (S_k > 1): slices
+// other than 0 store their sums to memory (a tile is "empty" while it holds the all-ones
+// pattern, which no sum can produce); slice 0 polls them (bounded), adds them in slice order,
+// marks them empty again for the next use and runs the epilogue.
 constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;
 
+struct FlushCtx {
+  f32x4* part;  // LDS [waves - 1][64]
+  int* pflag;   // LDS [waves]: tag of the phase in which the wave last parked a tile
+  unsigned tag;
+};
+
 __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
-                                               f32x4 acc, int lane, const EpiCtx& e, const float* rscale) {
-  const int first = uni((rb * S.nt) / S.share);
-  const int last = uni(((rb + 1) * S.nt - 1) / S.share);
-  const int c = last - first + 1;  // contributors per slice (same for every slice)
-  const int expected = c * S_k;
-  if (expected > 1) {
+                                               f32x4 acc, int lane, const EpiCtx& e, const float* rscale,
+                                               const FlushCtx& F) {
+  const int r = rb - S.rb0;
+  const int first = uni((r * S.nt) / S.share);
+  const int last = uni(((r + 1) * S.nt - 1) / S.share);
+  if (last > first) {
+    if (S.wave != first) {
+      F.part[(S.wave - 1) * 64 + lane] = acc;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      if (lane == 0) __hip_atomic_store(F.pflag + S.wave, (int)F.tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      return;
+    }
+    const unsigned long long t0 = wall_clock64();
+    for (unsigned spin = 0;; ++spin) {
+      int missing = 0;
+      for (int w = first + 1; w <= last; ++w)
+        missing |= __hip_atomic_load(F.pflag + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != (int)F.tag;
+      if (!uni(missing)) break;
+      __builtin_amdgcn_s_sleep(1);
+      if ((spin & 63) == 63 && wall_clock64() - t0 > A.timeout_ticks) {
+        if (lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    for (int w = first + 1; w <= last; ++w) acc += F.part[(w - 1) * 64 + lane];
+  }
+  if (S_k > 1) {
     const bool live = (lane & 15) < e.n;
-    const int maxc = A.part_maxc;
     const __amdgpu_buffer_rsrc_t pr = rsrc_of(A.part);
-    if (S.slice != 0 || S.gw != first) {
-      if (live) st_ag4(pr, (((S.slice * S.NRB + rb) * maxc + (S.gw - first)) * 64 + lane) * 16, acc);
+    if (S.slice != 0) {
+      if (live) st_ag4(pr, ((rb * S_k + S.slice) * 64 + lane) * 16, acc);
       return;
     }
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
     const unsigned long long t0 = wall_clock64();
-    for (int base = 1; base < expected; base += 8) {  // contributor 0 is this wave
+    for (int base = 1; base < S_k; base += 8) {  // slice 0 is this workgroup
       u32x4 t[8];
       int off[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int k = min(base + q, expected - 1);
-        off[q] = (((k / c * S.NRB + rb) * maxc + k % c) * 64 + lane) * 16;
-      }
+      for (int q = 0; q < 8; ++q) off[q] = ((rb * S_k + min(base + q, S_k - 1)) * 64 + lane) * 16;
       for (unsigned spin = 0;; ++spin) {
         bool ready = true;
 #pragma unroll
@@ -504,7 +535,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
       }
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        if (base + q < expected && live) {
+        if (base + q < S_k && live) {
           acc += __builtin_bit_cast(f32x4, t[q]);
           __builtin_amdgcn_raw_buffer_store_b128(empty, pr, off[q], 0, kAgent);
         }
@@ -572,11 +603,13 @@ __device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, Con
 template <int DT, int UR>
 __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                               const char* lds, int n, int lane, const EpiCtx& e,
-                                              const float* rscale, const MatDev* next, int next_sk, int wave) {
+                                              const float* rscale, const FlushCtx& F, const MatDev* next,
+                                              int next_sk, int wave) {
   ConsumeState C;
   C.f = S.f0;
-  C.rb = uni(S.f0 / S.nt);
-  C.t = S.f0 - C.rb * S.nt;
+  const int q0 = uni(S.f0 / S.nt);
+  C.rb = S.rb0 + q0;
+  C.t = S.f0 - q0 * S.nt;
   C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
   C.pending = false;
   C.prb = 0;
@@ -586,11 +619,11 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
       consume_step<DT, UR, 0>(R, S, C, lds, n, lane);
     } while (!C.pending && C.f < S.f1);
     if (C.pending) {
-      flush_rowblock(A, S, S_k, C.prb, C.pacc, lane, e, rscale);
+      flush_rowblock(A, S, S_k, C.prb, C.pacc, lane, e, rscale, F);
       C.pending = false;
     }
   }
-  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale);  // range ends inside a row block
+  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale, F);  // range ends inside a row block
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
   // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
   // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
@@ -1030,15 +1063,19 @@ __device__ void hidden_out_phase(const StageArgs& A) {
 template <int DT, int UR>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                            const float* xin, const float* gain, bool scaled, int K,
-                                           const EpiCtx& e, char* lds, int lane, const MatDev* next, int next_sk,
-                                           int wave, int trace_layer = -1) {
+                                           const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
+                                           const MatDev* next, int next_sk, int wave, int trace_layer = -1) {
   stream_make_uniform(S);
   const size_t xbytes = (size_t)S.nt * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
+  FlushCtx F;
+  F.part = (f32x4*)(rscale + 16);
+  F.pflag = pflag;
+  F.tag = tag;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
-  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, next, next_sk, wave);  // drains its stores
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, F, next, next_sk, wave);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
 
@@ -1046,6 +1083,8 @@ template <int DT, int UR>
 __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   extern __shared__ __align__(16) char lds[];
   __shared__ int bar_sh[2];
+  __shared__ int pflag[kWaves];
+  if (threadIdx.x < kWaves) pflag[threadIdx.x] = 0;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform: keep it scalar
   BarrierCtx bc;
@@ -1150,7 +1189,8 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     e.N = M.N;
     wg_mark(A, l * 8 + k, 0);
-    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, lane, has_next ? &nxt : nullptr, nsk, wave,
+    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, bc.epoch + 1, lane,
+                       has_next ? &nxt : nullptr, nsk, wave,
                        l * 8 + k);
     wg_mark(A, l * 8 + k, 3);
     if (k == 5) break;
@@ -1185,7 +1225,9 @@ size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
   return (size_t)attn_lds_layout(head_dim, cp, dtype == PI_DTYPE_BF16 ? 1 : 2).total;
 }
 
-size_t stage_proj_lds_bytes(int n, int nt) { return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float); }
+size_t stage_proj_lds_bytes(int n, int nt) {
+  return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1) * 1024;
+}
 
 namespace {
 const void* stage_fn(int dtype, int ring) {
