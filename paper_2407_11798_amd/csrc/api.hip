@@ -89,7 +89,8 @@ int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n) {
   const int ov = m->sk_override[phase];
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
     if (w.KT % sk || m->grid % sk) continue;
-    if (stage_proj_lds_bytes(n, w.KT / sk) > kProjLdsBudget) continue;
+    const int gs = m->grid / sk;
+    if (stage_proj_lds_bytes(n, w.KT / sk, (w.NRB + gs - 1) / gs) > kProjLdsBudget) continue;
     if (ov > sk) continue;  // an override asks for at least this many slices
     return sk;
   }
@@ -115,7 +116,8 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
     p->sk[ph] = sk;
     const int nt = mats[ph]->KT / sk;
     if (nt < p->min_nt) p->min_nt = nt;
-    const size_t lds = stage_proj_lds_bytes(n, nt);
+    const int gs = m->grid / sk;
+    const size_t lds = stage_proj_lds_bytes(n, nt, (mats[ph]->NRB + gs - 1) / gs);
     if (lds > p->lds) p->lds = lds;
     if (sk > 1 && (size_t)sk * mats[ph]->NRB > p->part_tiles) p->part_tiles = (size_t)sk * mats[ph]->NRB;
   }

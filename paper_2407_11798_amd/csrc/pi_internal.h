@@ -126,7 +126,7 @@ hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, Pac
 hipError_t launch_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t count,
                           hipStream_t s);
 size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells);
-size_t stage_proj_lds_bytes(int n, int nt);
+size_t stage_proj_lds_bytes(int n, int nt, int r_max);
 int stage_ring_size(int dtype, int min_nt);
 hipError_t stage_configure(int dtype, int ring, size_t max_lds, int* max_blocks_per_cu);
 hipError_t launch_stage(const StageArgs& a, int dtype, int ring, int grid, size_t lds, hipStream_t s);

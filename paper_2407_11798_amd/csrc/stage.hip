@@ -251,9 +251,9 @@ struct Ring {
 };
 
 // Issue the load of the next tile of the wave's range into slot J.  Branch-free: past the end
-// of the range every lane re-reads the first 16 bytes of the matrix (one cached line) and the
-// consumer discards the slot, so the steady-state loop is a single basic block and the loads
-// stay in flight (a branch around a load makes the compiler wait for it at the join).
+// of the range the load still executes, with out-of-range offsets, and the consumer discards
+// the slot, so the steady-state loop is a single basic block and the loads stay in flight (a
+// branch around a load makes the compiler wait for it at the join).
 template <int DT, int UR, int J>
 __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int lane) {
   // 0/1 integers in scalar registers rather than booleans: a boolean that also steers a per-lane
@@ -262,7 +262,9 @@ __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int l
   const int valid = uni(S.lf < S.f1 ? 1 : 0);
   const int mask = -valid;
   const int soff = ((S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes) & mask;
-  const int voff = (lane * 16) & mask;
+  // past the end of the range the lanes' offsets lie outside the buffer: the hardware's range
+  // check answers such a load with zeros without going to memory
+  const int voff = ((lane * 16) & mask) | (0x7ffffff0 & ~mask);
   const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(S.w, S.bytes);
   if constexpr (DT == PI_DTYPE_BF16) {
     R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
@@ -396,6 +398,8 @@ struct EpiCtx {
   const int32_t* positions;
   const int32_t* slots;
   const float2* rope;
+  const f32x4* resid;  // RESID: LDS copy of the residual rows of the workgroup's row blocks, [row block][lane]
+  int rb0;             // first row block of the workgroup
 };
 
 __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem_idx, const float* v) {
@@ -442,7 +446,9 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
     if (live && row < e.N) {
       const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
       const int off = (i * e.N + row) * 4;
-      const f32x4 x = ld_ag4(xr, off) + acc;
+      // the residual rows were copied to LDS when the phase began: a load issued here would queue
+      // behind the next phase's weight requests of the waves that are already done
+      const f32x4 x = e.resid[(rb - e.rb0) * 64 + lane] + acc;
       st_ag4(xr, off, x);
       s = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
     }
@@ -476,6 +482,7 @@ struct FlushCtx {
   f32x4* part;  // LDS [waves - 1][64]
   int* pflag;   // LDS [waves]: tag of the phase in which the wave last parked a tile
   unsigned tag;
+  int trace_key;
 };
 
 __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
@@ -1073,9 +1080,24 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.part = (f32x4*)(rscale + 16);
   F.pflag = pflag;
   F.tag = tag;
+  F.trace_key = trace_layer;
+  f32x4* resid = F.part + (kWaves - 1) * 64;
+  if (e.epi == EPI_RESID) {
+    const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
+    const int i = lane & 15;
+    for (int r = wave; r < S.R; r += kWaves) {
+      const int row = (S.rb0 + r) * kRowBlock + (lane >> 4) * 4;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (i < e.n && row < e.N) v = ld_ag4(xr, (i * e.N + row) * 4);
+      resid[r * 64 + lane] = v;
+    }
+  }
+  EpiCtx e2 = e;
+  e2.resid = resid;
+  e2.rb0 = S.rb0;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
-  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e, rscale, F, next, next_sk, wave);  // drains its stores
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
 
@@ -1157,6 +1179,8 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.positions = A.positions;
     e.slots = A.slots;
     e.rope = A.rope;
+    e.resid = nullptr;
+    e.rb0 = 0;
     e.ssq_out = A.ssq;
     MatDev M, nxt;
     const float* xin;
@@ -1225,8 +1249,8 @@ size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
   return (size_t)attn_lds_layout(head_dim, cp, dtype == PI_DTYPE_BF16 ? 1 : 2).total;
 }
 
-size_t stage_proj_lds_bytes(int n, int nt) {
-  return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1) * 1024;
+size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
+  return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + r_max) * 1024;
 }
 
 namespace {
