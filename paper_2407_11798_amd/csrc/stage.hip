@@ -161,8 +161,9 @@ struct WaveStream {
   int rb0, R;         // this workgroup's row blocks [rb0, rb0 + R)
   int f0, f1, share;  // this wave's flat range of the workgroup's R * nt tiles; tiles per wave
   int slice, wave;
-  // loader cursor: flat index, absolute row block, tile within the slice
-  int lf, lrb, lt;
+  // loader cursor: flat index, tile within the slice's part of the row block, byte offset of the tile
+  int lf, lt;
+  uint32_t loff;
 };
 
 // Wave-uniform values computed with vector instructions (integer division) are moved back to
@@ -211,7 +212,7 @@ __device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
   S.KT = uni(S.KT); S.nt = uni(S.nt); S.t0 = uni(S.t0); S.NRB = uni(S.NRB);
   S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
   S.slice = uni(S.slice); S.wave = uni(S.wave); S.rb0 = uni(S.rb0); S.R = uni(S.R);
-  S.lf = uni(S.lf); S.lrb = uni(S.lrb); S.lt = uni(S.lt);
+  S.lf = uni(S.lf); S.lt = uni(S.lt); S.loff = (uint32_t)uni((int)S.loff);
 }
 
 template <int DT>
@@ -235,8 +236,8 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   S.f1 = min(total, S.f0 + S.share);
   S.lf = S.f0;
   const int q = uni(S.f0 / S.nt);
-  S.lrb = S.rb0 + q;
   S.lt = S.f0 - q * S.nt;
+  S.loff = (uint32_t)((S.rb0 + q) * S.KT + S.t0 + S.lt) * (uint32_t)kTileBytes;
   stream_make_uniform(S);
 }
 
@@ -250,21 +251,31 @@ struct Ring {
   u32x4 r[kRegs];
 };
 
-// Issue the load of the next tile of the wave's range into slot J.  Branch-free: past the end
-// of the range the load still executes, with out-of-range offsets, and the consumer discards
-// the slot, so the steady-state loop is a single basic block and the loads stay in flight (a
-// branch around a load makes the compiler wait for it at the join).
+// What one pass over the ring does, worked out in scalar registers before the pass, so that every
+// per-slot decision inside it is a comparison of a scalar with the (compile-time) slot number and
+// no cursor is written between slots: the instruction count per tile is what bounds the stream.
+struct PassPlan {
+  int nc;              // the consumer takes slots 0 .. nc-1
+  int ec;              // slot ec-1 holds the last tile of the consumer's current row block
+  int cbaseA, cbaseB;  // slot J's operands start (J < ec ? cbaseA : cbaseB) + J * stride bytes into x
+  int stride;          // bytes of operand slots per tile: 64 n
+  int zoff;            // byte offset of the all-zero operand slots behind x
+  int nl;              // the loader refills slots 0 .. nl-1
+  int el;              // slot el-1 gets the last tile of the loader's current row block
+  uint32_t lbaseA, lbaseB;  // slot J loads the tile at (J < el ? lbaseA : lbaseB) + J * tile bytes
+};
+
+// Issue the load of the wave's next tile into slot J.  The load itself is unconditional: past
+// the end of the range it has out-of-range offsets (the hardware's range check answers with
+// zeros without going to memory) and the consumer never looks at the slot, so the loads of a
+// pass are never inside a branch (a branch around a load makes the compiler wait for it at the
+// join) and stay in flight.
 template <int DT, int UR, int J>
-__device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int lane) {
-  // 0/1 integers in scalar registers rather than booleans: a boolean that also steers a per-lane
-  // select becomes a lane mask, and the cursor arithmetic that depends on it would move to the
-  // vector unit (and the load's scalar operands with it).
-  const int valid = uni(S.lf < S.f1 ? 1 : 0);
-  const int mask = -valid;
-  const int soff = ((S.lrb * S.KT + S.t0 + S.lt) * Ring<DT, UR>::kTileBytes) & mask;
-  // past the end of the range the lanes' offsets lie outside the buffer: the hardware's range
-  // check answers such a load with zeros without going to memory
-  const int voff = ((lane * 16) & mask) | (0x7ffffff0 & ~mask);
+__device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, const WaveStream& S, const PassPlan& P, int lane16) {
+  constexpr int TB = Ring<DT, UR>::kTileBytes;
+  const int mask = J < P.nl ? -1 : 0;
+  const int soff = (int)((J < P.el ? P.lbaseA : P.lbaseB) + (uint32_t)(J * TB)) & mask;
+  const int voff = (lane16 & mask) | (0x7ffffff0 & ~mask);
   const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(S.w, S.bytes);
   if constexpr (DT == PI_DTYPE_BF16) {
     R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
@@ -272,23 +283,52 @@ __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, WaveStream& S, int l
     R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
     R.r[2 * J + 1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff + (1024 & mask), 2);
   }
-  S.lf += 1;
-  const int wrap = uni(S.lt + 1 == S.nt ? 1 : 0);
-  S.lt = (S.lt + 1) * (1 - wrap);
-  S.lrb += wrap;
 }
 
-template <int DT, int UR, int J = 0>
-__device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, int lane) {
-  if constexpr (J < UR) {
-    ring_issue<DT, UR, J>(R, S, lane);
-    ring_prefetch<DT, UR, J + 1>(R, S, lane);
+template <int DT, int UR, int J, int JEND>
+__device__ __forceinline__ void issue_slots(Ring<DT, UR>& R, const WaveStream& S, const PassPlan& P, int lane16) {
+  if constexpr (J < JEND) {
+    ring_issue<DT, UR, J>(R, S, P, lane16);
+    issue_slots<DT, UR, J + 1, JEND>(R, S, P, lane16);
   }
 }
 
+// The loader's part of a pass plan and of the cursor update after the pass (the host guarantees
+// nt >= UR: at most one row block ends in a pass).
+template <int UR>
+__device__ __forceinline__ void plan_loads(PassPlan& P, const WaveStream& S, int tile_bytes) {
+  P.nl = max(0, min(UR, S.f1 - S.lf));
+  P.el = S.nt - S.lt;
+  P.lbaseA = S.loff;
+  P.lbaseB = S.loff + (uint32_t)(S.KT - S.nt) * (uint32_t)tile_bytes;
+}
+__device__ __forceinline__ void advance_loads(WaveStream& S, const PassPlan& P, int tile_bytes) {
+  S.lf += P.nl;
+  if (P.nl > 0 && P.el <= P.nl) {
+    S.lt = P.nl - P.el;
+    S.loff = P.lbaseB + (uint32_t)(P.nl * tile_bytes);
+  } else {
+    S.lt += P.nl;
+    S.loff += (uint32_t)(P.nl * tile_bytes);
+  }
+}
+
+// Fill the (empty) ring with the first tiles of the wave's range.
+template <int DT, int UR>
+__device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, int lane) {
+  constexpr int TB = Ring<DT, UR>::kTileBytes;
+  PassPlan P;
+  plan_loads<UR>(P, S, TB);
+  issue_slots<DT, UR, 0, UR>(R, S, P, lane * 16);
+  advance_loads(S, P, TB);
+}
+
 // ---- activation staging (once per phase and workgroup) ---------------------------------------
-// LDS slot (tt, g, i) holds x[i][32(t0+tt) + 8g + 0..7] (times the gain): bf16 model: 16 B of hi
-// parts at the slot, 16 B of lo parts n_slots further; fp32 model: 32 B of floats.
+// LDS slot (tt, g, i) holds x[i][32(t0+tt) + 8g + 0..7] (times the gain), in two 16-byte halves
+// lo_off = (nt + 1) * 4 * n slots apart: bf16 model: the hi parts and the lo parts of the eight
+// values; fp32 model: the first four and the last four floats.  The slots of one more tile
+// (tt = nt) are all zero in both halves: the streaming loop multiplies by them where a slot of
+// its ring holds nothing.
 // Also computes 1/sqrt(mean x^2 + eps) per token (scaled phases) from the per-16-column partial
 // sums of squares, summed in a fixed order; its loads are issued together with the activation
 // loads so the whole staging costs one memory round trip.  Ends with a workgroup barrier.
@@ -296,8 +336,12 @@ template <int DT>
 __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
                         const float* ssq, int n_blocks, float eps, float* red, float* rscale) {
   const int items = nt * n * 4;
-  const int n_slots = nt * 4 * n;
+  const int lo_off = (nt + 1) * 4 * n;
   const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
+  for (int z = nt * 4 * n + threadIdx.x; z < lo_off; z += kThreads) {
+    ((uint4*)lds)[z] = make_uint4(0u, 0u, 0u, 0u);
+    ((uint4*)lds)[lo_off + z] = make_uint4(0u, 0u, 0u, 0u);
+  }
   constexpr int kGroups = kThreads / 16;
   float ssum = 0.0f;
   if (ssq) {
@@ -365,10 +409,10 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
           lo[j] = (uint32_t)l0 | ((uint32_t)l1 << 16);
         }
         ((uint4*)lds)[slot[q]] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-        ((uint4*)lds)[slot[q] + n_slots] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        ((uint4*)lds)[slot[q] + lo_off] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
       } else {
-        ((float4*)lds)[2 * slot[q]] = make_float4(v[0], v[1], v[2], v[3]);
-        ((float4*)lds)[2 * slot[q] + 1] = make_float4(v[4], v[5], v[6], v[7]);
+        ((float4*)lds)[slot[q]] = make_float4(v[0], v[1], v[2], v[3]);
+        ((float4*)lds)[slot[q] + lo_off] = make_float4(v[4], v[5], v[6], v[7]);
       }
     }
   }
@@ -553,17 +597,16 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
 }
 
 // ---- the MFMA inner step ----------------------------------------------------------------------
+// b0 / b1: LDS addresses of the lane's two operand halves for the tile.
 template <int DT, int UR, int J>
-__device__ __forceinline__ void mma_tile(const Ring<DT, UR>& R, const char* lds, int n_slots, int bslot, f32x4& acc) {
+__device__ __forceinline__ void mma_tile(const Ring<DT, UR>& R, const char* b0, const char* b1, f32x4& acc) {
   if constexpr (DT == PI_DTYPE_BF16) {
-    const u32x4* b = (const u32x4*)lds + bslot;
     const bf16x8 av = __builtin_bit_cast(bf16x8, R.r[J]);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b[0]), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, b[n_slots]), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, *(const u32x4*)b0), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, *(const u32x4*)b1), acc, 0, 0, 0);
   } else {
-    const f32x4* b = (const f32x4*)lds + 2 * bslot;
     const f32x4 w0 = __builtin_bit_cast(f32x4, R.r[2 * J]), w1 = __builtin_bit_cast(f32x4, R.r[2 * J + 1]);
-    const f32x4 x0 = b[0], x1 = b[1];
+    const f32x4 x0 = *(const f32x4*)b0, x1 = *(const f32x4*)b1;
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], x0[q], acc, 0, 0, 0);
 #pragma unroll
@@ -572,37 +615,48 @@ __device__ __forceinline__ void mma_tile(const Ring<DT, UR>& R, const char* lds,
 }
 
 struct ConsumeState {
-  int f, rb, t;
+  int f, rb, t;  // flat cursor, absolute row block, tile within the slice's part of it
   f32x4 acc;
-  bool pending;
+  int pending;   // a row block ended in the last pass: its tile is pacc, its number prb
   int prb;
   f32x4 pacc;
 };
 
-// One pass over the ring, branch-free.  The host guarantees nt >= UR, so at most one row block
-// ends inside a pass; its tile is set aside (pacc) and flushed after the pass.
-template <int DT, int UR, int J>
-__device__ __forceinline__ void consume_step(Ring<DT, UR>& R, WaveStream& S, ConsumeState& C, const char* lds,
-                                             int n, int lane) {
-  if constexpr (J < UR) {
-    const int valid = uni(C.f < S.f1 ? 1 : 0);
-    const int g = lane >> 4, ln = min(lane & 15, n - 1);
-    f32x4 acc2 = C.acc;
-    mma_tile<DT, UR, J>(R, lds, S.nt * 4 * n, (C.t * 4 + g) * n + ln, acc2);
-    ring_issue<DT, UR, J>(R, S, lane);
-    const int end_rb = uni(valid && C.t + 1 == S.nt ? 1 : 0);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float a = valid ? acc2[q] : C.acc[q];
-      C.pacc[q] = end_rb ? a : C.pacc[q];
-      C.acc[q] = end_rb ? 0.0f : a;
+// Per-lane constants of a pass.
+struct PassLane {
+  int lane16;      // byte offset of the lane's 16 bytes in a weight tile
+  const char* b0;  // the lane's operand halves of tile 0
+  const char* b1;
+};
+
+// A group of slots is consumed in a straight line behind one wave-uniform branch: a slot past the
+// consumer's end multiplies by the all-zero operand slots.
+template <int DT, int UR, int J, int JEND>
+__device__ __forceinline__ void consume_slots(const Ring<DT, UR>& R, ConsumeState& C, const PassPlan& P,
+                                              const PassLane& PLn) {
+  if constexpr (J < JEND) {
+    const int off = J < P.nc ? (J < P.ec ? P.cbaseA : P.cbaseB) + J * P.stride : P.zoff;
+    mma_tile<DT, UR, J>(R, PLn.b0 + off, PLn.b1 + off, C.acc);
+    if (__builtin_expect(J == P.ec - 1 && J < P.nc, 0)) {  // the row block's last tile: set its sum aside
+      C.pacc = C.acc;
+      C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    C.prb = end_rb ? C.rb : C.prb;
-    C.pending = C.pending || end_rb;
-    C.f += valid;
-    C.t = (C.t + valid) * (1 - end_rb);
-    C.rb += end_rb;
-    consume_step<DT, UR, J + 1>(R, S, C, lds, n, lane);
+    consume_slots<DT, UR, J + 1, JEND>(R, C, P, PLn);
+  }
+}
+
+// One pass over the ring, in groups of kGroup slots: the group's tiles are consumed (skipped as a
+// whole when the consumer has nothing for the group), then the group's slots are refilled,
+// outside any branch.
+constexpr int kGroup = 8;
+template <int DT, int UR, int J0>
+__device__ __forceinline__ void ring_pass(Ring<DT, UR>& R, const WaveStream& S, ConsumeState& C, const PassPlan& P,
+                                          const PassLane& PLn) {
+  if constexpr (J0 < UR) {
+    constexpr int J1 = J0 + kGroup < UR ? J0 + kGroup : UR;
+    if (J0 < P.nc) consume_slots<DT, UR, J0, J1>(R, C, P, PLn);
+    issue_slots<DT, UR, J0, J1>(R, S, P, PLn.lane16);
+    ring_pass<DT, UR, J1>(R, S, C, P, PLn);
   }
 }
 
@@ -612,23 +666,42 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
                                               const char* lds, int n, int lane, const EpiCtx& e,
                                               const float* rscale, const FlushCtx& F, const MatDev* next,
                                               int next_sk, int wave) {
+  constexpr int TB = Ring<DT, UR>::kTileBytes;
   ConsumeState C;
   C.f = S.f0;
   const int q0 = uni(S.f0 / S.nt);
   C.rb = S.rb0 + q0;
   C.t = S.f0 - q0 * S.nt;
   C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  C.pending = false;
+  C.pending = 0;
   C.prb = 0;
   C.pacc = C.acc;
+  PassLane PLn;
+  PLn.lane16 = lane * 16;
+  PLn.b0 = lds + ((lane >> 4) * n + min(lane & 15, n - 1)) * 16;
+  PLn.b1 = PLn.b0 + (S.nt + 1) * 64 * n;
   while (C.f < S.f1) {
-    do {  // hot loop: passes without a row-block end
-      consume_step<DT, UR, 0>(R, S, C, lds, n, lane);
-    } while (!C.pending && C.f < S.f1);
-    if (C.pending) {
-      flush_rowblock(A, S, S_k, C.prb, C.pacc, lane, e, rscale, F);
-      C.pending = false;
+    PassPlan P;
+    P.stride = 64 * n;
+    P.zoff = S.nt * P.stride;
+    P.nc = min(UR, S.f1 - C.f);
+    P.ec = S.nt - C.t;
+    P.cbaseA = C.t * P.stride;
+    P.cbaseB = -P.ec * P.stride;
+    plan_loads<UR>(P, S, TB);
+    ring_pass<DT, UR, 0>(R, S, C, P, PLn);
+    advance_loads(S, P, TB);
+    C.f += P.nc;
+    if (P.ec <= P.nc) {  // a row block ended in this pass
+      flush_rowblock(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F);
+      C.rb += 1;
+      C.t = P.nc - P.ec;
+    } else {
+      C.t += P.nc;
     }
+    C.f = uni(C.f);
+    C.t = uni(C.t);
+    C.rb = uni(C.rb);
   }
   if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale, F);  // range ends inside a row block
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
@@ -1073,7 +1146,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
                                            const MatDev* next, int next_sk, int wave, int trace_layer = -1) {
   stream_make_uniform(S);
-  const size_t xbytes = (size_t)S.nt * 128 * A.n;
+  const size_t xbytes = (size_t)(S.nt + 1) * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
   FlushCtx F;
@@ -1250,7 +1323,7 @@ size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
 }
 
 size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
-  return (size_t)nt * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + r_max) * 1024;
+  return (size_t)(nt + 1) * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + r_max) * 1024;
 }
 
 namespace {
