@@ -200,6 +200,12 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
  * O, gate/up, down (layer boundary).  count <= 5 * n_layers + 8.  Blocking. */
 int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count);
 int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64_t count);
+/* Debug hook: per-workgroup timestamps of one phase.  `key` = layer * 8 + phase (0 QKV, 1
+ * attention, 2 O, 3 gate/up, 4 down) selects the phase later runs record (-1: none).  With
+ * dst_host non-null, first copies the last recording to the host: grid x 8 values of the 100 MHz
+ * clock per workgroup: [0] phase start, [1] inputs staged, [2] wave 0 done streaming, [3] before
+ * the barrier, [4] workgroup arrived at the barrier, [5] barrier passed.  Blocking. */
+int32_t pi_debug_wgtrace(pi_model* m, int32_t key, uint64_t* dst_host);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,7 @@ EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
     "pi_stage_forward", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
-    "pi_debug_read_scratch", "pi_debug_read_trace",
+    "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
 ]
 
 

@@ -1,0 +1,61 @@
+"""The C-ABI library loads and exports every function the header declares (no compute calls:
+these tests run without a GPU), the binding's list matches the header, and argument checks that
+need no device reject bad calls with the documented status codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_11798_amd as pi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pipeinfer.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)  # comments mention function names too
+    return sorted(set(re.findall(r"\b(pi_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary_calls():
+    names = declared_functions()
+    for required in ("pi_model_load", "pi_kv_alloc", "pi_stage_forward", "pi_verify_greedy", "pi_kv_rollback"):
+        assert required in names
+
+
+def test_library_exports_every_declared_function():
+    lib = pi.lib()
+    missing = [n for n in declared_functions() if not hasattr(lib, n)]
+    assert not missing, "declared in include/pipeinfer.h but not exported: %s" % missing
+
+
+def test_binding_lists_every_declared_function():
+    assert sorted(pi.binding.EXPORTS) == declared_functions()
+
+
+def test_status_strings():
+    lib = pi.lib()
+    lib.pi_strerror.restype = ctypes.c_char_p
+    lib.pi_strerror.argtypes = [ctypes.c_int32]
+    seen = set()
+    for code in (0, 1, -1, -2, -3, -4, -5, -6):
+        s = lib.pi_strerror(code)
+        assert s and s != b"unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.pi_strerror(12345) == b"unknown status"
+
+
+def test_null_and_shape_arguments_are_refused_without_touching_a_device():
+    lib = pi.lib()
+    out = ctypes.c_void_p()
+    assert lib.pi_model_load(None, ctypes.byref(out)) == pi.binding.PI_E_ARG
+    cfg = pi.binding.PiModelConfig(n_layers=1, d_model=48, n_q_heads=2, n_kv_heads=2, head_dim=24, ffn=64,
+                                   vocab=64, rms_eps=1e-5, rope_base=10000.0, dtype=0, max_pos=16)
+    assert lib.pi_model_load(ctypes.byref(cfg), ctypes.byref(out)) == pi.binding.PI_E_SHAPE  # head_dim 24
+    assert out.value is None
+    assert lib.pi_stage_forward(None, None, None, 0, 1, None, None, None, None, None, None) == pi.binding.PI_E_ARG
+    assert lib.pi_verify_greedy(None, None, 1, None, 16, 0, None, None, None) == pi.binding.PI_E_ARG
+    assert lib.pi_kv_rollback(None, None, 1, None, None, None) == pi.binding.PI_E_ARG
