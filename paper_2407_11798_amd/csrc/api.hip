@@ -84,17 +84,22 @@ hipError_t dev_alloc(pi_model* m, T** p, size_t bytes, bool zero) {
 }
 
 // Column slices for one projection: the smallest power of two that divides the tile count and
-// the grid and lets the staged activations of n tokens fit the LDS budget.  0 = impossible.
+// the grid, lets the phase's LDS needs for n tokens fit the budget and -- where the matrix has
+// fewer row blocks than the grid has workgroups -- gives every workgroup a row block, as long as
+// a slice keeps at least 16 tiles per row block.  0 = impossible.
 int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n) {
   const int ov = m->sk_override[phase];
+  int fits = 0;
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
     if (w.KT % sk || m->grid % sk) continue;
     const int gs = m->grid / sk;
     if (stage_proj_lds_bytes(n, w.KT / sk, (w.NRB + gs - 1) / gs) > kProjLdsBudget) continue;
     if (ov > sk) continue;  // an override asks for at least this many slices
-    return sk;
+    if (fits && w.KT / sk < 16) break;  // more slices would starve the ring
+    fits = sk;
+    if ((long)w.NRB * sk >= m->grid) break;
   }
-  return 0;
+  return fits;
 }
 
 struct StagePlan {

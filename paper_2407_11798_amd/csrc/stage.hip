@@ -490,9 +490,9 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
     if (live && row < e.N) {
       const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
       const int off = (i * e.N + row) * 4;
-      // the residual rows were copied to LDS when the phase began: a load issued here would queue
-      // behind the next phase's weight requests of the waves that are already done
-      const f32x4 x = e.resid[(rb - e.rb0) * 64 + lane] + acc;
+      // the residual rows were copied to LDS when the phase began (unless the workgroup owns too
+      // many row blocks): a load issued here would queue behind the weight requests in flight
+      const f32x4 x = (e.resid ? e.resid[(rb - e.rb0) * 64 + lane] : ld_ag4(xr, off)) + acc;
       st_ag4(xr, off, x);
       s = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
     }
@@ -521,6 +521,7 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
 // pattern, which no sum can produce); slice 0 polls them (bounded), adds them in slice order,
 // marks them empty again for the next use and runs the epilogue.
 constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;
+constexpr int kMaxResidBlocks = 8;  // residual rows of at most this many row blocks per workgroup are kept in LDS
 
 struct FlushCtx {
   f32x4* part;  // LDS [waves - 1][64]
@@ -1155,7 +1156,9 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.tag = tag;
   F.trace_key = trace_layer;
   f32x4* resid = F.part + (kWaves - 1) * 64;
-  if (e.epi == EPI_RESID) {
+  const int Gs = uni((int)gridDim.x / S_k);
+  const bool stage_resid = e.epi == EPI_RESID && uni((S.NRB + Gs - 1) / Gs) <= kMaxResidBlocks;  // as sized by the host
+  if (stage_resid) {
     const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
     const int i = lane & 15;
     for (int r = wave; r < S.R; r += kWaves) {
@@ -1166,7 +1169,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
     }
   }
   EpiCtx e2 = e;
-  e2.resid = resid;
+  e2.resid = stage_resid ? resid : nullptr;
   e2.rb0 = S.rb0;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
@@ -1323,6 +1326,7 @@ size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
 }
 
 size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
+  if (r_max > kMaxResidBlocks) r_max = 0;  // too many row blocks per workgroup: residual rows are read in place
   return (size_t)(nt + 1) * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + r_max) * 1024;
 }
 

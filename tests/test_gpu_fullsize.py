@@ -133,3 +133,110 @@ def test_llama7b_concurrent_runs_with_cancellation(llama7b):
     ref = snapshot.reshape(img.shape)
     assert np.array_equal(np.delete(img, np.s_[T:T + best[1]], axis=3), np.delete(ref, np.s_[T:T + best[1]], axis=3))
     assert best[1] == 0 or img[:, :, :, T:T + best[1]].any()
+
+
+def test_tinyllama_decode_steps_match_oracle():
+    """TinyLlama-shaped draft model (grouped-query attention, 4 KV heads x 64): single-token decode
+    steps at short and long prefixes, the generator side's workload."""
+    sh = synth.SHAPES["tinyllama"]
+    g = _load("tinyllama_decode")
+    m = gpu_loader.load_model(sh, g["seed"])
+    cols = np.asarray(g["cols"])
+    try:
+        for T_str, rec in g["runs"].items():
+            T = int(T_str)
+            kv = pi.KVCache(m, T + 64)
+            gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+            toks = np.asarray(rec["tokens"], dtype=np.int32)
+            assert np.array_equal(toks, synth.tokens_host(sh, g["seed"], 1, synth.T_DRAFT, salt=T))
+            run = gpu_loader.make_run(synth.linear_run(1, T), toks)
+            logits = torch.zeros((1, sh.vocab), device="cuda")
+            status = torch.zeros(2, dtype=torch.int32, device="cuda")
+            pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+            worst = _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+            print("T=%d worst sampled logit error / row max: %.2e" % (T, worst))
+            kv.free()
+    finally:
+        m.free()
+
+
+def test_llama70b_shaped_layer_matches_oracle():
+    """One decoder layer plus the LM head of the Llama-70B shape (d 8192, 64 query / 8 KV heads,
+    FFN 28672) over 2048 prefix cells, batches of 1 and 16 tokens: the widest matrices, the most
+    column slices and the largest grouped-query fan-out the kernels meet."""
+    import dataclasses
+    g = _load("llama70b_layer")
+    sh = dataclasses.replace(synth.SHAPES["llama70b"], n_layers=g["n_layers"], name="llama70b_l1")
+    m = gpu_loader.load_model(sh, g["seed"])
+    T = g["prefix"]
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    try:
+        for n_str, rec in g["runs"].items():
+            n = int(n_str)
+            toks = np.asarray(rec["tokens"], dtype=np.int32)
+            assert np.array_equal(toks, synth.tokens_host(sh, g["seed"], n, synth.T_DRAFT, salt=n))
+            run = gpu_loader.make_run(synth.linear_run(n, T), toks)
+            logits = torch.zeros((n, sh.vocab), device="cuda")
+            status = torch.zeros(2, dtype=torch.int32, device="cuda")
+            pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+            worst = _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+            print("n=%d worst sampled logit error / row max: %.2e" % (n, worst))
+            pi.kv_rollback(kv, run.slots, n)
+    finally:
+        kv.free()
+        m.free()
+
+
+def test_llama70b_shaped_stage_slice_properties():
+    """A 4-layer model of the 70B shape run as two 2-layer pipeline stages must equal the single
+    4-layer stage bit for bit, and a 4-token batch must agree with four sequential single-token
+    runs within the bf16 tolerance (no oracle at this size: properties that hold at any size)."""
+    import dataclasses
+    sh = dataclasses.replace(synth.SHAPES["llama70b"], n_layers=4, name="llama70b_l4")
+    m = gpu_loader.load_model(sh, 0)
+    T, n = 2048, 4
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, 0, T)
+    toks = synth.tokens_host(sh, 0, n, synth.T_DRAFT, salt=n)
+    try:
+        run = gpu_loader.make_run(synth.linear_run(n, T), toks)
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        whole = torch.zeros((n, sh.vocab), device="cuda")
+        pi.stage_forward(m, kv, run, 0, 4, logits_out=whole, run_status=status)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pi.PI_OK, 4]
+        pi.kv_rollback(kv, run.slots, n)
+        hidden = torch.zeros((n, sh.d_model), device="cuda")
+        split = torch.zeros((n, sh.vocab), device="cuda")
+        pi.stage_forward(m, kv, run, 0, 2, hidden_out=hidden, run_status=status)
+        pi.stage_forward(m, kv, run, 2, 4, hidden_in=hidden, logits_out=split, run_status=status)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pi.PI_OK, 4]
+        assert torch.equal(whole, split)
+        pi.kv_rollback(kv, run.slots, n)
+        # sequential single-token steps, each committed before the next
+        seq = []
+        for i in range(n):
+            r1 = gpu_loader.make_run(synth.linear_run(1, T + i), toks[i:i + 1])
+            lg = torch.zeros((1, sh.vocab), device="cuda")
+            pi.stage_forward(m, kv, r1, 0, 4, logits_out=lg, run_status=status)
+            acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+            res = torch.tensor([1, 0], dtype=torch.int32, device="cuda")
+            pi.kv_rollback(kv, r1.slots, 1, acc, res)
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [pi.PI_OK, 4]
+            seq.append(lg.cpu().numpy()[0])
+        seq = np.stack(seq)
+        w = whole.cpu().numpy()
+        err = np.max(np.abs(w - seq), axis=1) / np.max(np.abs(seq), axis=1)
+        assert err.max() <= 2e-2, "batch vs sequential: %s" % err
+        assert len(kv) == T + n
+    finally:
+        kv.free()
+        m.free()
