@@ -428,6 +428,13 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
   __syncthreads();
 }
 
+// Sum of four squares as one explicit chain of fused multiply-adds: the residual stream's sums of
+// squares are produced at two places (stage input, residual epilogue) and must not depend on
+// which multiply-adds the compiler would choose to fuse at each.
+__device__ __forceinline__ float sum_sq4(float a, float b, float c, float d) {
+  return __builtin_fmaf(d, d, __builtin_fmaf(c, c, __builtin_fmaf(b, b, a * a)));
+}
+
 // ---- epilogues --------------------------------------------------------------------------------
 struct EpiCtx {
   int epi;  // Epilogue kind
@@ -494,7 +501,7 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
       // many row blocks): a load issued here would queue behind the weight requests in flight
       const f32x4 x = (e.resid ? e.resid[(rb - e.rb0) * 64 + lane] : ld_ag4(xr, off)) + acc;
       st_ag4(xr, off, x);
-      s = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+      s = sum_sq4(x[0], x[1], x[2], x[3]);
     }
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
@@ -1126,7 +1133,7 @@ __device__ void embed_phase(const StageArgs& A) {
       }
       st_ag4(rsrc_of(A.x), (i * A.d + c) * 4, f32x4{v[0], v[1], v[2], v[3]});
     }
-    float s = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    float s = sum_sq4(v[0], v[1], v[2], v[3]);
     s += __shfl_xor(s, 1);
     s += __shfl_xor(s, 2);
     if (live && (threadIdx.x & 3) == 0) st_ag(A.ssq + (c / 16) * 16 + i, s);
