@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cancel", action="store_true", help="skip the cancellation latency trials")
+    ap.add_argument("--slice-layers", type=int, default=0,
+                    help="also time a pipeline stage's share: the first this-many layers as one stage call")
     ap.add_argument("--calibrate-copy", type=int, default=0,
                     help="only run a device copy of this many MiB (known traffic for counter calibration)")
     args = ap.parse_args()
@@ -149,7 +151,19 @@ def main():
         kv.set_len(T)  # an accepted draft token would have advanced the prefix; keep the workload fixed
         ms = wall * 1e3 / args.steps
         ab = algorithmic_bytes(shape, layer_bytes, lm_bytes, T, n)
+        slice_ms = None
+        if args.slice_layers:
+            hidden = torch.empty((n, shape.d_model), device="cuda")
+            sev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+            for e0, e1 in sev:
+                e0.record()
+                pi.stage_forward(model, kv, run, 0, args.slice_layers, hidden_out=hidden, run_status=status)
+                e1.record()
+                pi.kv_rollback(kv, run.slots, n)
+            torch.cuda.synchronize()
+            slice_ms = sum(e0.elapsed_time(e1) for e0, e1 in sev) / args.steps
         per_batch[str(n)] = {
+            "slice_layers": args.slice_layers or None, "slice_forward_ms": slice_ms,
             "verified_tokens_per_s": n / (ms * 1e-3), "ms_per_step": ms, "forward_ms": fwd_ms,
             "per_layer_us": fwd_ms * 1e3 / (shape.n_layers + lm_bytes / layer_bytes),
             "algorithmic_GB": ab / 1e9, "achieved_GBps": ab / 1e9 / (fwd_ms * 1e-3),
