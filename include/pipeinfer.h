@@ -188,9 +188,11 @@ int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t
 
 const char* pi_strerror(int32_t status);
 
-/* Tuning hook (not needed for correct use): ask for at least `s_k` column slices in one
- * projection phase (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head); 0 restores the built-in
- * choice.  The library still rounds up to a split the tile count, grid and LDS allow. */
+/* Tuning hook (not needed for correct use): phase 0..4 (QKV, O, gate/up, down, LM head): ask
+ * for at least `s_k` column slices in that projection phase; 0 restores the built-in choice, and
+ * the library still rounds up to a split the tile count, grid and LDS allow.  phase 5: s_k != 0
+ * makes later runs record the barrier timestamps pi_debug_read_trace returns (off by default:
+ * reading the clock at every barrier costs time). */
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],

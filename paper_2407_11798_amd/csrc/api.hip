@@ -31,6 +31,7 @@ struct pi_model {
   StageSync* sync = nullptr;
   unsigned long long* trace = nullptr;  // timestamps of the barriers of the last run
   int trace_cap = 0;
+  bool trace_on = false;
   unsigned long long* wgtrace = nullptr;
   int wgtrace_layer = -1;
   int grid = 0;  // workgroups of the stage kernel = compute units
@@ -375,8 +376,9 @@ int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
 }
 
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
-  if (!m || phase < 0 || phase > 4 || s_k < 0) return PI_E_ARG;
-  m->sk_override[phase] = s_k;
+  if (!m || phase < 0 || phase > 5 || s_k < 0) return PI_E_ARG;
+  if (phase == 5) m->trace_on = s_k != 0;
+  else m->sk_override[phase] = s_k;
   return PI_OK;
 }
 
@@ -624,7 +626,7 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.timeout_ticks = kBarrierTimeoutTicks;
   a.epoch_base = m->epoch;
   m->epoch += (unsigned)(5 * (layer_end - layer_begin) + 4);  // every barrier this launch can reach
-  a.trace = m->trace;
+  a.trace = m->trace_on ? m->trace : nullptr;  // a clock read per barrier is not free: only on request
   a.trace_cap = m->trace_cap;
   a.wgtrace = m->wgtrace_layer >= 0 ? m->wgtrace : nullptr;
   a.wgtrace_layer = m->wgtrace_layer;

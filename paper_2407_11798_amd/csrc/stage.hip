@@ -64,8 +64,26 @@ __device__ __forceinline__ void st_ag2(__amdgpu_buffer_rsrc_t r, int byte_off, f
 // all earlier memory operations of this wave have completed (stores are visible at agent scope
 // because they were issued with agent scope)
 __device__ __forceinline__ void wave_drain() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); }
+// the same wait as an instruction the compiler's own counter tracking takes into account
+// (vmcnt = 0; the export and LDS/scalar counters are left alone)
+__device__ __forceinline__ void wave_settle() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 __device__ __forceinline__ void wg_mark(const StageArgs& A, int l, int ev) {
   if (A.wgtrace && l == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + ev] = wall_clock64();  // l: layer * 8 + phase kind
+}
+
+// Bounded waits read the clock only once a wait has lasted a while: a clock read is a scalar
+// memory round trip, which the fast path of every barrier and reduction would otherwise pay.
+struct Deadline {
+  unsigned long long t0 = 0;
+};
+__device__ __forceinline__ bool deadline_passed(Deadline& d, unsigned spin, unsigned long long limit) {
+  if ((spin & 255u) != 255u) return false;
+  const unsigned long long now = wall_clock64();
+  if (d.t0 == 0) {
+    d.t0 = now;
+    return false;
+  }
+  return now - d.t0 > limit;
 }
 
 // ---- grid barrier ---------------------------------------------------------------------------
@@ -91,7 +109,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
     if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const __amdgpu_buffer_rsrc_t fr = rsrc_of(sy->flags);
     const int G = gridDim.x;
-    const unsigned long long t0 = wall_clock64();
+    Deadline dl;
     int ok = 1;
     for (unsigned spin = 0;; ++spin) {
       bool all = true;
@@ -104,7 +122,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
       }
       if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
       __builtin_amdgcn_s_sleep(1);
-      if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+      if (deadline_passed(dl, spin, A.timeout_ticks)) {
         ok = 0;
         break;
       }
@@ -127,7 +145,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
           const unsigned d = __hip_atomic_load(&sy->decision, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           if ((int)(d - bc.epoch) >= 0) break;
           __builtin_amdgcn_s_sleep(1);
-          if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+          if (deadline_passed(dl, spin, A.timeout_ticks)) {
             ok = 0;
             break;
           }
@@ -283,6 +301,10 @@ __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, const WaveStream& S,
     R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
     R.r[2 * J + 1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff + (1024 & mask), 2);
   }
+  // Ring loads must be issued in slot order: the counter wait before slot J is consumed is "all but
+  // the newest U - 1", and the instruction scheduler is otherwise free to reorder independent loads
+  // (the oldest slot then looks newest and the compiler waits for the whole ring).
+  asm volatile("" ::: "memory");
 }
 
 template <int DT, int UR, int J, int JEND>
@@ -550,14 +572,14 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
       if (lane == 0) __hip_atomic_store(F.pflag + S.wave, (int)F.tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       return;
     }
-    const unsigned long long t0 = wall_clock64();
+    Deadline dl;
     for (unsigned spin = 0;; ++spin) {
       int missing = 0;
       for (int w = first + 1; w <= last; ++w)
         missing |= __hip_atomic_load(F.pflag + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != (int)F.tag;
       if (!uni(missing)) break;
       __builtin_amdgcn_s_sleep(1);
-      if ((spin & 63) == 63 && wall_clock64() - t0 > A.timeout_ticks) {
+      if (deadline_passed(dl, spin, A.timeout_ticks)) {
         if (lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
       }
@@ -573,7 +595,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
       return;
     }
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
-    const unsigned long long t0 = wall_clock64();
+    Deadline dl;
     for (int base = 1; base < S_k; base += 8) {  // slice 0 is this workgroup
       u32x4 t[8];
       int off[8];
@@ -587,7 +609,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
         for (int q = 0; q < 8; ++q) ready = ready && (t[q][0] != kEmptyWord || t[q][1] != kEmptyWord);
         if (__builtin_amdgcn_ballot_w64(live && !ready) == 0) break;
         __builtin_amdgcn_s_sleep(1);
-        if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+        if (deadline_passed(dl, spin, A.timeout_ticks)) {
           if (lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           break;
         }
@@ -605,26 +627,12 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
 }
 
 // ---- the MFMA inner step ----------------------------------------------------------------------
-// b0 / b1: LDS addresses of the lane's two operand halves for the tile.
-template <int DT, int UR, int J>
-__device__ __forceinline__ void mma_tile(const Ring<DT, UR>& R, const char* b0, const char* b1, f32x4& acc) {
-  if constexpr (DT == PI_DTYPE_BF16) {
-    const bf16x8 av = __builtin_bit_cast(bf16x8, R.r[J]);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, *(const u32x4*)b0), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, *(const u32x4*)b1), acc, 0, 0, 0);
-  } else {
-    const f32x4 w0 = __builtin_bit_cast(f32x4, R.r[2 * J]), w1 = __builtin_bit_cast(f32x4, R.r[2 * J + 1]);
-    const f32x4 x0 = *(const f32x4*)b0, x1 = *(const f32x4*)b1;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], x0[q], acc, 0, 0, 0);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[q], x1[q], acc, 0, 0, 0);
-  }
-}
-
 struct ConsumeState {
   int f, rb, t;  // flat cursor, absolute row block, tile within the slice's part of it
-  f32x4 acc;
+  // Two accumulators, one per operand half (bf16: hi and lo parts of the activations; fp32: first
+  // and last four columns of the tile): two independent chains of matrix instructions instead of
+  // one in which every instruction waits for the one before.  Their sum is the row block's tile.
+  f32x4 acc0, acc1;
   int pending;   // a row block ended in the last pass: its tile is pacc, its number prb
   int prb;
   f32x4 pacc;
@@ -637,32 +645,56 @@ struct PassLane {
   const char* b1;
 };
 
-// A group of slots is consumed in a straight line behind one wave-uniform branch: a slot past the
-// consumer's end multiplies by the all-zero operand slots.
-template <int DT, int UR, int J, int JEND>
-__device__ __forceinline__ void consume_slots(const Ring<DT, UR>& R, ConsumeState& C, const PassPlan& P,
+// A group of slots is consumed in a straight line behind one wave-uniform branch.  All operand
+// reads of the group are issued first and the matrix instructions follow, so the LDS latency is
+// paid once per group rather than twice per tile; a slot past the consumer's end multiplies by
+// the all-zero operand slots.
+template <int DT, int UR, int J0, int J1>
+__device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeState& C, const PassPlan& P,
                                               const PassLane& PLn) {
-  if constexpr (J < JEND) {
+  constexpr int NG = J1 - J0;
+  u32x4 x0[NG], x1[NG];
+#pragma unroll
+  for (int j = 0; j < NG; ++j) {
+    const int J = J0 + j;
     const int off = J < P.nc ? (J < P.ec ? P.cbaseA : P.cbaseB) + J * P.stride : P.zoff;
-    mma_tile<DT, UR, J>(R, PLn.b0 + off, PLn.b1 + off, C.acc);
-    if (__builtin_expect(J == P.ec - 1 && J < P.nc, 0)) {  // the row block's last tile: set its sum aside
-      C.pacc = C.acc;
-      C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    x0[j] = *(const u32x4*)(PLn.b0 + off);
+    x1[j] = *(const u32x4*)(PLn.b1 + off);
+  }
+#pragma unroll
+  for (int j = 0; j < NG; ++j) {
+    const int J = J0 + j;
+    if constexpr (DT == PI_DTYPE_BF16) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, R.r[J]);
+      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j]), C.acc0, 0, 0, 0);
+      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j]), C.acc1, 0, 0, 0);
+    } else {
+      const f32x4 w0 = __builtin_bit_cast(f32x4, R.r[2 * J]), w1 = __builtin_bit_cast(f32x4, R.r[2 * J + 1]);
+      const f32x4 a0 = __builtin_bit_cast(f32x4, x0[j]), a1 = __builtin_bit_cast(f32x4, x1[j]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], a0[q], C.acc0, 0, 0, 0);
+        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[q], a1[q], C.acc1, 0, 0, 0);
+      }
     }
-    consume_slots<DT, UR, J + 1, JEND>(R, C, P, PLn);
+    if (__builtin_expect(J == P.ec - 1 && J < P.nc, 0)) {  // the row block's last tile: set its sum aside
+      C.pacc = C.acc0 + C.acc1;
+      C.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
+      C.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
   }
 }
 
 // One pass over the ring, in groups of kGroup slots: the group's tiles are consumed (skipped as a
 // whole when the consumer has nothing for the group), then the group's slots are refilled,
 // outside any branch.
-constexpr int kGroup = 8;
+constexpr int kGroup = 4;
 template <int DT, int UR, int J0>
 __device__ __forceinline__ void ring_pass(Ring<DT, UR>& R, const WaveStream& S, ConsumeState& C, const PassPlan& P,
                                           const PassLane& PLn) {
   if constexpr (J0 < UR) {
     constexpr int J1 = J0 + kGroup < UR ? J0 + kGroup : UR;
-    if (J0 < P.nc) consume_slots<DT, UR, J0, J1>(R, C, P, PLn);
+    if (J0 < P.nc) consume_group<DT, UR, J0, J1>(R, C, P, PLn);
     issue_slots<DT, UR, J0, J1>(R, S, P, PLn.lane16);
     ring_pass<DT, UR, J1>(R, S, C, P, PLn);
   }
@@ -680,14 +712,18 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   const int q0 = uni(S.f0 / S.nt);
   C.rb = S.rb0 + q0;
   C.t = S.f0 - q0 * S.nt;
-  C.acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  C.acc0 = C.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
   C.pending = 0;
   C.prb = 0;
-  C.pacc = C.acc;
+  C.pacc = C.acc0;
   PassLane PLn;
   PLn.lane16 = lane * 16;
   PLn.b0 = lds + ((lane >> 4) * n + min(lane & 15, n - 1)) * 16;
   PLn.b1 = PLn.b0 + (S.nt + 1) * 64 * n;
+  // The compiler treats the vector memory counter as unordered while loads AND stores are pending
+  // and then waits for everything before it touches a ring slot -- in every pass of the loop, once
+  // that state has reached the loop header.  So stores are waited for, in a form the compiler sees,
+  // before the loop and after every flush; between flushes the passes wait for exactly one slot.
   while (C.f < S.f1) {
     PassPlan P;
     P.stride = 64 * n;
@@ -702,6 +738,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.f += P.nc;
     if (P.ec <= P.nc) {  // a row block ended in this pass
       flush_rowblock(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F);
+      wave_settle();
       C.rb += 1;
       C.t = P.nc - P.ec;
     } else {
@@ -711,14 +748,13 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.t = uni(C.t);
     C.rb = uni(C.rb);
   }
-  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc, lane, e, rscale, F);  // range ends inside a row block
+  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
   // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
   // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
   // starts its stream after the barrier instead (those loads overlap the activation staging).
   if (next) {
     stream_init<DT>(S, *next, next_sk, wave);
-    if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
   }
 }
 
@@ -1021,7 +1057,7 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
   const int upH = A.attn_units_per_head;
   if (u >= R) return true;  // no row for this unit
   if (tid < 64) {
-    const unsigned long long t0 = wall_clock64();
+    Deadline dl;
     int ok = 1;
     for (unsigned spin = 0;; ++spin) {
       bool all = true;
@@ -1031,7 +1067,7 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
       }
       if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
       __builtin_amdgcn_s_sleep(1);
-      if ((spin & 15) == 15 && wall_clock64() - t0 > A.timeout_ticks) {
+      if (deadline_passed(dl, spin, A.timeout_ticks)) {
         ok = 0;
         break;
       }
@@ -1180,6 +1216,8 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   e2.rb0 = S.rb0;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
   wg_mark(A, trace_layer, 1);
+  wave_settle();
+  ring_prefetch<DT, UR>(R, S, lane);
   consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
@@ -1225,9 +1263,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   if (ok && !dead) {
     embed_phase(A);
     stream_init<DT>(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
-    if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
     ok = grid_barrier(A, bc, -1, false);
-    if (wave == 0) ring_prefetch<DT, UR>(R, S, lane);
   }
   // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
   // O, gate/up, down), phase 1 is attention, and a final pass after the last layer is the LM
@@ -1243,11 +1279,9 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
         break;
       wg_mark(A, l * 8 + 1, 2);
       stream_init<DT>(S, uni_mat(A.layers[l].o), A.sk[1], wave);
-      if (wave != 0) ring_prefetch<DT, UR>(R, S, lane);
-      wg_mark(A, l * 8 + 1, 3);
+        wg_mark(A, l * 8 + 1, 3);
       if (!(ok = grid_barrier(A, bc, -1, false, l * 8 + 1))) break;
-      if (wave == 0) ring_prefetch<DT, UR>(R, S, lane);
-      wg_mark(A, l * 8 + 1, 5);
+        wg_mark(A, l * 8 + 1, 5);
       continue;
     }
     EpiCtx e;
@@ -1303,7 +1337,6 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     if (k == 5) break;
     const bool boundary = k == 4;
     if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
-    if (wave == 0 && has_next) ring_prefetch<DT, UR>(R, S, lane);
     wg_mark(A, l * 8 + k, 5);
     if (boundary) dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
   }
