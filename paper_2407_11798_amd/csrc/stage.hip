@@ -352,11 +352,16 @@ __device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, in
 // (tt = nt) are all zero in both halves: the streaming loop multiplies by them where a slot of
 // its ring holds nothing.
 // Also computes 1/sqrt(mean x^2 + eps) per token (scaled phases) from the per-16-column partial
-// sums of squares, summed in a fixed order; its loads are issued together with the activation
-// loads so the whole staging costs one memory round trip.  Ends with a workgroup barrier.
-template <int DT>
-__device__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
-                        const float* ssq, int n_blocks, float eps, float* red, float* rscale) {
+// sums of squares, summed in a fixed order.
+// Every load of a batch (partial sums, activations, gains) is issued outside any branch, and
+// those of the last batch before `mid` runs; the caller's `mid` starts the weight stream, so the activations and the
+// first weight tiles travel together and the activations, being older, are waited for alone.
+// (A load inside a branch would be waited for at the join, together with everything younger.)
+// `post` runs before the closing workgroup barrier.
+template <int DT, typename Mid, typename Post>
+__device__ __forceinline__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
+                                        const float* ssq, int n_blocks, float eps, float* red, float* rscale,
+                                        Mid&& mid, Post&& post) {
   const int items = nt * n * 4;
   const int lo_off = (nt + 1) * 4 * n;
   const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
@@ -365,27 +370,22 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
     ((uint4*)lds)[lo_off + z] = make_uint4(0u, 0u, 0u, 0u);
   }
   constexpr int kGroups = kThreads / 16;
-  float ssum = 0.0f;
-  if (ssq) {
-    const int i = threadIdx.x & 15, b0 = threadIdx.x >> 4;
-    constexpr int kMaxPer = 16;  // up to 16 * 32 = 512 blocks of 16 columns (d_model <= 8192) in one batch
-    float part[kMaxPer];
-    const __amdgpu_buffer_rsrc_t sr = rsrc_of(ssq);
+  constexpr int kMaxPer = 16;  // up to 16 * 32 = 512 blocks of 16 columns (d_model <= 8192) in one batch
+  float part[kMaxPer];
+  const int si = threadIdx.x & 15, sb0 = threadIdx.x >> 4;
+  {
+    // unscaled phases read the same number of words from the activations instead (and ignore them)
+    const __amdgpu_buffer_rsrc_t sr = rsrc_of(ssq ? ssq : xin);
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {  // plain (non-atomic) agent-scope loads: all in flight at once
-      const int b = min(b0 + q * kGroups, n_blocks - 1);
-      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, (b * 16 + i) * 4, 0, kAgent));
+      const int b = min(sb0 + q * kGroups, n_blocks - 1);
+      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, (b * 16 + si) * 4, 0, kAgent));
     }
-#pragma unroll
-    for (int q = 0; q < kMaxPer; ++q)
-      if (b0 + q * kGroups >= n_blocks) part[q] = 0.0f;
-#pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) ssum += part[q];
-    for (int b = b0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + i);
   }
-  for (int id0 = 0; id0 < items; id0 += 2 * kThreads) {
-    f32x4 p[2][2];
-    int slot[2], k0[2];
+  const float* gp = gain ? gain : xin;  // no gain: any readable words
+  auto batch = [&](int id0, auto&& between) {
+    f32x4 p[2][2], gq[2][2];
+    int slot[2];
     bool in_k[2], in_items[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -393,32 +393,26 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
       const int cl = id & 3;
       const int i = (id >> 2) % n;
       const int tt = (id >> 2) / n;
-      k0[q] = (t0 + tt) * kKTile + cl * 8;
+      const int k0 = (t0 + tt) * kKTile + cl * 8;
       slot[q] = (tt * 4 + cl) * n + i;
       in_items[q] = id < items;
-      in_k[q] = in_items[q] && k0[q] < K;
-      if (in_k[q]) {
-        const int off = (i * K + k0[q]) * 4;
-        p[q][0] = ld_ag4(xr, off);
-        p[q][1] = ld_ag4(xr, off + 16);
-      }
+      in_k[q] = in_items[q] && k0 < K;
+      const int off = in_k[q] ? (i * K + k0) * 4 : 0;
+      p[q][0] = ld_ag4(xr, off);
+      p[q][1] = ld_ag4(xr, off + 16);
+      const int goff = in_k[q] ? k0 : 0;
+      gq[q][0] = *(gptr_f32x4)(gp + goff);
+      gq[q][1] = *(gptr_f32x4)(gp + goff + 4);
     }
+    between();
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       if (!in_items[q]) continue;
       float v[8];
-      if (in_k[q]) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { v[j] = p[q][0][j]; v[4 + j] = p[q][1][j]; }
-        if (gain) {
-          const f32x4 g0 = *(gptr_f32x4)(gain + k0[q]);
-          const f32x4 g1 = *(gptr_f32x4)(gain + k0[q] + 4);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) { v[j] *= g0[j]; v[4 + j] *= g1[j]; }
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+      for (int j = 0; j < 4; ++j) {
+        v[j] = in_k[q] ? p[q][0][j] * (gain ? gq[q][0][j] : 1.0f) : 0.0f;
+        v[4 + j] = in_k[q] ? p[q][1][j] * (gain ? gq[q][1][j] : 1.0f) : 0.0f;
       }
       if (DT == PI_DTYPE_BF16) {
         uint32_t hi[4], lo[4];
@@ -437,8 +431,17 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
         ((float4*)lds)[slot[q] + lo_off] = make_float4(v[4], v[5], v[6], v[7]);
       }
     }
-  }
+  };
+  // `mid` goes with the last batch: every activation load is then older than the weight loads (a
+  // load younger than those could only be waited for together with them).
+  int id0 = 0;
+  for (; id0 + 2 * kThreads < items; id0 += 2 * kThreads) batch(id0, [] {});
+  batch(id0, mid);
   if (ssq) {
+    float ssum = 0.0f;
+#pragma unroll
+    for (int q = 0; q < kMaxPer; ++q) ssum += sb0 + q * kGroups < n_blocks ? part[q] : 0.0f;
+    for (int b = sb0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + si);
     red[threadIdx.x] = ssum;  // red[b0 * 16 + i]
     __syncthreads();
     if (threadIdx.x < 16) {
@@ -447,6 +450,7 @@ __device__ void stage_x(const float* xin, const float* gain, int K, int n, int t
       rscale[threadIdx.x] = 1.0f / sqrtf(t / (float)K + eps);
     }
   }
+  post();
   __syncthreads();
 }
 
@@ -1201,23 +1205,27 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   f32x4* resid = F.part + (kWaves - 1) * 64;
   const int Gs = uni((int)gridDim.x / S_k);
   const bool stage_resid = e.epi == EPI_RESID && uni((S.NRB + Gs - 1) / Gs) <= kMaxResidBlocks;  // as sized by the host
-  if (stage_resid) {
-    const __amdgpu_buffer_rsrc_t xr = rsrc_of(e.out);
-    const int i = lane & 15;
-    for (int r = wave; r < S.R; r += kWaves) {
-      const int row = (S.rb0 + r) * kRowBlock + (lane >> 4) * 4;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (i < e.n && row < e.N) v = ld_ag4(xr, (i * e.N + row) * 4);
-      resid[r * 64 + lane] = v;
-    }
+  // Nothing of the previous phase is pending any more (every wave drained before the barrier);
+  // said in a form the compiler's counter tracking sees, so that the waits below are counted.
+  wave_settle();
+  // The residual rows of the workgroup's row blocks (at most one row block per wave): the load
+  // goes out first and is parked in LDS behind the activations.
+  const bool has_r = stage_resid && wave < S.R;
+  f32x4 rv;
+  bool rv_live;
+  {
+    const int i = lane & 15, row = (S.rb0 + wave) * kRowBlock + (lane >> 4) * 4;
+    rv_live = has_r && i < e.n && row < e.N;
+    rv = ld_ag4(rsrc_of(e.out), rv_live ? (i * e.N + row) * 4 : 0);
   }
   EpiCtx e2 = e;
   e2.resid = stage_resid ? resid : nullptr;
   e2.rb0 = S.rb0;
-  stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale);
-  wg_mark(A, trace_layer, 1);
-  wave_settle();
-  ring_prefetch<DT, UR>(R, S, lane);
+  stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
+              [&] { ring_prefetch<DT, UR>(R, S, lane); },
+              [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; });
+  // (no global store may sit between the weight loads above and the streaming loop: with loads and
+  // stores both pending the compiler stops counting and waits for everything at every ring slot)
   consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
