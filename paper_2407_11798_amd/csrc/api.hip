@@ -40,6 +40,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
+  size_t part_tiles = 0;  // capacity of `part`, in 1 KiB tiles
   int n_q_rows() const { return cfg.n_q_heads * cfg.head_dim; }
   int n_kv_rows() const { return cfg.n_kv_heads * cfg.head_dim; }
 };
@@ -225,6 +226,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     }
     e = dev_alloc(m, &m->part, tiles * 1024, false);
     if (e == hipSuccess) e = hipMemset(m->part, 0xFF, tiles * 1024);
+    if (e == hipSuccess) m->part_tiles = tiles;
   }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);
@@ -377,8 +379,29 @@ int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
 
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
   if (!m || phase < 0 || phase > 5 || s_k < 0) return PI_E_ARG;
-  if (phase == 5) m->trace_on = s_k != 0;
-  else m->sk_override[phase] = s_k;
+  if (phase == 5) {
+    m->trace_on = s_k != 0;
+    return PI_OK;
+  }
+  m->sk_override[phase] = s_k;
+  // The buffer of cross-slice tiles was sized for the plans in force so far; grow it for this one.
+  size_t tiles = 1;
+  for (int n = 1; n <= PI_MAX_BATCH; ++n) {
+    StagePlan sp;
+    if (make_stage_plan(m, n, &sp) && sp.part_tiles > tiles) tiles = sp.part_tiles;
+  }
+  if (tiles > m->part_tiles) {
+    hipError_t e = hipDeviceSynchronize();
+    float* grown = nullptr;
+    if (e == hipSuccess) e = dev_alloc(m, &grown, tiles * 1024, false);
+    if (e == hipSuccess) e = hipMemset(grown, 0xFF, tiles * 1024);
+    if (e != hipSuccess) {
+      m->sk_override[phase] = 0;
+      return hip_status(e);
+    }
+    m->part = grown;  // the old buffer stays with the model until it is freed
+    m->part_tiles = tiles;
+  }
   return PI_OK;
 }
 
@@ -538,6 +561,7 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   if (kv->dtype != c.dtype) return PI_E_SHAPE;  // the attention kernels read the cache in the model's type
   StagePlan sp;
   if (!make_stage_plan(m, n, &sp)) return PI_E_SHAPE;
+  if (sp.part_tiles > m->part_tiles) return PI_E_SHAPE;  // the plan's cross-slice tiles must fit what was allocated
   const int ring = stage_ring_size(c.dtype, sp.min_nt);
   if (ring == 0) return PI_E_SHAPE;
   // attention work units: per kv head, the prefix in chunks (multiples of 32 cells) sized so that

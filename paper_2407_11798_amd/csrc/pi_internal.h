@@ -46,13 +46,14 @@ struct RunState {
   int32_t pad;
 };
 
-// Grid barrier state.  Every workgroup owns one arrival flag and publishes the (ever growing)
-// number of the barrier it has reached; a barrier is passed when every flag has reached it, so
-// there is no shared counter to contend on and nothing to reset between launches.
+// Grid barrier state.  Every workgroup owns one arrival word and publishes the (ever growing)
+// number of the barrier it has reached, shifted left by one; a barrier is passed when every word
+// has reached it, so there is no shared counter to contend on and nothing to reset between
+// launches.  Bit 0 of workgroup 0's word is the stop decision of a layer-boundary barrier.
 constexpr int kMaxGrid = 1024;
 struct StageSync {
   unsigned flags[kMaxGrid];
-  unsigned decision;  // last layer-boundary barrier whose cancel decision workgroup 0 has published
+  unsigned reserved;
   unsigned abort;     // sticky: a barrier wait ran into its time limit
   unsigned exited;
   unsigned pad;

@@ -97,8 +97,12 @@ struct BarrierCtx {
 
 // Every workgroup calls it the same number of times.  Returns false when the grid must stop (a
 // wait ran into its time limit): callers then leave the kernel at once.  layers_done >= 0 marks
-// a layer boundary: workgroup 0 records progress, probes the cancel flag when `probe` is set
-// and publishes the decision, which every workgroup reads before going on.
+// a layer boundary: workgroup 0 records progress and probes the cancel flag when `probe` is set,
+// BEFORE it arrives, and its arrival word carries the decision in bit 0 (the barrier number sits
+// in the bits above), so every workgroup learns it from the poll that ends its wait -- a layer
+// boundary costs no round trip more than any other barrier.  (A workgroup that is late to look
+// may find workgroup 0's word of the NEXT barrier there; that one exists only if this decision
+// was "go on", and boundaries are never adjacent, so bit 0 reads the same.)
 __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
   __syncthreads();  // every wave of this workgroup has drained its stores
   if (A.wgtrace && mark == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + 4] = wall_clock64();
@@ -106,19 +110,37 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
   StageSync* sy = A.sync;
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
-    if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned want = bc.epoch << 1;
+    unsigned word = want;
+    if (layers_done >= 0 && blockIdx.x == 0) {
+      if (lane == 0) {
+        __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int dead = __hip_atomic_load(&A.rs->dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // the run latch's verdict
+        if (!dead && probe && A.cancel_flag &&
+            __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
+          __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(&A.rs->dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          dead = 1;
+        }
+        word |= (unsigned)dead;
+      }
+      wave_drain();
+    }
+    if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const __amdgpu_buffer_rsrc_t fr = rsrc_of(sy->flags);
     const int G = gridDim.x;
     Deadline dl;
     int ok = 1;
+    unsigned first = want;  // workgroup 0's word, in lane 0
     for (unsigned spin = 0;; ++spin) {
       bool all = true;
       for (int base = 0; base < G; base += 256) {
         const int idx = base + lane * 4;
-        u32x4 f = {bc.epoch, bc.epoch, bc.epoch, bc.epoch};
+        u32x4 f = {want, want, want, want};
         if (idx < G) f = __builtin_amdgcn_raw_buffer_load_b128(fr, idx * 4, 0, kAgent);
+        if (base == 0) first = f[0];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (int)(f[q] - bc.epoch) >= 0);
+        for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (int)((f[q] & ~1u) - want) >= 0);
       }
       if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
       __builtin_amdgcn_s_sleep(1);
@@ -127,32 +149,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
         break;
       }
     }
-    int dead = 0;
-    if (ok && layers_done >= 0) {
-      if (blockIdx.x == 0) {
-        if (lane == 0) {
-          __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (probe && A.cancel_flag &&
-              __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
-            __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&A.rs->dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-        }
-        wave_drain();
-        if (lane == 0) __hip_atomic_store(&sy->decision, bc.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      } else {
-        for (unsigned spin = 0;; ++spin) {
-          const unsigned d = __hip_atomic_load(&sy->decision, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if ((int)(d - bc.epoch) >= 0) break;
-          __builtin_amdgcn_s_sleep(1);
-          if (deadline_passed(dl, spin, A.timeout_ticks)) {
-            ok = 0;
-            break;
-          }
-        }
-      }
-      if (ok) dead = __hip_atomic_load(&A.rs->dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    const int dead = ok && layers_done >= 0 ? (int)(__builtin_amdgcn_readfirstlane(first) & 1u) : 0;
     if (lane == 0) {
       if (!ok) __hip_atomic_store(&sy->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (A.trace && blockIdx.x == 0 && (int)(bc.epoch - A.epoch_base) <= A.trace_cap)
