@@ -371,15 +371,17 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
   float part[kMaxPer];
   const int si = threadIdx.x & 15, sb0 = threadIdx.x >> 4;
   {
-    // unscaled phases read the same number of words from the activations instead (and ignore them)
-    const __amdgpu_buffer_rsrc_t sr = rsrc_of(ssq ? ssq : xin);
+    // The loads stay unconditional; the ones nobody needs (an unscaled phase; the columns of tokens
+    // the run does not have) get out-of-range offsets, which the hardware answers with zeros
+    // without going to memory -- every workgroup reads these same few lines at the same moment.
+    const __amdgpu_buffer_rsrc_t sr = make_rsrc(ssq ? ssq : xin, ssq ? (uint32_t)n_blocks * 64u : 0u);
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {  // plain (non-atomic) agent-scope loads: all in flight at once
       const int b = min(sb0 + q * kGroups, n_blocks - 1);
-      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, (b * 16 + si) * 4, 0, kAgent));
+      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, si < n ? (b * 16 + si) * 4 : 0x7ffffff0, 0, kAgent));
     }
   }
-  const float* gp = gain ? gain : xin;  // no gain: any readable words
+  const __amdgpu_buffer_rsrc_t gr = make_rsrc(gain ? gain : xin, gain ? (uint32_t)K * 4u : 0u);  // no gain: zeros, no traffic
   auto batch = [&](int id0, auto&& between) {
     f32x4 p[2][2], gq[2][2];
     int slot[2];
@@ -398,8 +400,8 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
       p[q][0] = ld_ag4(xr, off);
       p[q][1] = ld_ag4(xr, off + 16);
       const int goff = in_k[q] ? k0 : 0;
-      gq[q][0] = *(gptr_f32x4)(gp + goff);
-      gq[q][1] = *(gptr_f32x4)(gp + goff + 4);
+      gq[q][0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(gr, goff * 4, 0, 0));
+      gq[q][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(gr, goff * 4 + 16, 0, 0));
     }
     between();
 #pragma unroll
@@ -438,7 +440,8 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
     float ssum = 0.0f;
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) ssum += sb0 + q * kGroups < n_blocks ? part[q] : 0.0f;
-    for (int b = sb0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + si);
+    if (si < n)
+      for (int b = sb0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + si);
     red[threadIdx.x] = ssum;  // red[b0 * 16 + i]
     __syncthreads();
     if (threadIdx.x < 16) {
@@ -560,7 +563,8 @@ struct FlushCtx {
   int trace_key;
 };
 
-__device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
+// Returns whether global memory was touched (false: the tile was parked in LDS and that is all).
+__device__ __forceinline__ bool flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
                                                f32x4 acc, int lane, const EpiCtx& e, const float* rscale,
                                                const FlushCtx& F) {
   const int r = rb - S.rb0;
@@ -571,7 +575,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
       F.part[(S.wave - 1) * 64 + lane] = acc;
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       if (lane == 0) __hip_atomic_store(F.pflag + S.wave, (int)F.tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      return;
+      return false;
     }
     Deadline dl;
     for (unsigned spin = 0;; ++spin) {
@@ -593,7 +597,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
     const __amdgpu_buffer_rsrc_t pr = rsrc_of(A.part);
     if (S.slice != 0) {
       if (live) st_ag4(pr, ((rb * S_k + S.slice) * 64 + lane) * 16, acc);
-      return;
+      return true;
     }
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
     Deadline dl;
@@ -625,6 +629,7 @@ __device__ __forceinline__ void flush_rowblock(const StageArgs& A, const WaveStr
     }
   }
   epilogue(e, rb, acc, lane, rscale);
+  return true;
 }
 
 // ---- the MFMA inner step ----------------------------------------------------------------------
@@ -738,8 +743,8 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     advance_loads(S, P, TB);
     C.f += P.nc;
     if (P.ec <= P.nc) {  // a row block ended in this pass
-      flush_rowblock(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F);
-      wave_settle();
+      // (a tile parked in LDS leaves no store behind: the ring stays in flight across it)
+      if (flush_rowblock(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F)) wave_settle();
       C.rb += 1;
       C.t = P.nc - P.ec;
     } else {
@@ -749,7 +754,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.t = uni(C.t);
     C.rb = uni(C.rb);
   }
-  if (C.t > 0) flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
+  if (C.t > 0) (void)flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
   // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
   // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
