@@ -164,6 +164,32 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
                          float* logits_out, const int32_t* cancel_flag, int32_t* run_status,
                          void* stream);
 
+/* Several speculative runs in ONE weight pass (the single-node form of the paper's "Continuous
+ * Asynchronous Speculation": many small speculative runs are in flight at once and each can be
+ * cancelled on its own, Section "Early Inference Cancellation"; PipeInfer on a single node is
+ * the outlook of Section "Future Work").  The micro-batch of `run` holds the tokens of n_groups
+ * runs; runs see each other's cells only where their masks say so.
+ *   group_of_token: HOST int32[run->n], run index of every token; each of 0..n_groups-1 occurs.
+ *   cancel_flags:   device-visible int32[n_groups] (or NULL: never cancel), probed like
+ *                   cancel_flag of pi_stage_forward.  From the boundary at which a run's word is
+ *                   seen set, the K/V of its tokens is no longer written and its rows of the
+ *                   outputs are unspecified; the other runs are unaffected.  When every run is
+ *                   cancelled no further layer starts and the outputs stay untouched.
+ *   group_status:   device int32[n_groups][2] (or NULL), written by the device: per run
+ *                   {PI_OK | PI_CANCELLED | PI_E_SLOT_LIVE, layers_done}, layers_done = first
+ *                   layer whose K/V the run did NOT write.
+ * run_status is as for pi_stage_forward; its status is PI_CANCELLED only if every run was. */
+#define PI_MAX_GROUPS 16
+typedef struct {
+  int32_t n_groups;
+  const int32_t* group_of_token;
+  const int32_t* cancel_flags;
+  int32_t* group_status;
+} pi_group_desc;
+int32_t pi_stage_forward_multi(pi_model* m, pi_kv* kv, const pi_run_desc* run, const pi_group_desc* groups,
+                               int32_t layer_begin, int32_t layer_end, const float* hidden_in,
+                               float* hidden_out, float* logits_out, int32_t* run_status, void* stream);
+
 /* Greedy token-tree verification (Section "Speculative Inference / Verification"; greedy
  * sampling as in Section "Experiments").  logits[i] follows tree node i; parent[i] < i is
  * node i's parent, -1 = child of the last accepted token (parent == NULL: linear chain).

@@ -26,7 +26,7 @@ PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
-    "pi_stage_forward", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
+    "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
     "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
 ]
 
@@ -40,6 +40,11 @@ class PiModelConfig(ctypes.Structure):
 class PiRunDesc(ctypes.Structure):
     _fields_ = [("n", c_int32), ("tokens", c_void_p), ("positions", c_void_p), ("slots", c_void_p),
                 ("mask", c_void_p), ("prefix_len", c_int32), ("window_base", c_int32)]
+
+
+class PiGroupDesc(ctypes.Structure):
+    _fields_ = [("n_groups", c_int32), ("group_of_token", c_void_p), ("cancel_flags", c_void_p),
+                ("group_status", c_void_p)]
 
 
 class PiError(RuntimeError):
@@ -70,6 +75,8 @@ def lib():
         L.pi_kv_set_len.argtypes = [c_void_p, c_int32]
         L.pi_kv_len.argtypes = [c_void_p, POINTER(c_int32)]
         L.pi_kv_raw.argtypes = [c_void_p, c_void_p, POINTER(c_int64)]
+        L.pi_stage_forward_multi.argtypes = [c_void_p, c_void_p, POINTER(PiRunDesc), POINTER(PiGroupDesc), c_int32,
+                                             c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_stage_forward.argtypes = [c_void_p, c_void_p, POINTER(PiRunDesc), c_int32, c_int32, c_void_p,
                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_verify_greedy.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
@@ -259,6 +266,26 @@ def stage_forward(model: Model, kv: KVCache, run: Run, layer_begin: int, layer_e
                                 _ptr(hidden_out), _ptr(logits_out), cf, _ptr(run_status),
                                 _stream_handle(stream))
     return _check(st, "pi_stage_forward")
+
+
+def stage_forward_multi(model: Model, kv: KVCache, run: Run, group_of_token, layer_begin: int, layer_end: int,
+                        hidden_in=None, hidden_out=None, logits_out=None, cancel_flags=None, group_status=None,
+                        run_status=None, stream=None, cancel_flags_ptr: int | None = None) -> int:
+    """Enqueue pi_stage_forward_multi: the run's tokens belong to several runs (group_of_token: one
+    run index per token, host side); cancel_flags: torch int32 device tensor with one word per run
+    (or a raw device-visible address), group_status: torch int32 device tensor [n_groups][2]."""
+    d = run.desc()
+    g = [int(v) for v in group_of_token]
+    arr = (c_int32 * len(g))(*g)
+    gd = PiGroupDesc()
+    gd.n_groups = (max(g) + 1) if g else 0
+    gd.group_of_token = ctypes.cast(arr, c_void_p)
+    gd.cancel_flags = c_void_p(cancel_flags_ptr) if cancel_flags_ptr is not None else _ptr(cancel_flags)
+    gd.group_status = _ptr(group_status)
+    st = lib().pi_stage_forward_multi(model.handle, kv.handle, byref(d), byref(gd), layer_begin, layer_end,
+                                      _ptr(hidden_in), _ptr(hidden_out), _ptr(logits_out), _ptr(run_status),
+                                      _stream_handle(stream))
+    return _check(st, "pi_stage_forward_multi")
 
 
 def verify_greedy(draft, parent, n: int, logits, vocab: int, root_expected: int, accepted_nodes, result,

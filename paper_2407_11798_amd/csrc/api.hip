@@ -131,6 +131,11 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
   return true;
 }
 
+int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int n_groups, const uint32_t* group_mask,
+                             const int32_t* cancel_flags, int32_t* group_status, int32_t layer_begin,
+                             int32_t layer_end, const float* hidden_in, float* hidden_out, float* logits_out,
+                             int32_t* run_status, void* stream);
+
 bool is_layer_kind(int kind) { return kind >= PI_T_ATTN_NORM && kind <= PI_T_WD; }
 
 size_t flag_index(const pi_model* m, int kind, int layer) {
@@ -539,6 +544,38 @@ int32_t pi_kv_raw(const pi_kv* kv, void* dst_host, int64_t* nbytes) {
 int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t layer_begin, int32_t layer_end,
                          const float* hidden_in, float* hidden_out, float* logits_out,
                          const int32_t* cancel_flag, int32_t* run_status, void* stream) {
+  if (!run) return PI_E_ARG;
+  const uint32_t everyone = run->n >= 1 && run->n < 32 ? (1u << run->n) - 1u : 0u;
+  return stage_forward_groups(m, kv, run, 1, &everyone, cancel_flag, nullptr, layer_begin, layer_end, hidden_in,
+                              hidden_out, logits_out, run_status, stream);
+}
+
+int32_t pi_stage_forward_multi(pi_model* m, pi_kv* kv, const pi_run_desc* run, const pi_group_desc* groups,
+                               int32_t layer_begin, int32_t layer_end, const float* hidden_in, float* hidden_out,
+                               float* logits_out, int32_t* run_status, void* stream) {
+  if (!run || !groups || !groups->group_of_token) return PI_E_ARG;
+  if (groups->n_groups < 1 || groups->n_groups > PI_MAX_GROUPS) return PI_E_SHAPE;
+  if (run->n < 1 || run->n > PI_MAX_BATCH) return PI_E_SHAPE;
+  uint32_t masks[PI_MAX_GROUPS] = {0};
+  for (int i = 0; i < run->n; ++i) {
+    const int g = groups->group_of_token[i];
+    if (g < 0 || g >= groups->n_groups) return PI_E_ARG;
+    masks[g] |= 1u << i;
+  }
+  for (int g = 0; g < groups->n_groups; ++g)
+    if (!masks[g]) return PI_E_ARG;  // a run without tokens
+  return stage_forward_groups(m, kv, run, groups->n_groups, masks, groups->cancel_flags, groups->group_status,
+                              layer_begin, layer_end, hidden_in, hidden_out, logits_out, run_status, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int n_groups, const uint32_t* group_mask,
+                             const int32_t* cancel_flags, int32_t* group_status, int32_t layer_begin,
+                             int32_t layer_end, const float* hidden_in, float* hidden_out, float* logits_out,
+                             int32_t* run_status, void* stream) {
   if (!m || !kv || !run) return PI_E_ARG;
   if (kv->model != m) return PI_E_STATE;
   const pi_model_config& c = m->cfg;
@@ -624,7 +661,10 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.hidden_in = hidden_in;
   a.hidden_out = hidden_out;
   a.logits_out = logits_out;
-  a.cancel_flag = cancel_flag;
+  a.cancel_flags = cancel_flags;
+  a.group_status = group_status;
+  a.n_groups = n_groups;
+  for (int g = 0; g < n_groups; ++g) a.group_mask[g] = group_mask[g];
   a.run_status = run_status;
   a.kbase = (char*)kv->k;
   a.vbase = (char*)kv->v;
@@ -656,6 +696,10 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
   a.wgtrace_layer = m->wgtrace_layer;
   return hip_status(launch_stage(a, c.dtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
+
+}  // namespace
+
+extern "C" {
 
 int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
                          int32_t vocab, int32_t root_expected, int32_t* accepted_nodes, int32_t* result,

@@ -40,16 +40,17 @@ constexpr int kStageThreads = 512;  // 8 waves per workgroup, one workgroup per 
 
 // Device-visible state of the run in flight on a model.
 struct RunState {
-  int32_t dead;         // non-zero: the run stops at the next layer boundary
-  int32_t status;       // PI_OK / PI_CANCELLED / PI_E_SLOT_LIVE
+  int32_t reserved0;
+  int32_t status;       // PI_OK / PI_CANCELLED (every run of the micro-batch) / PI_E_SLOT_LIVE
   int32_t layers_done;  // first layer not evaluated
-  int32_t pad;
+  int32_t reserved1;
 };
 
 // Grid barrier state.  Every workgroup owns one arrival word and publishes the (ever growing)
-// number of the barrier it has reached, shifted left by one; a barrier is passed when every word
-// has reached it, so there is no shared counter to contend on and nothing to reset between
-// launches.  Bit 0 of workgroup 0's word is the stop decision of a layer-boundary barrier.
+// number of the barrier it has reached in the upper 16 bits (compared modulo 2^16); a barrier is
+// passed when every word has reached it, so there is no shared counter to contend on and nothing
+// to reset between launches.  The lower 16 bits of workgroup 0's word are the tokens whose runs
+// have been cancelled so far.
 constexpr int kMaxGrid = 1024;
 struct StageSync {
   unsigned flags[kMaxGrid];
@@ -93,7 +94,7 @@ struct StageArgs {
   const float* hidden_in;
   float* hidden_out;
   float* logits_out;
-  const int32_t* cancel_flag;
+  const int32_t* cancel_flags;       // [n_groups] device-visible words, or null
   int32_t* run_status;
   // kv cache: K and V each [L][Hkv][cells][hd]
   char* kbase;
@@ -119,6 +120,10 @@ struct StageArgs {
   int trace_cap;
   unsigned long long* wgtrace;  // optional debug: [grid][8] timestamps of workgroup events in one layer
   int wgtrace_layer;
+  // rarely read (workgroup 0, at layer boundaries), so kept behind everything the phases use
+  int32_t* group_status;             // [n_groups][2] {status, layers_done} per run, or null
+  int n_groups;                      // runs sharing the micro-batch
+  uint32_t group_mask[PI_MAX_GROUPS];  // bit i: token i belongs to the run
 };
 
 // ---- launch wrappers (each defined next to its kernels) ---------------------------------

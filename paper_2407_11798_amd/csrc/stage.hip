@@ -92,39 +92,58 @@ __device__ __forceinline__ bool deadline_passed(Deadline& d, unsigned spin, unsi
 // probe_layer >= 0: layer boundary; the last arriver records progress and probes the cancel flag.
 struct BarrierCtx {
   unsigned epoch;  // absolute number of the last barrier passed
-  int* sh;         // 2 ints of LDS: {ok, dead}
+  int* sh;         // 2 ints of LDS: {ok, tokens whose runs are cancelled}
+  // first wave of workgroup 0 only: the cancelled tokens and runs so far (kept in registers: a
+  // load here would delay workgroup 0's arrival, and with it the whole grid, at every barrier)
+  unsigned dead, dead_groups;
 };
 
 // Every workgroup calls it the same number of times.  Returns false when the grid must stop (a
 // wait ran into its time limit): callers then leave the kernel at once.  layers_done >= 0 marks
-// a layer boundary: workgroup 0 records progress and probes the cancel flag when `probe` is set,
-// BEFORE it arrives, and its arrival word carries the decision in bit 0 (the barrier number sits
-// in the bits above), so every workgroup learns it from the poll that ends its wait -- a layer
+// a layer boundary: workgroup 0 records progress and, when `probe` is set, reads the cancel word
+// of every run of the micro-batch that is still alive, BEFORE it arrives; the lower half of its
+// arrival word carries the set of tokens whose runs are cancelled (the barrier number sits in
+// the upper half), so every workgroup learns it from the poll that ends its wait -- a layer
 // boundary costs no round trip more than any other barrier.  (A workgroup that is late to look
-// may find workgroup 0's word of the NEXT barrier there; that one exists only if this decision
-// was "go on", and boundaries are never adjacent, so bit 0 reads the same.)
-__device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
+// may find workgroup 0's word of the NEXT barrier there; the set only changes at boundaries and
+// boundaries are never adjacent, so it reads the same set.)  sh[1] is that set.
+__device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
   __syncthreads();  // every wave of this workgroup has drained its stores
   if (A.wgtrace && mark == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + 4] = wall_clock64();
   bc.epoch += 1;
   StageSync* sy = A.sync;
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
-    const unsigned want = bc.epoch << 1;
+    const unsigned want = bc.epoch << 16;
     unsigned word = want;
-    if (layers_done >= 0 && blockIdx.x == 0) {
-      if (lane == 0) {
-        __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int dead = __hip_atomic_load(&A.rs->dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // the run latch's verdict
-        if (!dead && probe && A.cancel_flag &&
-            __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
-          __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(&A.rs->dead, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          dead = 1;
+    if (blockIdx.x == 0) {
+      unsigned dead = bc.dead;
+      if (layers_done >= 0) {
+        const unsigned all = A.n >= 32 ? 0xffffffffu : (1u << A.n) - 1u;
+        unsigned groups = bc.dead_groups;
+        // lane g looks after run g: all cancel words are read with one load instruction
+        const bool mine = lane < A.n_groups && !((groups >> lane) & 1u);
+        if (mine && A.group_status)
+          __hip_atomic_store(A.group_status + 2 * lane + 1, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool hit = false;
+        if (dead != all && probe && A.cancel_flags && mine)
+          hit = __hip_atomic_load(A.cancel_flags + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0;
+        if (hit && A.group_status)
+          __hip_atomic_store(A.group_status + 2 * lane, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
+        if (hits) {
+          groups |= (unsigned)hits;
+          for (int g = 0; g < A.n_groups; ++g)
+            if ((hits >> g) & 1ull) dead |= A.group_mask[g];
+          bc.dead = dead;
+          bc.dead_groups = groups;
+          if (lane == 0 && dead == all)
+            __hip_atomic_store(&A.rs->status, PI_CANCELLED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        word |= (unsigned)dead;
+        if (lane == 0) __hip_atomic_store(&A.rs->layers_done, layers_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        wave_drain();
       }
-      wave_drain();
+      word |= dead & 0xffffu;
     }
     if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const __amdgpu_buffer_rsrc_t fr = rsrc_of(sy->flags);
@@ -140,7 +159,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
         if (idx < G) f = __builtin_amdgcn_raw_buffer_load_b128(fr, idx * 4, 0, kAgent);
         if (base == 0) first = f[0];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (int)((f[q] & ~1u) - want) >= 0);
+        for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (short)((f[q] - want) >> 16) >= 0);
       }
       if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
       __builtin_amdgcn_s_sleep(1);
@@ -149,7 +168,7 @@ __device__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done
         break;
       }
     }
-    const int dead = ok && layers_done >= 0 ? (int)(__builtin_amdgcn_readfirstlane(first) & 1u) : 0;
+    const int dead = ok ? (int)(__builtin_amdgcn_readfirstlane(first) & 0xffffu) : 0;
     if (lane == 0) {
       if (!ok) __hip_atomic_store(&sy->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (A.trace && blockIdx.x == 0 && (int)(bc.epoch - A.epoch_base) <= A.trace_cap)
@@ -474,6 +493,7 @@ struct EpiCtx {
   int n_cells, kv_dtype;
   const int32_t* positions;
   const int32_t* slots;
+  unsigned dead_tokens;  // QKV: tokens of cancelled runs
   const float2* rope;
   const f32x4* resid;  // RESID: LDS copy of the residual rows of the workgroup's row blocks, [row block][lane]
   int rb0;             // first row block of the workgroup
@@ -516,7 +536,7 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
       const int kr = row - e.n_q_rows - (is_k ? 0 : e.n_kv_rows);
       const int head = kr / hd, dim = kr % hd;
       const size_t idx = ((size_t)head * e.n_cells + e.slots[i]) * hd + dim;
-      store_kv4(is_k ? e.kcache : e.vcache, e.kv_dtype, idx, v);
+      if (!((e.dead_tokens >> i) & 1u)) store_kv4(is_k ? e.kcache : e.vcache, e.kv_dtype, idx, v);  // a cancelled run writes no more K/V
     }
   } else if (EPI == EPI_RESID) {
     float s = 0.0f;
@@ -1243,33 +1263,52 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   BarrierCtx bc;
   bc.epoch = A.epoch_base;
   bc.sh = bar_sh;
+  bc.dead = 0;
+  bc.dead_groups = 0;
   const int L = A.n_layers;
 
-  // run latch: validate the run's slots, probe the cancel flag once
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    int status = PI_OK, dead = 0;
+  // run latch (first wave of workgroup 0): validate the slots (lane i: token i), probe every run's
+  // cancel word once (lane g: run g)
+  const unsigned all_tokens = (1u << A.n) - 1u;
+  if (blockIdx.x == 0 && threadIdx.x < 64) {
+    int status = PI_OK;
+    unsigned dead = 0;
     const int len = *A.kv_len;
-    for (int i = 0; i < A.n; ++i) {
-      const int s = A.slots[i];
-      if (s < len || s < A.window_base || s >= A.window_base + PI_WINDOW || s >= A.n_cells) {
-        status = PI_E_SLOT_LIVE;
-        dead = 1;
-      }
+    bool bad = false;
+    if (lane < A.n) {
+      const int s = A.slots[lane];
+      bad = s < len || s < A.window_base || s >= A.window_base + PI_WINDOW || s >= A.n_cells;
     }
-    if (!dead && A.cancel_flag &&
-        __hip_atomic_load(A.cancel_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0) {
-      status = PI_CANCELLED;
-      dead = 1;
+    const bool refused = __builtin_amdgcn_ballot_w64(bad) != 0;
+    if (refused) {
+      status = PI_E_SLOT_LIVE;
+      dead = all_tokens;
     }
-    __hip_atomic_store(&A.rs->status, status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&A.rs->dead, dead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(&A.rs->layers_done, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool hit = false;
+    if (!refused && A.cancel_flags && lane < A.n_groups)
+      hit = __hip_atomic_load(A.cancel_flags + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0;
+    const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
+    for (int g = 0; g < A.n_groups; ++g)
+      if ((hits >> g) & 1ull) dead |= A.group_mask[g];
+    if (!refused && dead == all_tokens) status = PI_CANCELLED;
+    if (A.group_status && lane < A.n_groups) {
+      __hip_atomic_store(A.group_status + 2 * lane, refused ? PI_E_SLOT_LIVE : (hit ? PI_CANCELLED : PI_OK), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(A.group_status + 2 * lane + 1, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    bc.dead = dead;
+    bc.dead_groups = refused ? 0xffffffffu : (unsigned)hits;
+    if (lane == 0) {
+      __hip_atomic_store(&A.rs->status, status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&A.rs->layers_done, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     wave_drain();
   }
   Ring<DT, UR> R;
   WaveStream S;
   bool ok = grid_barrier(A, bc, A.layer_begin, false);
-  bool dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
+  unsigned dead_tokens = (unsigned)__builtin_amdgcn_readfirstlane(bar_sh[1]);  // tokens of cancelled runs
+  bool dead = dead_tokens == all_tokens;  // nothing left to do
   if (ok && !dead) {
     embed_phase(A);
     stream_init<DT>(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
@@ -1305,6 +1344,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.kv_dtype = A.kv_dtype;
     e.positions = A.positions;
     e.slots = A.slots;
+    e.dead_tokens = dead_tokens;
     e.rope = A.rope;
     e.resid = nullptr;
     e.rb0 = 0;
@@ -1348,7 +1388,10 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     const bool boundary = k == 4;
     if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
     wg_mark(A, l * 8 + k, 5);
-    if (boundary) dead = __builtin_amdgcn_readfirstlane(bar_sh[1]) != 0;
+    if (boundary) {
+      dead_tokens = (unsigned)__builtin_amdgcn_readfirstlane(bar_sh[1]);
+      dead = dead_tokens == all_tokens;
+    }
   }
   if (ok && !dead && A.layer_end < L) hidden_out_phase(A);
   // Exit: the last workgroup to leave re-arms the barrier for the next launch and reports.
