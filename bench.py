@@ -80,6 +80,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cancel", action="store_true", help="skip the cancellation latency trials")
+    ap.add_argument("--no-multi-run", action="store_true", help="skip the several-runs-per-pass comparison")
     ap.add_argument("--slice-layers", type=int, default=0,
                     help="also time a pipeline stage's share: the first this-many layers as one stage call")
     ap.add_argument("--calibrate-copy", type=int, default=0,
@@ -220,6 +221,55 @@ def main():
               "latency_layers_max": float(np.max(lat)) / layer_us if lat else None,
               "layers_done": stopped_at}
 
+    # Several runs per weight pass: eight 4-token speculation trees under the shared prefix (the
+    # shape of the paper's continuous speculation: many small runs in flight), evaluated as eight
+    # passes of one run each and as two passes of four runs each (pi_stage_forward_multi, every run
+    # with its own cancel word; none is raised here).
+    multi = None
+    if not args.no_multi_run:
+        trees = [synth.random_tree(args.seed, 100 + r, 4) for r in range(8)]
+        singles, quads = [], []
+        for r, parent in enumerate(trees):
+            rd = synth.tree_run(parent, T, T, offset=4 * r)
+            singles.append(gpu_loader.make_run(rd, synth.sibling_distinct_tokens(shape, args.seed, 100 + r, parent)))
+        for q in range(2):
+            parent = np.concatenate([np.where(trees[4 * q + j] >= 0, trees[4 * q + j] + 4 * j, -1) for j in range(4)]).astype(np.int32)
+            toks = np.concatenate([synth.sibling_distinct_tokens(shape, args.seed, 100 + 4 * q + j, trees[4 * q + j])
+                                   for j in range(4)]).astype(np.int32)
+            quads.append((gpu_loader.make_run(synth.tree_run(parent, T, T, offset=16 * q), toks),
+                          [j for j in range(4) for _ in range(4)]))
+        lg4 = torch.empty((4, shape.vocab), device="cuda")
+        lg16 = torch.empty((16, shape.vocab), device="cuda")
+        flags = torch.zeros(4, dtype=torch.int32, device="cuda")
+        gstat = torch.zeros((4, 2), dtype=torch.int32, device="cuda")
+
+        def eight_passes():
+            for run in singles:
+                pi.stage_forward(model, kv, run, 0, shape.n_layers, logits_out=lg4, run_status=status)
+                pi.kv_rollback(kv, run.slots, 4)
+
+        def two_passes():
+            for run, groups in quads:
+                pi.stage_forward_multi(model, kv, run, groups, 0, shape.n_layers, logits_out=lg16,
+                                       cancel_flags=flags, group_status=gstat, run_status=status)
+                pi.kv_rollback(kv, run.slots, 16)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        reps = max(2, args.steps // 10)
+        t8, t2 = timed(eight_passes, reps), timed(two_passes, reps)
+        assert gstat.cpu().tolist() == [[0, shape.n_layers]] * 4
+        multi = {"runs": 8, "tokens_per_run": 4,
+                 "one_run_per_pass": {"passes": 8, "ms": t8 * 1e3, "verified_tokens_per_s": 32 / t8},
+                 "four_runs_per_pass": {"passes": 2, "ms": t2 * 1e3, "verified_tokens_per_s": 32 / t2}}
+
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
         "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
@@ -231,6 +281,7 @@ def main():
                    "step": "pi_stage_forward(all layers + LM head) + pi_verify_greedy + pi_kv_rollback"},
         "per_batch": per_batch,
         "cancellation": cancel,
+        "multi_run": multi,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": hb["frac_of_peak"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get((shape.name, T, int(head))),

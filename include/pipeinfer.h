@@ -177,7 +177,10 @@ int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t
  *                   cancelled no further layer starts and the outputs stay untouched.
  *   group_status:   device int32[n_groups][2] (or NULL), written by the device: per run
  *                   {PI_OK | PI_CANCELLED | PI_E_SLOT_LIVE, layers_done}, layers_done = first
- *                   layer whose K/V the run did NOT write.
+ *                   layer whose K/V the run did NOT write.  It travels with the activations
+ *                   through the stages of one pass: a run whose entry says PI_CANCELLED when a
+ *                   stage starts is treated as cancelled and its entry is left as it is, so
+ *                   clear the entries (any value but PI_CANCELLED) before the first stage.
  * run_status is as for pi_stage_forward; its status is PI_CANCELLED only if every run was. */
 #define PI_MAX_GROUPS 16
 typedef struct {

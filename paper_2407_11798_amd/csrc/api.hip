@@ -12,7 +12,8 @@ using namespace pi;
 
 namespace {
 
-constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS the staged activations may take
+constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS a projection phase should take (more slices beat a fuller LDS)
+constexpr size_t kProjLdsLimit = 150 * 1024;  // ... and may take where no split fits the budget (160 KiB; a little is static)
 constexpr unsigned long long kBarrierTimeoutTicks = 200000000ull;  // 2 s of the 100 MHz clock
 
 }  // namespace
@@ -89,18 +90,19 @@ hipError_t dev_alloc(pi_model* m, T** p, size_t bytes, bool zero) {
 // the grid, lets the phase's LDS needs for n tokens fit the budget and -- where the matrix has
 // fewer row blocks than the grid has workgroups -- gives every workgroup a row block, as long as
 // a slice keeps at least 16 tiles per row block.  0 = impossible.
-int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n) {
+int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t budget = kProjLdsBudget) {
   const int ov = m->sk_override[phase];
   int fits = 0;
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
     if (w.KT % sk || m->grid % sk) continue;
     const int gs = m->grid / sk;
-    if (stage_proj_lds_bytes(n, w.KT / sk, (w.NRB + gs - 1) / gs) > kProjLdsBudget) continue;
+    if (stage_proj_lds_bytes(n, w.KT / sk, (w.NRB + gs - 1) / gs) > budget) continue;
     if (ov > sk) continue;  // an override asks for at least this many slices
     if (fits && w.KT / sk < 16) break;  // more slices would starve the ring
     fits = sk;
     if ((long)w.NRB * sk >= m->grid) break;
   }
+  if (!fits && budget < kProjLdsLimit) return choose_sk(m, phase, w, n, kProjLdsLimit);
   return fits;
 }
 

@@ -1284,14 +1284,19 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       status = PI_E_SLOT_LIVE;
       dead = all_tokens;
     }
-    bool hit = false;
-    if (!refused && A.cancel_flags && lane < A.n_groups)
+    // a run that an earlier stage of the same pass reported cancelled stays cancelled, and its
+    // entry (which says where it stopped) is left alone
+    bool hit = false, before = false;
+    if (!refused && A.group_status && lane < A.n_groups)
+      before = __hip_atomic_load(A.group_status + 2 * lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == PI_CANCELLED;
+    if (!refused && !before && A.cancel_flags && lane < A.n_groups)
       hit = __hip_atomic_load(A.cancel_flags + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0;
+    hit = hit || before;
     const unsigned long long hits = __builtin_amdgcn_ballot_w64(hit);
     for (int g = 0; g < A.n_groups; ++g)
       if ((hits >> g) & 1ull) dead |= A.group_mask[g];
     if (!refused && dead == all_tokens) status = PI_CANCELLED;
-    if (A.group_status && lane < A.n_groups) {
+    if (A.group_status && lane < A.n_groups && !before) {
       __hip_atomic_store(A.group_status + 2 * lane, refused ? PI_E_SLOT_LIVE : (hit ? PI_CANCELLED : PI_OK), __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(A.group_status + 2 * lane + 1, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

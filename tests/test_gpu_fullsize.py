@@ -135,6 +135,62 @@ def test_llama7b_concurrent_runs_with_cancellation(llama7b):
     assert best[1] == 0 or img[:, :, :, T:T + best[1]].any()
 
 
+def test_llama7b_four_runs_per_weight_pass_match_oracle(llama7b):
+    """The same eight tree runs, four per weight pass (pi_stage_forward_multi, 16 tokens): runs the
+    schedule cancels stop before their layer (their words are stored in-stream between two stage
+    calls per distinct stop layer), the others' sampled logits equal the oracle's values for that
+    run evaluated alone, and every run reports its own status."""
+    sh, m = llama7b
+    g = _load("llama7b_runs")
+    T, n = g["prefix"], 4
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    snapshot = kv.raw().copy()
+    for q in range(2):
+        recs = g["runs"][4 * q:4 * q + 4]
+        stops = [g["cancel_before_layer"][4 * q + j] for j in range(4)]
+        parent = np.concatenate([np.where(np.asarray(r["parent"]) >= 0, np.asarray(r["parent"]) + n * j, -1)
+                                 for j, r in enumerate(recs)]).astype(np.int32)
+        toks = np.concatenate([np.asarray(r["tokens"]) for r in recs]).astype(np.int32)
+        rd = synth.tree_run(parent, T, T, offset=4 * n * q)
+        run = gpu_loader.make_run(rd, toks)
+        groups = [j for j in range(4) for _ in range(n)]
+        logits = torch.zeros((4 * n, sh.vocab), device="cuda")
+        hid = [torch.zeros((4 * n, sh.d_model), device="cuda") for _ in range(2)]
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        gstat = torch.full((4, 2), -9, dtype=torch.int32, device="cuda")
+        flags = torch.zeros(4, dtype=torch.int32, device="cuda")
+        cuts = sorted({s for s in stops if s > 0})          # stage boundaries at which words are raised
+        for j, s in enumerate(stops):
+            if s == 0:
+                flags[j] = 1
+        begin, hin = 0, None
+        for k, cut in enumerate(cuts + [sh.n_layers]):
+            last = cut == sh.n_layers
+            pi.stage_forward_multi(m, kv, run, groups, begin, cut, hidden_in=hin,
+                                   hidden_out=None if last else hid[k % 2], logits_out=logits if last else None,
+                                   cancel_flags=flags, group_status=gstat, run_status=status)
+            for j, s in enumerate(stops):
+                if s == cut:
+                    flags[j] = 1                             # in-stream store between two stage calls
+            begin, hin = cut, hid[k % 2]
+        torch.cuda.synchronize()
+        if all(s >= 0 for s in stops):                       # every run of the pass cancelled: the pass itself stops
+            assert status.cpu().tolist() == [pi.PI_CANCELLED, max(stops)]
+        else:
+            assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+        want = [[pi.PI_CANCELLED, s] if s >= 0 else [pi.PI_OK, sh.n_layers] for s in stops]
+        assert gstat.cpu().tolist() == want
+        lg = logits.cpu().numpy()
+        for j, rec in enumerate(recs):
+            if stops[j] < 0:
+                _check_rows(lg[n * j:n * j + n], rec["rows"], cols)
+        pi.kv_rollback(kv, run.slots, 4 * n)
+        torch.cuda.synchronize()
+        assert np.array_equal(kv.raw(), snapshot)
+
+
 def test_tinyllama_decode_steps_match_oracle():
     """TinyLlama-shaped draft model (grouped-query attention, 4 KV heads x 64): single-token decode
     steps at short and long prefixes, the generator side's workload."""
