@@ -59,3 +59,15 @@ def test_null_and_shape_arguments_are_refused_without_touching_a_device():
     assert lib.pi_stage_forward(None, None, None, 0, 1, None, None, None, None, None, None) == pi.binding.PI_E_ARG
     assert lib.pi_verify_greedy(None, None, 1, None, 16, 0, None, None, None) == pi.binding.PI_E_ARG
     assert lib.pi_kv_rollback(None, None, 1, None, None, None) == pi.binding.PI_E_ARG
+    # several runs per pass: the description of the runs is checked before anything else
+    run = pi.binding.PiRunDesc(n=4)
+    gd = pi.binding.PiGroupDesc()
+    assert lib.pi_stage_forward_multi(None, None, ctypes.byref(run), None, 0, 1, None, None, None, None, None) == pi.binding.PI_E_ARG
+    grp = (ctypes.c_int32 * 4)(0, 0, 2, 2)                      # run 1 has no token
+    gd.n_groups, gd.group_of_token = 3, ctypes.cast(grp, ctypes.c_void_p)
+    assert lib.pi_stage_forward_multi(None, None, ctypes.byref(run), ctypes.byref(gd), 0, 1, None, None, None, None, None) == pi.binding.PI_E_ARG
+    gd.n_groups = 17
+    assert lib.pi_stage_forward_multi(None, None, ctypes.byref(run), ctypes.byref(gd), 0, 1, None, None, None, None, None) == pi.binding.PI_E_SHAPE
+    grp2 = (ctypes.c_int32 * 4)(0, 1, 1, 0)
+    gd.n_groups, gd.group_of_token = 2, ctypes.cast(grp2, ctypes.c_void_p)
+    assert lib.pi_stage_forward_multi(None, None, ctypes.byref(run), ctypes.byref(gd), 0, 1, None, None, None, None, None) == pi.binding.PI_E_ARG  # no model
