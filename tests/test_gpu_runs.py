@@ -200,3 +200,31 @@ def test_write_into_live_cell_is_refused():
     assert status.cpu().tolist() == [pi.PI_E_SLOT_LIVE, 0]
     assert np.array_equal(gkv.raw(), snapshot)
     gm.free()
+
+
+def test_barrier_numbers_wrap_around():
+    """The grid barrier compares barrier numbers modulo 2^16: enough launches on one model to pass
+    that point several times give the same bits as the first."""
+    sh, om, okv, gm, gkv = _setup("tiny", 16, 96)
+    rd = synth.linear_run(3, 16)
+    toks = synth.tokens_host(sh, 5, 3, synth.T_DRAFT)
+    run = gpu_loader.make_run(rd, toks)
+    logits = torch.zeros((3, sh.vocab), device="cuda")
+    status = torch.full((2,), -9, dtype=torch.int32, device="cuda")
+    per_launch = 5 * sh.n_layers + 4
+    launches = 2 * 65536 // per_launch + 50
+    first = None
+    for it in range(launches):
+        pi.stage_forward(gm, gkv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+        pi.kv_rollback(gkv, run.slots, 3)
+        if it == 0:
+            torch.cuda.synchronize()
+            first = logits.clone()
+        if it % 2000 == 1999:
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+            assert torch.equal(logits, first)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+    assert torch.equal(logits, first)
+    gm.free()
