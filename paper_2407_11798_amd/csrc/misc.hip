@@ -19,10 +19,33 @@ __global__ void __launch_bounds__(256) verify_kernel(const int32_t* draft, const
   const float* lg = logits + (size_t)row * vocab;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int v = threadIdx.x; v < vocab; v += blockDim.x) {
-    const float f = lg[v];
+  // 16 bytes per load, four loads in flight per thread (the scan is a chain of memory round trips
+  // otherwise); rows start 16-byte aligned when the vocabulary is a multiple of four
+  const auto take = [&](float f, int v) {
     if (f > bv || (f == bv && v < bi)) { bv = f; bi = v; }
+  };
+  int v0 = 0;
+  if ((vocab & 3) == 0 && ((size_t)lg & 15) == 0) {
+    const float4* lg4 = (const float4*)lg;
+    const int quads = vocab >> 2, step = blockDim.x;
+    int q = threadIdx.x;
+    for (; q + 3 * step < quads; q += 4 * step) {
+      float4 t[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) t[k] = lg4[q + k * step];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int v = (q + k * step) * 4;
+        take(t[k].x, v); take(t[k].y, v + 1); take(t[k].z, v + 2); take(t[k].w, v + 3);
+      }
+    }
+    for (; q < quads; q += step) {
+      const float4 t = lg4[q];
+      take(t.x, q * 4); take(t.y, q * 4 + 1); take(t.z, q * 4 + 2); take(t.w, q * 4 + 3);
+    }
+    v0 = vocab;
   }
+  for (int v = v0 + threadIdx.x; v < vocab; v += blockDim.x) take(lg[v], v);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
     const float ov = __shfl_xor(bv, o);
