@@ -36,14 +36,14 @@ def row_record(logits_row, cols):
 
 
 def llama7b_linear():
-    """Llama-7B-shaped bf16 target, 512 synthetic prefix cells, linear runs of 1, 4 and 8 draft tokens."""
+    """Llama-7B-shaped bf16 target, 512 synthetic prefix cells, linear runs of 1, 4, 8 and 16 draft tokens."""
     sh = synth.SHAPES["llama7b"]
     seed, T = 0, 512
     om = from_synth.model_from_seed(sh, seed)
     base = from_synth.kv_synthetic(sh, seed, T + 64, T)
     cols = sample_cols(sh.vocab, seed)
     out = {"shape": sh.name, "seed": seed, "prefix": T, "cols": cols, "runs": {}}
-    for n in (1, 4, 8):
+    for n in (1, 4, 8, 16):
         t0 = time.time()
         run = synth.linear_run(n, T)
         toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT, salt=n)
