@@ -18,7 +18,8 @@
  *  - pi_model and pi_kv own their device memory until the matching *_free.  A pi_model
  *    carries one set of activation scratch buffers: at most one forward per model may be
  *    in flight at a time (issue them on one stream, or serialise streams with events).
- *  - Tokens per run: 1 .. PI_MAX_BATCH.  All sizes are validated on the host before any
+ *  - Tokens per weight pass: 1 .. PI_MAX_BATCH (of one run, or of up to PI_MAX_GROUPS runs
+ *    sharing the pass).  All sizes are validated on the host before any
  *    launch; a shape the kernels do not support returns PI_E_SHAPE, never a launch.
  */
 #ifndef PIPEINFER_H
@@ -39,7 +40,7 @@ extern "C" {
 #define PI_E_HIP (-5)       /* HIP runtime error */
 #define PI_E_STATE (-6)     /* model not fully loaded / handle misuse */
 
-#define PI_MAX_BATCH 16  /* tokens per run */
+#define PI_MAX_BATCH 16  /* tokens per weight pass */
 #define PI_WINDOW 64     /* cells addressable by one run's mask word */
 
 #define PI_DTYPE_F32 0
