@@ -361,6 +361,8 @@ __device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, in
   advance_loads(S, P, TB);
 }
 
+constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;  // all-ones: "nothing here yet" in buffers that workgroups poll
+
 // ---- activation staging (once per phase and workgroup) ---------------------------------------
 // LDS slot (tt, g, i) holds x[i][32(t0+tt) + 8g + 0..7] (times the gain), in two 16-byte halves
 // lo_off = (nt + 1) * 4 * n slots apart: bf16 model: the hi parts and the lo parts of the eight
@@ -374,10 +376,14 @@ __device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, in
 // first weight tiles travel together and the activations, being older, are waited for alone.
 // (A load inside a branch would be waited for at the join, together with everything younger.)
 // `post` runs before the closing workgroup barrier.
+// poll_limit > 0: the activations may still be on their way (no grid barrier separates this phase
+// from their producer); a 16-byte piece that reads as the all-ones "empty" pattern is read again,
+// at most poll_limit times.  Their producer overwrites every piece, and a later phase puts the
+// pattern back once every workgroup has staged them.
 template <int DT, typename Mid, typename Post>
 __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
                                         const float* ssq, int n_blocks, float eps, float* red, float* rscale,
-                                        Mid&& mid, Post&& post) {
+                                        Mid&& mid, Post&& post, unsigned poll_limit, bool* timed_out) {
   const int items = nt * n * 4;
   const int lo_off = (nt + 1) * 4 * n;
   const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
@@ -403,7 +409,7 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
   const __amdgpu_buffer_rsrc_t gr = make_rsrc(gain ? gain : xin, gain ? (uint32_t)K * 4u : 0u);  // no gain: zeros, no traffic
   auto batch = [&](int id0, auto&& between) {
     f32x4 p[2][2], gq[2][2];
-    int slot[2];
+    int slot[2], xoff[2];
     bool in_k[2], in_items[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -416,6 +422,7 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
       in_items[q] = id < items;
       in_k[q] = in_items[q] && k0 < K;
       const int off = in_k[q] ? (i * K + k0) * 4 : 0;
+      xoff[q] = off;
       p[q][0] = ld_ag4(xr, off);
       p[q][1] = ld_ag4(xr, off + 16);
       const int goff = in_k[q] ? k0 : 0;
@@ -423,6 +430,28 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
       gq[q][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(gr, goff * 4 + 16, 0, 0));
     }
     between();
+    if (poll_limit) {
+      const auto empty = [](f32x4 t) {
+        return __float_as_uint(t[0]) == kEmptyWord && __float_as_uint(t[1]) == kEmptyWord;
+      };
+      for (unsigned spin = 0;; ++spin) {
+        bool missing = false;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) missing = missing || (in_k[q] && (empty(p[q][0]) || empty(p[q][1])));
+        if (!__syncthreads_or(missing)) break;  // the whole workgroup goes round again together
+        if (spin >= poll_limit) {               // the same count in every thread: a uniform way out
+          *timed_out = true;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          p[q][0] = ld_ag4(xr, xoff[q]);
+          p[q][1] = ld_ag4(xr, xoff[q] + 16);
+        }
+      }
+      wave_settle();  // the re-reads are younger than the weight loads: leave nothing of them pending
+    }
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       if (!in_items[q]) continue;
@@ -573,7 +602,7 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
 // other than 0 store their sums to memory (a tile is "empty" while it holds the all-ones
 // pattern, which no sum can produce); slice 0 polls them (bounded), adds them in slice order,
 // marks them empty again for the next use and runs the epilogue.
-constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;
+constexpr unsigned kPollLimit = 1u << 20;  // re-reads of activations on their way (each a memory round trip): seconds
 constexpr int kMaxResidBlocks = 8;  // residual rows of at most this many row blocks per workgroup are kept in LDS
 
 struct FlushCtx {
@@ -581,6 +610,8 @@ struct FlushCtx {
   int* pflag;   // LDS [waves]: tag of the phase in which the wave last parked a tile
   unsigned tag;
   int trace_key;
+  float* rearm;     // when set: this phase puts the "empty" pattern back into the first rearm_n floats
+  int rearm_n;      // of that buffer (every workgroup a share), before its stores are drained
 };
 
 // Returns whether global memory was touched (false: the tile was parked in LDS and that is all).
@@ -775,6 +806,15 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.rb = uni(C.rb);
   }
   if (C.t > 0) (void)flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
+  if (F.rearm) {
+    const int pieces = F.rearm_n / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
+    const __amdgpu_buffer_rsrc_t rr = rsrc_of(F.rearm);
+    const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
+    for (int j = (int)threadIdx.x; j < per; j += kThreads) {
+      const int piece = (int)blockIdx.x * per + j;
+      if (piece < pieces) __builtin_amdgcn_raw_buffer_store_b128(empty, rr, piece * 16, 0, kAgent);
+    }
+  }
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
   // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
   // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
@@ -1214,7 +1254,8 @@ template <int DT, int UR>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                            const float* xin, const float* gain, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
-                                           const MatDev* next, int next_sk, int wave, int trace_layer = -1) {
+                                           const MatDev* next, int next_sk, int wave, int trace_layer,
+                                           bool poll_x, float* rearm, int rearm_n) {
   stream_make_uniform(S);
   const size_t xbytes = (size_t)(S.nt + 1) * 128 * A.n;
   float* red = (float*)(lds + xbytes);
@@ -1224,6 +1265,8 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.pflag = pflag;
   F.tag = tag;
   F.trace_key = trace_layer;
+  F.rearm = rearm;
+  F.rearm_n = rearm_n;
   f32x4* resid = F.part + (kWaves - 1) * 64;
   const int Gs = uni((int)gridDim.x / S_k);
   const bool stage_resid = e.epi == EPI_RESID && uni((S.NRB + Gs - 1) / Gs) <= kMaxResidBlocks;  // as sized by the host
@@ -1240,12 +1283,15 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
     rv_live = has_r && i < e.n && row < e.N;
     rv = ld_ag4(rsrc_of(e.out), rv_live ? (i * e.N + row) * 4 : 0);
   }
+  bool timed_out = false;
   EpiCtx e2 = e;
   e2.resid = stage_resid ? resid : nullptr;
   e2.rb0 = S.rb0;
   stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
               [&] { ring_prefetch<DT, UR>(R, S, lane); },
-              [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; });
+              [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; },
+              poll_x ? kPollLimit : 0u, &timed_out);
+  if (timed_out && threadIdx.x == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // (no global store may sit between the weight loads above and the streaming loop: with loads and
   // stores both pending the compiler stops counting and waits for everything at every ring slot)
   consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave);  // drains its stores
@@ -1309,6 +1355,16 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     wave_drain();
   }
+  {  // the attention output starts "empty" whatever an earlier launch left behind
+    const int pieces = A.n * A.n_q_heads * A.head_dim / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
+    const __amdgpu_buffer_rsrc_t rr = rsrc_of(A.o);
+    const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
+    for (int j = (int)threadIdx.x; j < per; j += kThreads) {
+      const int piece = (int)blockIdx.x * per + j;
+      if (piece < pieces) __builtin_amdgcn_raw_buffer_store_b128(empty, rr, piece * 16, 0, kAgent);
+    }
+    wave_drain();
+  }
   Ring<DT, UR> R;
   WaveStream S;
   bool ok = grid_barrier(A, bc, A.layer_begin, false);
@@ -1333,9 +1389,10 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
         break;
       wg_mark(A, l * 8 + 1, 2);
       stream_init<DT>(S, uni_mat(A.layers[l].o), A.sk[1], wave);
-        wg_mark(A, l * 8 + 1, 3);
-      if (!(ok = grid_barrier(A, bc, -1, false, l * 8 + 1))) break;
-        wg_mark(A, l * 8 + 1, 5);
+      // No grid barrier here: the output projection asks for its weights at once and reads the
+      // attention output until no piece of it is "empty" any more (the merging workgroups are
+      // the last to finish this phase; everyone else's weight requests travel meanwhile).
+      wg_mark(A, l * 8 + 1, 5);
       continue;
     }
     EpiCtx e;
@@ -1386,8 +1443,8 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.N = M.N;
     wg_mark(A, l * 8 + k, 0);
     proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, bc.epoch + 1, lane,
-                       has_next ? &nxt : nullptr, nsk, wave,
-                       l * 8 + k);
+                       has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
+                       /*poll_x=*/k == 2, /*rearm=*/k == 3 ? A.o : nullptr, A.n * A.n_q_heads * A.head_dim);
     wg_mark(A, l * 8 + k, 3);
     if (k == 5) break;
     const bool boundary = k == 4;
