@@ -104,7 +104,8 @@ struct StageArgs {
   const int32_t* kv_len;
   // scratch
   float *x, *q, *o, *a, *ssq;
-  float* part;   // [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
+  float* part;   // two halves of [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
+  size_t part_half_floats;  // floats per half
   float* attn_o;   // [Hkv][units][R][hd]
   float* attn_ml;  // [Hkv][units][R][2]
   unsigned* attn_flags;  // [Hkv][attn_flag_stride]: barrier number at which a unit last published

@@ -431,8 +431,10 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
     }
     between();
     if (poll_limit) {
+      // producers store 8 or 16 bytes at a time: a piece is here when neither 8-byte half is empty
       const auto empty = [](f32x4 t) {
-        return __float_as_uint(t[0]) == kEmptyWord && __float_as_uint(t[1]) == kEmptyWord;
+        return (__float_as_uint(t[0]) == kEmptyWord && __float_as_uint(t[1]) == kEmptyWord) ||
+               (__float_as_uint(t[2]) == kEmptyWord && __float_as_uint(t[3]) == kEmptyWord);
       };
       for (unsigned spin = 0;; ++spin) {
         bool missing = false;
@@ -610,6 +612,7 @@ struct FlushCtx {
   int* pflag;   // LDS [waves]: tag of the phase in which the wave last parked a tile
   unsigned tag;
   int trace_key;
+  float* xpart;     // this phase's half of the cross-slice tiles in memory
   float* rearm;     // when set: this phase puts the "empty" pattern back into the first rearm_n floats
   int rearm_n;      // of that buffer (every workgroup a share), before its stores are drained
 };
@@ -645,7 +648,7 @@ __device__ __forceinline__ bool flush_rowblock(const StageArgs& A, const WaveStr
   }
   if (S_k > 1) {
     const bool live = (lane & 15) < e.n;
-    const __amdgpu_buffer_rsrc_t pr = rsrc_of(A.part);
+    const __amdgpu_buffer_rsrc_t pr = rsrc_of(F.xpart);
     if (S.slice != 0) {
       if (live) st_ag4(pr, ((rb * S_k + S.slice) * 64 + lane) * 16, acc);
       return true;
@@ -1256,6 +1259,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
                                            const MatDev* next, int next_sk, int wave, int trace_layer,
                                            bool poll_x, float* rearm, int rearm_n) {
+  if (poll_x) __syncthreads();  // no grid barrier came before: the workgroup's slower waves are done with LDS
   stream_make_uniform(S);
   const size_t xbytes = (size_t)(S.nt + 1) * 128 * A.n;
   float* red = (float*)(lds + xbytes);
@@ -1266,6 +1270,10 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.tag = tag;
   F.trace_key = trace_layer;
   F.rearm = rearm;
+  // Consecutive phases may not be separated by a grid barrier any more, so they use different
+  // halves of the cross-slice tiles: a workgroup ahead in the next phase must not store into a
+  // tile the phase behind it is still collecting.
+  F.xpart = A.part + (size_t)(tag & 1u) * A.part_half_floats;
   F.rearm_n = rearm_n;
   f32x4* resid = F.part + (kWaves - 1) * 64;
   const int Gs = uni((int)gridDim.x / S_k);
@@ -1355,16 +1363,18 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     wave_drain();
   }
-  {  // the attention output starts "empty" whatever an earlier launch left behind
-    const int pieces = A.n * A.n_q_heads * A.head_dim / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
-    const __amdgpu_buffer_rsrc_t rr = rsrc_of(A.o);
+  // the attention output and the SwiGLU output start "empty" whatever an earlier launch left behind
+  for (int which = 0; which < 2; ++which) {
+    const int pieces = A.n * (which ? A.ffn : A.n_q_heads * A.head_dim) / 4;
+    const int per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
+    const __amdgpu_buffer_rsrc_t rr = rsrc_of(which ? A.a : A.o);
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
     for (int j = (int)threadIdx.x; j < per; j += kThreads) {
       const int piece = (int)blockIdx.x * per + j;
       if (piece < pieces) __builtin_amdgcn_raw_buffer_store_b128(empty, rr, piece * 16, 0, kAgent);
     }
-    wave_drain();
   }
+  wave_drain();
   Ring<DT, UR> R;
   WaveStream S;
   bool ok = grid_barrier(A, bc, A.layer_begin, false);
@@ -1442,11 +1452,13 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     e.N = M.N;
     wg_mark(A, l * 8 + k, 0);
-    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, bc.epoch + 1, lane,
+    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
                        has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
-                       /*poll_x=*/k == 2, /*rearm=*/k == 3 ? A.o : nullptr, A.n * A.n_q_heads * A.head_dim);
+                       /*poll_x=*/k == 2 || k == 4, /*rearm=*/k == 3 ? A.o : (k == 0 ? A.a : nullptr),
+                       k == 3 ? A.n * A.n_q_heads * A.head_dim : A.n * A.ffn);
     wg_mark(A, l * 8 + k, 3);
     if (k == 5) break;
+    if (k == 3) continue;  // no grid barrier: the down projection reads the SwiGLU output until all of it is there
     const bool boundary = k == 4;
     if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
     wg_mark(A, l * 8 + k, 5);
