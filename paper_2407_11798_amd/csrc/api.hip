@@ -28,6 +28,7 @@ struct pi_model {
   LayerDev* layers_dev = nullptr;
   // activation scratch of the one run in flight
   float *x = nullptr, *q = nullptr, *o = nullptr, *a = nullptr, *ssq = nullptr, *part = nullptr;
+  unsigned* kv_ready = nullptr;
   RunState* rs = nullptr;
   StageSync* sync = nullptr;
   unsigned long long* trace = nullptr;  // timestamps of the barriers of the last run
@@ -41,7 +42,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
-  size_t part_tiles = 0;  // capacity of each half of `part`, in 1 KiB tiles
+  size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
   int n_q_rows() const { return cfg.n_q_heads * cfg.head_dim; }
   int n_kv_rows() const { return cfg.n_kv_heads * cfg.head_dim; }
 };
@@ -217,6 +218,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (e == hipSuccess) e = dev_alloc(m, &m->o, (size_t)PI_MAX_BATCH * nq * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->a, (size_t)PI_MAX_BATCH * c.ffn * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->ssq, (size_t)(d / 16) * 16 * sizeof(float), true);
+  if (e == hipSuccess) e = dev_alloc(m, &m->kv_ready, (size_t)(2 * c.n_kv_heads * c.head_dim / 16) * sizeof(unsigned), true);
   if (e == hipSuccess) {
     int dev = 0;
     hipDeviceProp_t prop;
@@ -231,8 +233,8 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
       StagePlan sp;
       if (make_stage_plan(m, n, &sp) && sp.part_tiles > tiles) tiles = sp.part_tiles;
     }
-    e = dev_alloc(m, &m->part, 2 * tiles * 1024, false);  // two halves, used by alternate phases
-    if (e == hipSuccess) e = hipMemset(m->part, 0xFF, 2 * tiles * 1024);
+    e = dev_alloc(m, &m->part, 3 * tiles * 1024, false);  // three regions, one per kind of phase in a barrier-free chain
+    if (e == hipSuccess) e = hipMemset(m->part, 0xFF, 3 * tiles * 1024);
     if (e == hipSuccess) m->part_tiles = tiles;
   }
   if (e == hipSuccess) e = dev_alloc(m, &m->rs, sizeof(RunState), true);
@@ -400,8 +402,8 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
   if (tiles > m->part_tiles) {
     hipError_t e = hipDeviceSynchronize();
     float* grown = nullptr;
-    if (e == hipSuccess) e = dev_alloc(m, &grown, 2 * tiles * 1024, false);
-    if (e == hipSuccess) e = hipMemset(grown, 0xFF, 2 * tiles * 1024);
+    if (e == hipSuccess) e = dev_alloc(m, &grown, 3 * tiles * 1024, false);
+    if (e == hipSuccess) e = hipMemset(grown, 0xFF, 3 * tiles * 1024);
     if (e != hipSuccess) {
       m->sk_override[phase] = 0;
       return hip_status(e);
@@ -679,6 +681,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.o = m->o;
   a.a = m->a;
   a.ssq = m->ssq;
+  a.kv_ready = m->kv_ready;
   a.part = m->part;
   a.part_half_floats = m->part_tiles * 256;
   a.attn_o = kv->attn_o;

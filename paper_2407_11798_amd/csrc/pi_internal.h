@@ -104,11 +104,12 @@ struct StageArgs {
   const int32_t* kv_len;
   // scratch
   float *x, *q, *o, *a, *ssq;
-  float* part;   // two halves of [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
-  size_t part_half_floats;  // floats per half
+  float* part;   // three regions of [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
+  size_t part_half_floats;  // floats per region
   float* attn_o;   // [Hkv][units][R][hd]
   float* attn_ml;  // [Hkv][units][R][2]
   unsigned* attn_flags;  // [Hkv][attn_flag_stride]: barrier number at which a unit last published
+  unsigned* kv_ready;    // [2 * n_kv_rows / 16]: per 16-row block of K, then of V: the tag of the QKV phase that last wrote the run's cells
   int attn_flag_stride;
   RunState* rs;
   StageSync* sync;

@@ -525,6 +525,8 @@ struct EpiCtx {
   const int32_t* positions;
   const int32_t* slots;
   unsigned dead_tokens;  // QKV: tokens of cancelled runs
+  unsigned* kv_ready;    // QKV: per 16-row block of K and V, raised to kv_tag once the block's cells are in memory
+  unsigned kv_tag;
   const float2* rope;
   const f32x4* resid;  // RESID: LDS copy of the residual rows of the workgroup's row blocks, [row block][lane]
   int rb0;             // first row block of the workgroup
@@ -548,26 +550,35 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
   const int row = rb * kRowBlock + g * 4;
   const bool live = i < e.n;
   if (EPI == EPI_QKV) {
-    if (!live) return;
-    const float r = rscale[i];
-    float v[4] = {acc[0] * r, acc[1] * r, acc[2] * r, acc[3] * r};
     const int hd = e.head_dim;
-    if (row < e.n_q_rows + e.n_kv_rows) {  // q or k: rotary embedding on adjacent pairs
-      const int dim = row % hd;
-      const float2* cs = e.rope + (size_t)e.positions[i] * (hd / 2) + dim / 2;
-      const float2 c0 = cs[0], c1 = cs[1];
-      const float a0 = v[0] * c0.x - v[1] * c0.y, a1 = v[0] * c0.y + v[1] * c0.x;
-      const float a2 = v[2] * c1.x - v[3] * c1.y, a3 = v[2] * c1.y + v[3] * c1.x;
-      v[0] = a0; v[1] = a1; v[2] = a2; v[3] = a3;
+    if (live) {
+      const float r = rscale[i];
+      float v[4] = {acc[0] * r, acc[1] * r, acc[2] * r, acc[3] * r};
+      if (row < e.n_q_rows + e.n_kv_rows) {  // q or k: rotary embedding on adjacent pairs
+        const int dim = row % hd;
+        const float2* cs = e.rope + (size_t)e.positions[i] * (hd / 2) + dim / 2;
+        const float2 c0 = cs[0], c1 = cs[1];
+        const float a0 = v[0] * c0.x - v[1] * c0.y, a1 = v[0] * c0.y + v[1] * c0.x;
+        const float a2 = v[2] * c1.x - v[3] * c1.y, a3 = v[2] * c1.y + v[3] * c1.x;
+        v[0] = a0; v[1] = a1; v[2] = a2; v[3] = a3;
+      }
+      if (row < e.n_q_rows) {
+        st_ag4(rsrc_of(e.out), (i * e.n_q_rows + row) * 4, f32x4{v[0], v[1], v[2], v[3]});
+      } else if (row < e.n_q_rows + 2 * e.n_kv_rows) {
+        const bool is_k = row < e.n_q_rows + e.n_kv_rows;
+        const int kr = row - e.n_q_rows - (is_k ? 0 : e.n_kv_rows);
+        const int head = kr / hd, dim = kr % hd;
+        const size_t idx = ((size_t)head * e.n_cells + e.slots[i]) * hd + dim;
+        if (!((e.dead_tokens >> i) & 1u)) store_kv4(is_k ? e.kcache : e.vcache, e.kv_dtype, idx, v);  // a cancelled run writes no more K/V
+      }
     }
-    if (row < e.n_q_rows) {
-      st_ag4(rsrc_of(e.out), (i * e.n_q_rows + row) * 4, f32x4{v[0], v[1], v[2], v[3]});
-    } else if (row < e.n_q_rows + 2 * e.n_kv_rows) {
-      const bool is_k = row < e.n_q_rows + e.n_kv_rows;
-      const int kr = row - e.n_q_rows - (is_k ? 0 : e.n_kv_rows);
-      const int head = kr / hd, dim = kr % hd;
-      const size_t idx = ((size_t)head * e.n_cells + e.slots[i]) * hd + dim;
-      if (!((e.dead_tokens >> i) & 1u)) store_kv4(is_k ? e.kcache : e.vcache, e.kv_dtype, idx, v);  // a cancelled run writes no more K/V
+    // Attention is not behind a grid barrier: it reads the queries until none is "empty", and the
+    // window's cells once the words of their 16-row blocks say this phase has written them.  A row
+    // block is all Q, all K or all V, so the whole wave takes this branch together.
+    const int kv0 = rb * kRowBlock - e.n_q_rows;
+    if (kv0 >= 0 && kv0 < 2 * e.n_kv_rows) {
+      wave_drain();  // the block's cells are in memory
+      if (lane == 0) __hip_atomic_store(e.kv_ready + kv0 / kRowBlock, e.kv_tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   } else if (EPI == EPI_RESID) {
     float s = 0.0f;
@@ -613,8 +624,10 @@ struct FlushCtx {
   unsigned tag;
   int trace_key;
   float* xpart;     // this phase's half of the cross-slice tiles in memory
-  float* rearm;     // when set: this phase puts the "empty" pattern back into the first rearm_n floats
-  int rearm_n;      // of that buffer (every workgroup a share), before its stores are drained
+  // buffers this phase puts the "empty" pattern back into (the first rearm_n floats, every workgroup
+  // a share), before its stores are drained; null: none
+  float* rearm[2];
+  int rearm_n[2];
 };
 
 // Returns whether global memory was touched (false: the tile was parked in LDS and that is all).
@@ -809,9 +822,10 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.rb = uni(C.rb);
   }
   if (C.t > 0) (void)flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
-  if (F.rearm) {
-    const int pieces = F.rearm_n / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
-    const __amdgpu_buffer_rsrc_t rr = rsrc_of(F.rearm);
+  for (int b = 0; b < 2; ++b) {
+    if (!F.rearm[b]) continue;
+    const int pieces = F.rearm_n[b] / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
+    const __amdgpu_buffer_rsrc_t rr = rsrc_of(F.rearm[b]);
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
     for (int j = (int)threadIdx.x; j < per; j += kThreads) {
       const int piece = (int)blockIdx.x * per + j;
@@ -907,6 +921,26 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
   const size_t head_elems = (size_t)h * A.n_cells * HD;
 
   __syncthreads();  // LDS of the previous unit / phase is free
+  // No grid barrier separates this phase from the QKV projection.  The unit that takes the window
+  // waits (bounded) until the words of its head's K and V row blocks carry this layer's tag: the
+  // run's cells are then in memory.  (Prefix cells are older than the launch.)
+  if (has_window) {
+    const int blocks = HD / 16, kv_blocks = A.n_kv_heads * blocks;
+    for (unsigned spin = 0;; ++spin) {
+      bool missing = false;
+      if (tid < 2 * blocks) {
+        const int w = (tid < blocks ? 0 : kv_blocks) + h * blocks + (tid % blocks);
+        const unsigned f = __hip_atomic_load(A.kv_ready + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        missing = (int)(f - tag) < 0;
+      }
+      if (!__syncthreads_or(missing)) break;
+      if (spin >= kPollLimit) {
+        if (tid == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
   // ---- stage K rows and V columns (as bf16 terms) ----
   {
     const __amdgpu_buffer_rsrc_t kr = rsrc_of(kl), vr = rsrc_of(vl);
@@ -979,16 +1013,41 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
     const int rows = min(kRG, R - r0);
     __syncthreads();
     // ---- stage the query rows as bf16 hi + lo ----
-    for (int it = tid; it < kRG * (HD / 4); it += kThreads) {
+    // The queries may still be on their way: a piece that reads "empty" is read again (bounded).
+    constexpr int QI = (kRG * (HD / 4) + kThreads - 1) / kThreads;  // items per thread
+    f32x4 qv[QI];
+    int qoff[QI];
+#pragma unroll
+    for (int k = 0; k < QI; ++k) {
+      const int it = tid + k * kThreads;
       const int rr = it / (HD / 4), d4 = (it % (HD / 4)) * 4;
-      f32x4 qv = {0.f, 0.f, 0.f, 0.f};
-      if (rr < rows) {
-        const int r = r0 + rr, gq = r / A.n, i = r % A.n;
-        qv = ld_ag4(qr, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4);
+      const int r = r0 + rr, gq = r / A.n, i = r % A.n;
+      qoff[k] = it < kRG * (HD / 4) && rr < rows ? ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4 : -1;
+      qv[k] = ld_ag4(qr, qoff[k] < 0 ? 0 : qoff[k]);
+    }
+    for (unsigned spin = 0;; ++spin) {
+      bool missing = false;
+#pragma unroll
+      for (int k = 0; k < QI; ++k)
+        missing = missing || (qoff[k] >= 0 && __float_as_uint(qv[k][0]) == kEmptyWord && __float_as_uint(qv[k][1]) == kEmptyWord);
+      if (!__syncthreads_or(missing)) break;
+      if (spin >= kPollLimit) {
+        if (tid == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
       }
-      const uint32_t h0 = pack_bf16(qv[0], qv[1]), h1 = pack_bf16(qv[2], qv[3]);
-      const uint32_t l0 = pack_bf16(qv[0] - bf16_to_f32((uint16_t)h0), qv[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
-      const uint32_t l1 = pack_bf16(qv[2] - bf16_to_f32((uint16_t)h1), qv[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
+      __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+      for (int k = 0; k < QI; ++k) qv[k] = ld_ag4(qr, qoff[k] < 0 ? 0 : qoff[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < QI; ++k) {
+      const int it = tid + k * kThreads;
+      if (it >= kRG * (HD / 4)) continue;
+      const int rr = it / (HD / 4), d4 = (it % (HD / 4)) * 4;
+      const f32x4 v = qoff[k] >= 0 ? qv[k] : f32x4{0.f, 0.f, 0.f, 0.f};
+      const uint32_t h0 = pack_bf16(v[0], v[1]), h1 = pack_bf16(v[2], v[3]);
+      const uint32_t l0 = pack_bf16(v[0] - bf16_to_f32((uint16_t)h0), v[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
+      const uint32_t l1 = pack_bf16(v[2] - bf16_to_f32((uint16_t)h1), v[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
       *(uint2*)(lds + L.q_off[0] + rr * L.kstride + d4 * 2) = make_uint2(h0, h1);
       *(uint2*)(lds + L.q_off[1] + rr * L.kstride + d4 * 2) = make_uint2(l0, l1);
     }
@@ -1258,7 +1317,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            const float* xin, const float* gain, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
                                            const MatDev* next, int next_sk, int wave, int trace_layer,
-                                           bool poll_x, float* rearm, int rearm_n) {
+                                           bool poll_x, int kind) {
   if (poll_x) __syncthreads();  // no grid barrier came before: the workgroup's slower waves are done with LDS
   stream_make_uniform(S);
   const size_t xbytes = (size_t)(S.nt + 1) * 128 * A.n;
@@ -1269,12 +1328,18 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.pflag = pflag;
   F.tag = tag;
   F.trace_key = trace_layer;
-  F.rearm = rearm;
-  // Consecutive phases may not be separated by a grid barrier any more, so they use different
-  // halves of the cross-slice tiles: a workgroup ahead in the next phase must not store into a
-  // tile the phase behind it is still collecting.
-  F.xpart = A.part + (size_t)(tag & 1u) * A.part_half_floats;
-  F.rearm_n = rearm_n;
+  // What the barrier-free phase changes wait on is put back to "empty" where every reader is known
+  // to be done and a grid barrier still comes before the next writer: the attention output and
+  // the queries at the end of gate/up (behind the barrier that follows O), the SwiGLU output at
+  // the end of QKV (behind the layer boundary).
+  F.rearm[0] = kind == 3 ? A.o : kind == 0 ? A.a : nullptr;
+  F.rearm_n[0] = kind == 3 ? A.n * A.n_q_heads * A.head_dim : A.n * A.ffn;
+  F.rearm[1] = kind == 3 ? A.q : nullptr;
+  F.rearm_n[1] = A.n * A.n_q_heads * A.head_dim;
+  // Phases in a row without a grid barrier between them (QKV, O; gate/up, down) use different
+  // regions of the cross-slice tiles: a workgroup ahead in a later phase must not store into a
+  // tile an earlier phase is still collecting.  Kinds 0, 2, 3, 4 -> regions 0, 2, 0, 1.
+  F.xpart = A.part + (size_t)(kind % 3) * A.part_half_floats;
   f32x4* resid = F.part + (kWaves - 1) * 64;
   const int Gs = uni((int)gridDim.x / S_k);
   const bool stage_resid = e.epi == EPI_RESID && uni((S.NRB + Gs - 1) / Gs) <= kMaxResidBlocks;  // as sized by the host
@@ -1363,11 +1428,11 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     wave_drain();
   }
-  // the attention output and the SwiGLU output start "empty" whatever an earlier launch left behind
-  for (int which = 0; which < 2; ++which) {
-    const int pieces = A.n * (which ? A.ffn : A.n_q_heads * A.head_dim) / 4;
+  // the attention output, the SwiGLU output and the queries start "empty" whatever an earlier launch left behind
+  for (int which = 0; which < 3; ++which) {
+    const int pieces = A.n * (which == 1 ? A.ffn : A.n_q_heads * A.head_dim) / 4;
     const int per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
-    const __amdgpu_buffer_rsrc_t rr = rsrc_of(which ? A.a : A.o);
+    const __amdgpu_buffer_rsrc_t rr = rsrc_of(which == 0 ? A.o : which == 1 ? A.a : A.q);
     const u32x4 empty = {kEmptyWord, kEmptyWord, kEmptyWord, kEmptyWord};
     for (int j = (int)threadIdx.x; j < per; j += kThreads) {
       const int piece = (int)blockIdx.x * per + j;
@@ -1417,6 +1482,8 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.positions = A.positions;
     e.slots = A.slots;
     e.dead_tokens = dead_tokens;
+    e.kv_ready = A.kv_ready;
+    e.kv_tag = bc.epoch + 1;  // attention of this layer starts without a barrier in between and looks for the same number
     e.rope = A.rope;
     e.resid = nullptr;
     e.rb0 = 0;
@@ -1454,11 +1521,12 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     wg_mark(A, l * 8 + k, 0);
     proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
                        has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
-                       /*poll_x=*/k == 2 || k == 4, /*rearm=*/k == 3 ? A.o : (k == 0 ? A.a : nullptr),
-                       k == 3 ? A.n * A.n_q_heads * A.head_dim : A.n * A.ffn);
+                       /*poll_x=*/k == 2 || k == 4, /*kind=*/k);
     wg_mark(A, l * 8 + k, 3);
     if (k == 5) break;
-    if (k == 3) continue;  // no grid barrier: the down projection reads the SwiGLU output until all of it is there
+    // no grid barrier behind QKV and gate/up: attention waits for the queries and the run's cells,
+    // the down projection for the SwiGLU output
+    if (k == 0 || k == 3) continue;
     const bool boundary = k == 4;
     if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
     wg_mark(A, l * 8 + k, 5);
