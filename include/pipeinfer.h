@@ -158,7 +158,10 @@ typedef struct {
  *   run_status: device-visible int32[2], written by the device: [0] = PI_OK, PI_CANCELLED
  *              or PI_E_SLOT_LIVE, [1] = layers_done = index of the first layer NOT
  *              evaluated (== layer_end on success).  K/V of layers < layers_done were
- *              written to the run's slots; clean them with pi_kv_rollback.
+ *              written to the run's slots; clean them with pi_kv_rollback.  [0] = PI_E_HIP
+ *              means a bounded wait inside the kernel ran out (workgroups wait for each
+ *              other's data for at most about two seconds): the outputs and the model's
+ *              scratch state are undefined after that; free the model and the cache.
  * Asynchronous: returns PI_OK after enqueueing; read run_status after synchronising. */
 int32_t pi_stage_forward(pi_model* m, pi_kv* kv, const pi_run_desc* run, int32_t layer_begin,
                          int32_t layer_end, const float* hidden_in, float* hidden_out,
