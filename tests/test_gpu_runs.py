@@ -228,3 +228,29 @@ def test_barrier_numbers_wrap_around():
     assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
     assert torch.equal(logits, first)
     gm.free()
+
+
+def test_plan_override_grows_the_cross_slice_buffer():
+    """Asking for more column slices than the built-in plan needs more cross-slice tiles than were
+    allocated at load: the override grows the buffer (it used to be written past its end), and the
+    results stay within tolerance of the oracle for every split."""
+    sh, om, okv, gm, gkv = _setup("tiny_bf16", 16, 96)
+    rd = synth.linear_run(6, 16)
+    toks = synth.tokens_host(sh, 9, 6, synth.T_DRAFT)
+    ref = oracle.stage_forward(om, okv.clone(), rd, 0, sh.n_layers, tokens=toks)["logits"]
+    for plan in [(1, 1, 1, 1, 1), (2, 2, 2, 2, 2), (1, 2, 1, 2, 1), (0, 0, 0, 0, 0)]:
+        for phase, sk in enumerate(plan):
+            gm.set_plan(phase, sk)
+        st, done, lg, _, grun = forward(gm, gkv, rd, toks)
+        assert (st, done) == (pi.PI_OK, sh.n_layers), plan
+        assert _tol_ok(lg, ref, sh.dtype), plan
+        pi.kv_rollback(gkv, grun.slots, 6)
+    # a split that leaves a slice fewer tiles than the smallest ring is refused, not launched
+    gm.set_plan(0, 8)
+    with pytest.raises(pi.PiError) as err:
+        forward(gm, gkv, rd, toks)
+    assert err.value.status == pi.PI_E_SHAPE
+    gm.set_plan(0, 0)
+    st, done, lg, _, grun = forward(gm, gkv, rd, toks)
+    assert (st, done) == (pi.PI_OK, sh.n_layers) and _tol_ok(lg, ref, sh.dtype)
+    gm.free()
