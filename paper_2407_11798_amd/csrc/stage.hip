@@ -1,15 +1,18 @@
 // The stage kernel: one persistent launch evaluates a whole slice of decoder layers.
 //
 // One workgroup of 8 waves per compute unit stays resident for the whole stage and walks the
-// phases of every layer (QKV projection, attention, output projection, gate/up, down), with a
-// grid-wide barrier between phases.  Weights never wait for activations: each wave owns a
-// fixed, contiguous range of weight tiles in every phase and keeps a ring of 16 outstanding
-// 128-bit non-temporal loads, which it refills for the NEXT phase before it arrives at the
-// barrier, so HBM stays busy while the grid synchronises.
+// phases of every layer (QKV projection, attention, output projection, gate/up, down).  Two
+// grid-wide barriers per layer remain (after the output projection and at the layer boundary);
+// the other three phase changes wait for the data itself: the buffers a phase reads start out
+// holding an all-ones "empty" word and the reader re-reads, a bounded number of times, until
+// none is left.  Each wave owns a fixed, contiguous range of weight tiles in every phase and
+// keeps a ring of up to 16 outstanding 128-bit non-temporal loads per lane, which it starts
+// while the phase's activations are still on their way into LDS.
 //
-// Early Inference Cancellation: the last workgroup to arrive at a layer-boundary barrier
-// probes the device-visible cancel flag and publishes the decision with the barrier release,
-// so every workgroup takes the same decision and a cancelled run stops within one layer.
+// Early Inference Cancellation: at every layer-boundary barrier the first wave of workgroup 0
+// probes the device-visible cancel flag of each run that is still alive (one lane per run) and
+// publishes the set of dead tokens in the barrier word itself, so every workgroup takes the
+// same decision and a cancelled run stops within one layer.
 //
 // Cross-workgroup data (activations, split-k partial tiles, counters) is written and read
 // with agent-scope accesses that bypass the per-XCD L2, which is not coherent across XCDs;
