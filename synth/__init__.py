@@ -252,6 +252,31 @@ def tree_run(parent: np.ndarray, prefix_len: int, window_base: int, offset: int 
             "mask": mask, "prefix_len": int(prefix_len), "window_base": int(window_base), "n": n}
 
 
+def tree_sequences(parent: np.ndarray, ids):
+    """One sequence identifier per branch: the k-th leaf (in node order) takes ids[k], and a
+    node belongs to the sequences of all leaves below it.  Returns a list of sorted lists."""
+    n = len(parent)
+    is_leaf = [True] * n
+    for i in range(n):
+        if parent[i] >= 0:
+            is_leaf[int(parent[i])] = False
+    sets = [set() for _ in range(n)]
+    k = 0
+    for i in range(n):
+        if is_leaf[i]:
+            j = i
+            while j >= 0:
+                sets[j].add(int(ids[k]))
+                j = int(parent[j])
+            k += 1
+    return [sorted(s) for s in sets]
+
+
+def n_leaves(parent: np.ndarray) -> int:
+    has_child = set(int(p) for p in parent if p >= 0)
+    return len(parent) - len(has_child)
+
+
 def random_tree(seed: int, salt: int, n: int, max_children: int = 3, max_depth: int = 4):
     """Seeded growth: node 0 is a root; node k attaches to a uniformly chosen earlier node
     that still has < max_children children and depth < max_depth-1 (depth counts the root
