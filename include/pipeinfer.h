@@ -39,6 +39,8 @@ extern "C" {
 #define PI_E_SLOT_LIVE (-4) /* a speculative write targets a live canonical cell */
 #define PI_E_HIP (-5)       /* HIP runtime error */
 #define PI_E_STATE (-6)     /* model not fully loaded / handle misuse */
+#define PI_E_FULL (-7)      /* no free cell in the window / no free sequence identifier */
+#define PI_E_BUSY (-8)      /* compaction while a partition still holds a cell of the window */
 
 #define PI_MAX_BATCH 16  /* tokens per weight pass */
 #define PI_WINDOW 64     /* cells addressable by one run's mask word */
@@ -219,6 +221,86 @@ int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n,
 int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t* accepted_nodes,
                        const int32_t* result, void* stream);
 
+/* ---- KV cell metadata and sequence partitions ------------------------------------------
+ * Sections "KV Cache" and "Pipelined KV Cache Multibuffering": every cache cell carries the
+ * position of its entry and the set of sequences it belongs to; runs are kept apart by giving
+ * each a sequence identifier of its own, cache edits are edits of this metadata, and the
+ * attention mask is built from it.  Sequence 0 is the canonical sequence; identifiers
+ * 1 .. n_seq-1 are partitions, handed out first-in first-out.  A cell is canonical iff
+ * sequence 0 is in its set, and free iff it is in no sequence.
+ *
+ * The table lives in device memory (pos[n_cells] int32, -1 = free; seq[n_cells] uint32, bit s
+ * = sequence s) so that every edit below is a small kernel enqueued on `stream`, in order with
+ * the forward, verify and rollback calls of the same stream; only the queue of free
+ * identifiers is host state.  A pi_kvmeta is not tied to one pi_kv: it describes cells by
+ * index.  Device arguments: positions[n] int32, tok_seq[n] uint32 (the sequences token i
+ * belongs to: one bit for a linear run, one bit per branch through the node for a tree),
+ * slots/masks/status words as stated.  n is 1 .. PI_MAX_BATCH.
+ *
+ * Token i sees cell c iff seq[c] & tok_seq[i] != 0 and pos[c] <= positions[i]. */
+#define PI_MAX_SEQ 32
+#define PI_SEQ_CANONICAL 0
+#define PI_POS_MAX 0x7fffffff /* "no upper bound" for position ranges [p0, p1) */
+
+typedef struct pi_kvmeta pi_kvmeta;
+
+/* n_cells >= 1, 2 <= n_seq <= PI_MAX_SEQ.  All cells free; the queue holds 1, 2, ...,
+ * n_seq-1 in this order.  Blocking. */
+int32_t pi_kvmeta_alloc(int32_t n_cells, int32_t n_seq, pi_kvmeta** out);
+int32_t pi_kvmeta_free(pi_kvmeta* meta);
+/* Take the identifier at the head of the queue (Section "Sequence partitions").  Host only,
+ * no device work.  PI_E_FULL when every partition is in use. */
+int32_t pi_kvmeta_seq_acquire(pi_kvmeta* meta, int32_t* seq_out);
+/* The run that held `seq` is over: the identifier leaves every cell that is not canonical
+ * (cells left in no sequence are free), then joins the tail of the queue.  The device part
+ * is asynchronous; an identifier acquired again is safe to use on the same stream.
+ * PI_E_ARG if `seq` is not currently held. */
+int32_t pi_kvmeta_seq_release(pi_kvmeta* meta, int32_t seq, void* stream);
+/* Mark cells [cell_begin, cell_begin+n) as holding positions pos_begin .. in the sequences
+ * of seq_mask (prefilled entries); seq_mask 0 frees them.  Asynchronous. */
+int32_t pi_kvmeta_fill(pi_kvmeta* meta, int32_t cell_begin, int32_t n, int32_t pos_begin, uint32_t seq_mask,
+                       void* stream);
+/* Cells for a run's new entries: token i gets the i-th lowest free cell of the window
+ * [window_base, window_base+PI_WINDOW), which then holds (positions[i], tok_seq[i]).
+ * slots_out[n] (device) receives the cells; status[0] (device) PI_OK, or PI_E_FULL when the
+ * window has fewer than n free cells, or PI_E_ARG when a token has a negative position, no
+ * sequence or a sequence the table does not have: then nothing changes and slots_out is all
+ * -1 (which a forward refuses with PI_E_SLOT_LIVE).  Asynchronous. */
+int32_t pi_kvmeta_place(pi_kvmeta* meta, int32_t n, const int32_t* positions, const uint32_t* tok_seq,
+                        int32_t window_base, int32_t* slots_out, int32_t* status, void* stream);
+/* Entries of sequence `src` at positions [p0, p1) also become entries of every sequence in
+ * dst_mask: a copy that moves no data (Sections "Pipelined KV Cache Multibuffering", "Early
+ * cache entry sharing").  Asynchronous. */
+int32_t pi_kvmeta_seq_cp(pi_kvmeta* meta, int32_t src, uint32_t dst_mask, int32_t p0, int32_t p1, void* stream);
+/* Entries at positions [p0, p1) leave every sequence in seq_mask; a cell left in no sequence
+ * is free (Section "KV Cache": rejected entries are removed by editing metadata).
+ * Asynchronous. */
+int32_t pi_kvmeta_seq_rm(pi_kvmeta* meta, uint32_t seq_mask, int32_t p0, int32_t p1, void* stream);
+/* Section "Sequence acceptance and propagation": the accepted path of a run joins every
+ * sequence, up to and including the position of the last accepted token and no further.
+ * accepted_nodes/result are pi_verify_greedy's device outputs; the branch is the lowest
+ * sequence of tok_seq[last accepted node]; result[0] == 0 changes nothing.  Asynchronous. */
+int32_t pi_kvmeta_accept(pi_kvmeta* meta, int32_t n, const int32_t* positions, const uint32_t* tok_seq,
+                         const int32_t* accepted_nodes, const int32_t* result, void* stream);
+/* The attention mask from the metadata (Section "KV Cache"), in the form pi_run_desc takes:
+ * mask_out[i] bit c = token i sees cell window_base+c (bits of cells below prefix_len stay
+ * clear: the prefix covers them).  n_unexpressed[0] (device) counts the (token, cell) pairs
+ * that this form gets wrong -- a cell below prefix_len the token must not see, or a visible
+ * cell in neither prefix nor window; run a forward only if it is 0.  Asynchronous. */
+int32_t pi_kvmeta_build_mask(pi_kvmeta* meta, int32_t n, const int32_t* positions, const uint32_t* tok_seq,
+                             int32_t prefix_len, int32_t window_base, uint64_t* mask_out,
+                             int32_t* n_unexpressed, void* stream);
+/* Move the canonical cells of the window [prefix_len, prefix_len+PI_WINDOW) down to cells
+ * prefix_len, prefix_len+1, ... in position order: metadata, and K/V of every layer of `kv`
+ * (may be NULL: metadata only).  Cells moved away from and not refilled are free; their
+ * data stays.  result[2] (device) = {status, dense length}: PI_E_BUSY with nothing changed
+ * while a cell of the window belongs to partitions only or two canonical window cells hold
+ * one position; else PI_OK, and kv's canonical length becomes the dense length.  No run may
+ * be in flight on another stream.  Asynchronous. */
+int32_t pi_kvmeta_compact(pi_kvmeta* meta, pi_kv* kv, int32_t prefix_len, int32_t* result, void* stream);
+/* Copy the table to the host (either pointer may be NULL).  Blocking. */
+int32_t pi_kvmeta_read(const pi_kvmeta* meta, int32_t* pos_host, uint32_t* seq_host);
+
 const char* pi_strerror(int32_t status);
 
 /* Tuning hook (not needed for correct use): phase 0..4 (QKV, O, gate/up, down, LM head): ask
@@ -230,11 +312,11 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],
  * 3 SwiGLU output [n][ffn]).  Blocking. */
-/* Debug hook: device timestamps (100 MHz clock) taken by workgroup 0 each time it passes a grid
- * barrier of the last run: [0] run latch, [1] stage input ready, then per layer QKV, attention,
- * O, gate/up, down (layer boundary).  count <= 5 * n_layers + 8.  Blocking. */
-int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count);
 int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64_t count);
+/* Debug hook: device timestamps (100 MHz clock) taken by workgroup 0 each time it passes a grid
+ * barrier of the last run: [0] run latch, [1] stage input ready, then two per layer (after the
+ * output projection; layer boundary).  count <= 5 * n_layers + 8.  Blocking. */
+int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count);
 /* Debug hook: per-workgroup timestamps of one phase.  `key` = layer * 8 + phase (0 QKV, 1
  * attention, 2 O, 3 gate/up, 4 down) selects the phase later runs record (-1: none).  With
  * dst_host non-null, first copies the last recording to the host: grid x 8 values of the 100 MHz

@@ -37,6 +37,7 @@ from __future__ import annotations
 import numpy as np
 
 PI_OK = 0
+PI_E_ARG = -1
 PI_E_FULL = -7
 PI_E_BUSY = -8
 WINDOW = 64
@@ -83,8 +84,13 @@ class OracleKVMeta:
 
     def place(self, positions, tok_seqs, window_base: int):
         """Cells for a run's new entries: token i gets the i-th lowest free cell of the
-        window.  Returns (PI_OK, slots) or (PI_E_FULL, None) with nothing changed."""
-        free = [c for c in range(window_base, min(window_base + WINDOW, self.n_cells)) if self.pos[c] < 0]
+        window.  Returns (PI_OK, slots), or with nothing changed (PI_E_FULL, None), or
+        (PI_E_ARG, None) for a token with a negative position, no sequence or an identifier
+        the table does not have."""
+        for p, ss in zip(positions, tok_seqs):
+            if int(p) < 0 or len(ss) == 0 or any(not 0 <= s < self.n_seq for s in ss):
+                return PI_E_ARG, None
+        free =[c for c in range(window_base, min(window_base + WINDOW, self.n_cells)) if self.pos[c] < 0]
         n = len(positions)
         if len(free) < n:
             return PI_E_FULL, None

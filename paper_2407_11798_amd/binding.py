@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libpipeinfer_hip.so")
 
 PI_OK, PI_CANCELLED = 0, 1
 PI_E_ARG, PI_E_SHAPE, PI_E_OOM, PI_E_SLOT_LIVE, PI_E_HIP, PI_E_STATE = -1, -2, -3, -4, -5, -6
+PI_E_FULL, PI_E_BUSY = -7, -8
 PI_MAX_BATCH, PI_WINDOW = 16, 64
+PI_MAX_SEQ, PI_SEQ_CANONICAL, PI_POS_MAX = 32, 0, 0x7FFFFFFF
 PI_DTYPE_F32, PI_DTYPE_BF16 = 0, 1
 PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 (PI_T_EMBED, PI_T_ATTN_NORM, PI_T_WQ, PI_T_WK, PI_T_WV, PI_T_WO, PI_T_FFN_NORM, PI_T_WG, PI_T_WU,
@@ -28,6 +30,9 @@ EXPORTS = [
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
     "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
     "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
+    "pi_kvmeta_alloc", "pi_kvmeta_free", "pi_kvmeta_seq_acquire", "pi_kvmeta_seq_release", "pi_kvmeta_fill",
+    "pi_kvmeta_place", "pi_kvmeta_seq_cp", "pi_kvmeta_seq_rm", "pi_kvmeta_accept", "pi_kvmeta_build_mask",
+    "pi_kvmeta_compact", "pi_kvmeta_read",
 ]
 
 
@@ -87,6 +92,21 @@ def lib():
         L.pi_debug_set_plan.argtypes = [c_void_p, c_int32, c_int32]
         L.pi_debug_read_trace.argtypes = [c_void_p, c_void_p, c_int32]
         L.pi_debug_read_scratch.argtypes = [c_void_p, c_int32, c_void_p, c_int64]
+        c_uint32 = ctypes.c_uint32
+        L.pi_debug_wgtrace.argtypes = [c_void_p, c_int32, c_void_p]
+        L.pi_kvmeta_alloc.argtypes = [c_int32, c_int32, POINTER(c_void_p)]
+        L.pi_kvmeta_free.argtypes = [c_void_p]
+        L.pi_kvmeta_seq_acquire.argtypes = [c_void_p, POINTER(c_int32)]
+        L.pi_kvmeta_seq_release.argtypes = [c_void_p, c_int32, c_void_p]
+        L.pi_kvmeta_fill.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_uint32, c_void_p]
+        L.pi_kvmeta_place.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
+        L.pi_kvmeta_seq_cp.argtypes = [c_void_p, c_int32, c_uint32, c_int32, c_int32, c_void_p]
+        L.pi_kvmeta_seq_rm.argtypes = [c_void_p, c_uint32, c_int32, c_int32, c_void_p]
+        L.pi_kvmeta_accept.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.pi_kvmeta_build_mask.argtypes = [c_void_p, c_int32, c_void_p, c_void_p, c_int32, c_int32, c_void_p,
+                                           c_void_p, c_void_p]
+        L.pi_kvmeta_compact.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
+        L.pi_kvmeta_read.argtypes = [c_void_p, c_void_p, c_void_p]
         for name in EXPORTS:
             if name != "pi_strerror":
                 getattr(L, name).restype = c_int32
@@ -299,3 +319,82 @@ def kv_rollback(kv: KVCache, slots, n: int, accepted_nodes=None, result=None, st
     st = lib().pi_kv_rollback(kv.handle, _ptr(slots), n, _ptr(accepted_nodes), _ptr(result),
                               _stream_handle(stream))
     return _check(st, "pi_kv_rollback")
+
+
+def seq_bits(seqs) -> int:
+    """Sequence identifiers -> the uint32 set the C ABI takes."""
+    m = 0
+    for q in seqs:
+        m |= 1 << int(q)
+    return m
+
+
+class KVMeta:
+    """pi_kvmeta handle: cell metadata (position, sequence set) on the device and the FIFO of
+    free partition identifiers.  Device arguments are torch tensors: positions int32[n],
+    tok_seq int32[n] holding the uint32 bit sets, slots int32[n], mask int64[n], status words
+    int32."""
+
+    def __init__(self, n_cells: int, n_seq: int):
+        self.n_cells, self.n_seq = n_cells, n_seq
+        h = c_void_p()
+        _check(lib().pi_kvmeta_alloc(n_cells, n_seq, byref(h)), "pi_kvmeta_alloc")
+        self.handle = h
+
+    def acquire(self):
+        """Partition identifier at the head of the queue, or None when all are in use."""
+        out = c_int32()
+        st = lib().pi_kvmeta_seq_acquire(self.handle, byref(out))
+        if st == PI_E_FULL:
+            return None
+        _check(st, "pi_kvmeta_seq_acquire")
+        return out.value
+
+    def release(self, seq: int, stream=None):
+        _check(lib().pi_kvmeta_seq_release(self.handle, seq, _stream_handle(stream)), "pi_kvmeta_seq_release")
+
+    def fill(self, cell_begin: int, n: int, pos_begin: int, seq_mask: int, stream=None):
+        _check(lib().pi_kvmeta_fill(self.handle, cell_begin, n, pos_begin, seq_mask, _stream_handle(stream)),
+               "pi_kvmeta_fill")
+
+    def place(self, n: int, positions, tok_seq, window_base: int, slots_out, status, stream=None):
+        _check(lib().pi_kvmeta_place(self.handle, n, _ptr(positions), _ptr(tok_seq), window_base, _ptr(slots_out),
+                                     _ptr(status), _stream_handle(stream)), "pi_kvmeta_place")
+
+    def seq_cp(self, src: int, dst_mask: int, p0: int = 0, p1: int = PI_POS_MAX, stream=None):
+        _check(lib().pi_kvmeta_seq_cp(self.handle, src, dst_mask, p0, p1, _stream_handle(stream)), "pi_kvmeta_seq_cp")
+
+    def seq_rm(self, seq_mask: int, p0: int = 0, p1: int = PI_POS_MAX, stream=None):
+        _check(lib().pi_kvmeta_seq_rm(self.handle, seq_mask, p0, p1, _stream_handle(stream)), "pi_kvmeta_seq_rm")
+
+    def accept(self, n: int, positions, tok_seq, accepted_nodes, result, stream=None):
+        _check(lib().pi_kvmeta_accept(self.handle, n, _ptr(positions), _ptr(tok_seq), _ptr(accepted_nodes),
+                                      _ptr(result), _stream_handle(stream)), "pi_kvmeta_accept")
+
+    def build_mask(self, n: int, positions, tok_seq, prefix_len: int, window_base: int, mask_out, n_unexpressed,
+                   stream=None):
+        _check(lib().pi_kvmeta_build_mask(self.handle, n, _ptr(positions), _ptr(tok_seq), prefix_len, window_base,
+                                          _ptr(mask_out), _ptr(n_unexpressed), _stream_handle(stream)),
+               "pi_kvmeta_build_mask")
+
+    def compact(self, kv, prefix_len: int, result, stream=None):
+        _check(lib().pi_kvmeta_compact(self.handle, None if kv is None else kv.handle, prefix_len, _ptr(result),
+                                       _stream_handle(stream)), "pi_kvmeta_compact")
+
+    def read(self):
+        pos = np.empty(self.n_cells, dtype=np.int32)
+        seq = np.empty(self.n_cells, dtype=np.uint32)
+        _check(lib().pi_kvmeta_read(self.handle, c_void_p(pos.ctypes.data), c_void_p(seq.ctypes.data)),
+               "pi_kvmeta_read")
+        return pos, seq
+
+    def free(self):
+        if self.handle:
+            lib().pi_kvmeta_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass

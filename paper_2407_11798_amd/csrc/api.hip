@@ -59,6 +59,12 @@ struct pi_kv {
   int attn_flag_stride = 0;
 };
 
+namespace pi {
+KvView kv_view(pi_kv* kv) {
+  return KvView{kv->k, kv->v, kv->dtype, kv->n_layers, kv->n_kv_heads, kv->n_cells, kv->head_dim, kv->len_dev};
+}
+}  // namespace pi
+
 namespace {
 
 int32_t hip_status(hipError_t e) {
@@ -168,6 +174,8 @@ const char* pi_strerror(int32_t s) {
     case PI_E_SLOT_LIVE: return "speculative write targets a live canonical cell or leaves the window";
     case PI_E_HIP: return "HIP runtime error";
     case PI_E_STATE: return "model not fully loaded or handle misused";
+    case PI_E_FULL: return "no free cell in the window or no free sequence identifier";
+    case PI_E_BUSY: return "a partition still holds a cell of the window";
     default: return "unknown status";
   }
 }

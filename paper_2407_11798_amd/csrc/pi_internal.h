@@ -128,6 +128,14 @@ struct StageArgs {
   uint32_t group_mask[PI_MAX_GROUPS];  // bit i: token i belongs to the run
 };
 
+// What other translation units may know of a pi_kv (the handle itself is private to the ABI file).
+struct KvView {
+  void *k, *v;
+  int dtype, n_layers, n_kv_heads, n_cells, head_dim;
+  int32_t* len_dev;  // canonical length, on the device
+};
+KvView kv_view(pi_kv* kv);
+
 // ---- launch wrappers (each defined next to its kernels) ---------------------------------
 hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, PackedMat dst,
                          int dst_dtype, int row_mul, int row_add, hipStream_t s);

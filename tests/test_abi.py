@@ -40,11 +40,11 @@ def test_status_strings():
     lib.pi_strerror.restype = ctypes.c_char_p
     lib.pi_strerror.argtypes = [ctypes.c_int32]
     seen = set()
-    for code in (0, 1, -1, -2, -3, -4, -5, -6):
+    for code in (0, 1, -1, -2, -3, -4, -5, -6, -7, -8):
         s = lib.pi_strerror(code)
         assert s and s != b"unknown status"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 10
     assert lib.pi_strerror(12345) == b"unknown status"
 
 
@@ -71,3 +71,26 @@ def test_null_and_shape_arguments_are_refused_without_touching_a_device():
     grp2 = (ctypes.c_int32 * 4)(0, 1, 1, 0)
     gd.n_groups, gd.group_of_token = 2, ctypes.cast(grp2, ctypes.c_void_p)
     assert lib.pi_stage_forward_multi(None, None, ctypes.byref(run), ctypes.byref(gd), 0, 1, None, None, None, None, None) == pi.binding.PI_E_ARG  # no model
+
+
+def test_cell_metadata_calls_refuse_bad_arguments_without_touching_a_device():
+    lib = pi.lib()
+    B = pi.binding
+    out = ctypes.c_void_p()
+    assert lib.pi_kvmeta_alloc(64, 4, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_alloc(0, 4, ctypes.byref(out)) == B.PI_E_SHAPE
+    assert lib.pi_kvmeta_alloc(64, 1, ctypes.byref(out)) == B.PI_E_SHAPE       # no partition beside sequence 0
+    assert lib.pi_kvmeta_alloc(64, 33, ctypes.byref(out)) == B.PI_E_SHAPE
+    assert out.value is None
+    seq = ctypes.c_int32()
+    assert lib.pi_kvmeta_seq_acquire(None, ctypes.byref(seq)) == B.PI_E_ARG
+    assert lib.pi_kvmeta_seq_release(None, 1, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_fill(None, 0, 1, 0, 1, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_place(None, 1, None, None, 0, None, None, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_seq_cp(None, 0, 1, 0, 1, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_seq_rm(None, 1, 0, 1, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_accept(None, 1, None, None, None, None, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_build_mask(None, 1, None, None, 0, 0, None, None, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_compact(None, None, 0, None, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_read(None, None, None) == B.PI_E_ARG
+    assert lib.pi_kvmeta_free(None) == B.PI_E_ARG

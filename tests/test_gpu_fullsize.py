@@ -191,6 +191,74 @@ def test_llama7b_four_runs_per_weight_pass_match_oracle(llama7b):
         assert np.array_equal(kv.raw(), snapshot)
 
 
+def test_llama7b_runs_described_by_cell_metadata(llama7b):
+    """The same eight tree runs, described on the device: every run takes one partition per
+    branch, its cells and window words come from the metadata kernels (they must equal the
+    workload's own descriptors bit for bit), the forward reads them where they lie, the best
+    run is accepted from the device's verification result, all partitions are given back, and
+    compaction leaves a dense canonical prefix that holds the accepted path's entries."""
+    from test_gpu_kvmeta import Pair, dev_i32, dev_sets
+    sh, m = llama7b
+    g = _load("llama7b_runs")
+    T, n = g["prefix"], 4
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    p = Pair(T + 64, 32)
+    p.fill(0, T, 0, range(32))
+    survivors = []
+    all_ids = []
+    for r, rec in enumerate(g["runs"]):
+        parent = np.asarray(rec["parent"], dtype=np.int32)
+        toks = np.asarray(rec["tokens"], dtype=np.int32)
+        rd = synth.tree_run(parent, T, T, offset=n * r)
+        ids = [p.acquire() for _ in range(synth.n_leaves(parent))]
+        assert None not in ids
+        all_ids += ids
+        seqs = synth.tree_sequences(parent, ids)
+        positions = rd["positions"].tolist()
+        st, slots = p.place(positions, seqs, T)
+        mask, bad = p.build_mask(positions, seqs, T, T)
+        assert st == 0 and bad == 0
+        assert np.array_equal(slots.cpu().numpy(), rd["slots"])
+        assert np.array_equal(mask.cpu().numpy().view(np.uint64), rd["mask"])
+        if g["cancel_before_layer"][r] >= 0:
+            continue                                       # a cancelled run: its cells stay unwritten
+        run = gpu_loader.make_run(rd, toks)
+        run.slots, run.mask = slots, mask
+        logits = torch.zeros((n, sh.vocab), device="cuda")
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+        acc = torch.zeros(n, dtype=torch.int32, device="cuda")
+        res = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pi.verify_greedy(run.tokens, run.parent, n, logits, sh.vocab, g["root_expected"], acc, res)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+        _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+        survivors.append((r, int(res[0].item()), acc, res, positions, seqs, slots.cpu().numpy()))
+    p.check("eight runs placed")
+    best = max(survivors, key=lambda x: (x[1], -x[0]))
+    r, a, acc, res, positions, seqs, slots = best
+    p.g.accept(n, dev_i32(positions), dev_sets(seqs), acc, res)          # device results straight in
+    path = acc.cpu().tolist()[:a]
+    p.o.accept(positions, seqs, path)
+    for s in all_ids:
+        p.release(s)
+    p.check("accepted and released")
+    before = kv.raw().copy().reshape(2, sh.n_layers, sh.n_kv_heads, T + 64, sh.head_dim * 2)
+    st, dense = p.compact(T, kv)
+    assert (st, dense) == (0, T + a) and len(kv) == T + a
+    p.check("compaction")
+    after = kv.raw().reshape(before.shape)
+    src = [int(slots[i]) for i in path]                                   # path order == position order
+    want = before.copy()
+    want[:, :, :, T:T + a] = before[:, :, :, src]
+    assert np.array_equal(after, want)
+    assert a == 0 or after[:, :, :, T:T + a].any()
+    pos, seq = p.g.read()
+    assert pos[:T + a].tolist() == list(range(T + a)) and not (pos[T + a:] >= 0).any()
+
+
 def test_tinyllama_decode_steps_match_oracle():
     """TinyLlama-shaped draft model (grouped-query attention, 4 KV heads x 64): single-token decode
     steps at short and long prefixes, the generator side's workload."""
