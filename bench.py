@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cancel", action="store_true", help="skip the cancellation latency trials")
     ap.add_argument("--no-multi-run", action="store_true", help="skip the several-runs-per-pass comparison")
+    ap.add_argument("--no-kv-metadata", action="store_true", help="skip the cell-metadata bookkeeping timing")
     ap.add_argument("--slice-layers", type=int, default=0,
                     help="also time a pipeline stage's share: the first this-many layers as one stage call")
     ap.add_argument("--calibrate-copy", type=int, default=0,
@@ -270,6 +271,78 @@ def main():
                  "one_run_per_pass": {"passes": 8, "ms": t8 * 1e3, "verified_tokens_per_s": 32 / t8},
                  "four_runs_per_pass": {"passes": 2, "ms": t2 * 1e3, "verified_tokens_per_s": 32 / t2}}
 
+    # Cell metadata and sequence partitions: the bookkeeping of one round of eight 4-token tree
+    # runs -- per run: partitions from the queue, cells from the window, window words from the
+    # table; then the best run accepted, every partition given back, and the accepted entries
+    # compacted into the dense prefix (K/V of all layers moved).  Device time per round by events
+    # around the enqueued calls; the oracle's Python bookkeeping of the same round beside it.
+    kvmeta = None
+    if not args.no_kv_metadata:
+        trees = [synth.random_tree(args.seed, 100 + r, 4) for r in range(8)]
+        meta = pi.KVMeta(n_cells, 32)
+        all_seq = (1 << 32) - 1
+        pos_t = [torch.as_tensor(synth.tree_run(tr, T, T)["positions"], device="cuda") for tr in trees]
+        slots_t = [torch.zeros(4, dtype=torch.int32, device="cuda") for _ in trees]
+        mask_t = [torch.zeros(4, dtype=torch.int64, device="cuda") for _ in trees]
+        stat_t = torch.zeros(1, dtype=torch.int32, device="cuda")
+        bad_t = torch.zeros(1, dtype=torch.int32, device="cuda")
+        res_t = torch.zeros(2, dtype=torch.int32, device="cuda")
+        acc_t = torch.as_tensor(np.array([0, -1, -1, -1], dtype=np.int32), device="cuda")
+        one_t = torch.as_tensor(np.array([1, 0], dtype=np.int32), device="cuda")
+
+        def meta_round():
+            meta.fill(0, T, 0, all_seq)
+            meta.fill(T, n_cells - T, 0, 0)
+            held, seqs_dev = [], []
+            for r, tr in enumerate(trees):
+                ids = [meta.acquire() for _ in range(synth.n_leaves(tr))]
+                held += ids
+                sq = torch.as_tensor(np.asarray([pi.seq_bits(x) for x in synth.tree_sequences(tr, ids)],
+                                                dtype=np.uint32).view(np.int32), device="cuda")
+                seqs_dev.append(sq)
+                meta.place(4, pos_t[r], sq, T, slots_t[r], stat_t)
+                meta.build_mask(4, pos_t[r], sq, T, T, mask_t[r], bad_t)
+            meta.accept(4, pos_t[7], seqs_dev[7], acc_t, one_t)          # the last run's root is accepted
+            for s in held:
+                meta.release(s)
+            meta.compact(kv, T, res_t)
+
+        meta_round()
+        torch.cuda.synchronize()
+        assert res_t.cpu().tolist() == [0, T + 1] and int(bad_t.item()) == 0 and int(stat_t.item()) == 0
+        reps = max(3, args.steps // 5)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            meta_round()
+        torch.cuda.synchronize()
+        t_dev = (time.perf_counter() - t0) / reps
+        kv.set_len(T)
+        kvmeta = {"round": "8 tree runs x 4 tokens over %d cells: 8 x (place + build_mask), accept, %d releases, "
+                           "compaction moving 1 cell of %d layers" % (n_cells, sum(synth.n_leaves(t) for t in trees),
+                                                                      shape.n_layers),
+                  "calls_per_round": 2 + 16 + 1 + sum(synth.n_leaves(t) for t in trees) + 2,
+                  "us_per_round": t_dev * 1e6}
+        if not args.no_cpu_baseline:
+            from oracle import OracleKVMeta
+            om = OracleKVMeta(n_cells, 32)
+            t0 = time.perf_counter()
+            om.fill(0, T, 0, range(32))
+            held = []
+            for r, tr in enumerate(trees):
+                ids = [om.acquire() for _ in range(synth.n_leaves(tr))]
+                held += ids
+                sq = synth.tree_sequences(tr, ids)
+                positions = synth.tree_run(tr, T, T)["positions"].tolist()
+                om.place(positions, sq, T)
+                om.build_mask(positions, sq, T, T)
+                last = (positions, sq)
+            om.accept(last[0], last[1], [0])
+            for s_ in held:
+                om.release(s_)
+            om.compact(T)
+            kvmeta["oracle_us_per_round"] = (time.perf_counter() - t0) * 1e6
+        meta.free()
+
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
         "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
@@ -282,6 +355,7 @@ def main():
         "per_batch": per_batch,
         "cancellation": cancel,
         "multi_run": multi,
+        "kv_metadata": kvmeta,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": hb["frac_of_peak"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get((shape.name, T, int(head))),

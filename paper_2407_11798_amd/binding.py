@@ -68,6 +68,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libpipeinfer_hip.so is missing: run __graft_entry__.build() "
                                "(python -m paper_2407_11798_amd.build) first; there is no fallback path")
+        # torch ships a HIP runtime of its own; it must be in the process first, so that this
+        # library binds to the same one (device pointers and streams are shared with torch)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         L.pi_model_load.argtypes = [POINTER(PiModelConfig), POINTER(c_void_p)]
         L.pi_model_set_tensor.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_int32, c_int32]

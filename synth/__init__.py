@@ -133,6 +133,7 @@ def hip_lib():
     if _hip is None:
         if not os.path.exists(_HIP_SO):
             raise RuntimeError("synth device library missing: run __graft_entry__.build() first")
+        import torch  # noqa: F401  (its HIP runtime first: the fills write into torch's device memory)
         _hip = ctypes.CDLL(_HIP_SO)
         _hip.synth_fill_normal_device.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64,
                                                   ctypes.c_uint64, ctypes.c_double, ctypes.c_int,
