@@ -301,6 +301,55 @@ int32_t pi_kvmeta_compact(pi_kvmeta* meta, pi_kv* kv, int32_t prefix_len, int32_
 /* Copy the table to the host (either pointer may be NULL).  Blocking. */
 int32_t pi_kvmeta_read(const pi_kvmeta* meta, int32_t* pos_host, uint32_t* seq_host);
 
+/* ---- Head-node run bookkeeping (host only: no device work, callable without a GPU) -------
+ * Sections "State tracking", "Invalidation detection", "Cancellation back-propagation" and
+ * "Reactive speculation": every run in flight has a record in a FIFO queue holding its
+ * speculated tokens and positions; after every sampling phase the queue is searched for runs
+ * that are superfluous (highest position below the position of the last accepted token) or
+ * invalidated (their tokens do not continue the accepted ones) and those are cancelled: for a
+ * speculative run the scheduler stores 1 into the run's cancel word -- the word a forward of
+ * that run polls at every layer boundary -- while a non-speculative run is only marked (it
+ * must still be evaluated in full; just its sampling is skipped).  The confidence cutoff for
+ * further speculation rises by `recovery` with every speculation issued, returns to `base`
+ * when a completed run is accepted, and falls by `decay` when speculation stops for lack of
+ * confidence while no logits are waiting.  Positions count tokens from 0.  Not thread-safe. */
+#define PI_RUN_SUPERFLUOUS 1
+#define PI_RUN_INVALIDATED 2
+
+typedef struct pi_sched pi_sched;
+
+int32_t pi_sched_create(double base_cutoff, double recovery, double decay, pi_sched** out);
+int32_t pi_sched_free(pi_sched* s);
+/* Create the record of a run that is about to start and append it to the queue.
+ *   assumed[n_assumed]: tokens at positions assumed_pos0 .. that the run builds on and that
+ *     were still speculation when it started (may be empty);
+ *   tokens/parent/positions[n]: the run's own batch (parent -1 = root; parent < child; all
+ *     roots at one position, a child one position after its parent);
+ *   cancel_word: host-visible address of the run's device-visible cancel word (e.g. mapped
+ *     pinned memory), or NULL; it must stay valid until pi_sched_complete_run.
+ * run_id receives a unique identifier (0, 1, 2, ... in creation order). */
+int32_t pi_sched_begin_run(pi_sched* s, int32_t speculative, const int32_t* assumed, int32_t n_assumed,
+                           int32_t assumed_pos0, const int32_t* tokens, const int32_t* parent,
+                           const int32_t* positions, int32_t n, volatile int32_t* cancel_word, int32_t* run_id);
+/* A sampling phase has ended: tokens[n] join the accepted sequence; run_completed != 0 says
+ * they come from a completed run (the cutoff returns to its base).  The queue is then
+ * searched, oldest run first, by the position method, then the token method; every run newly
+ * found is reported once in ids/reasons/signalled (capacity cap; *n_found is the number
+ * found, which may exceed cap) and, if speculative, has its cancel word set. */
+int32_t pi_sched_accept_tokens(pi_sched* s, const int32_t* tokens, int32_t n, int32_t run_completed, int32_t* ids,
+                               int32_t* reasons, int32_t* signalled, int32_t cap, int32_t* n_found);
+/* The run's result has been dealt with: its record leaves the queue; *state receives 0,
+ * PI_RUN_SUPERFLUOUS or PI_RUN_INVALIDATED.  PI_E_ARG for an unknown run. */
+int32_t pi_sched_complete_run(pi_sched* s, int32_t run_id, int32_t* state);
+/* Reactive speculation. */
+int32_t pi_sched_want_speculation(const pi_sched* s, double confidence, int32_t* yes);
+int32_t pi_sched_on_speculated(pi_sched* s);
+int32_t pi_sched_on_speculation_stopped(pi_sched* s, int32_t logits_waiting);
+/* Read-back: the current cutoff, the number of accepted tokens, the queue (ids[cap], oldest
+ * first; *n_runs is the queue length). */
+int32_t pi_sched_state(const pi_sched* s, double* cutoff, int32_t* n_accepted, int32_t* ids, int32_t cap,
+                       int32_t* n_runs);
+
 const char* pi_strerror(int32_t status);
 
 /* Tuning hook (not needed for correct use): phase 0..4 (QKV, O, gate/up, down, LM head): ask

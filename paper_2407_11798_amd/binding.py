@@ -20,6 +20,7 @@ PI_E_ARG, PI_E_SHAPE, PI_E_OOM, PI_E_SLOT_LIVE, PI_E_HIP, PI_E_STATE = -1, -2, -
 PI_E_FULL, PI_E_BUSY = -7, -8
 PI_MAX_BATCH, PI_WINDOW = 16, 64
 PI_MAX_SEQ, PI_SEQ_CANONICAL, PI_POS_MAX = 32, 0, 0x7FFFFFFF
+PI_RUN_SUPERFLUOUS, PI_RUN_INVALIDATED = 1, 2
 PI_DTYPE_F32, PI_DTYPE_BF16 = 0, 1
 PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 (PI_T_EMBED, PI_T_ATTN_NORM, PI_T_WQ, PI_T_WK, PI_T_WV, PI_T_WO, PI_T_FFN_NORM, PI_T_WG, PI_T_WU,
@@ -33,6 +34,8 @@ EXPORTS = [
     "pi_kvmeta_alloc", "pi_kvmeta_free", "pi_kvmeta_seq_acquire", "pi_kvmeta_seq_release", "pi_kvmeta_fill",
     "pi_kvmeta_place", "pi_kvmeta_seq_cp", "pi_kvmeta_seq_rm", "pi_kvmeta_accept", "pi_kvmeta_build_mask",
     "pi_kvmeta_compact", "pi_kvmeta_read",
+    "pi_sched_create", "pi_sched_free", "pi_sched_begin_run", "pi_sched_accept_tokens", "pi_sched_complete_run",
+    "pi_sched_want_speculation", "pi_sched_on_speculated", "pi_sched_on_speculation_stopped", "pi_sched_state",
 ]
 
 
@@ -110,6 +113,18 @@ def lib():
                                            c_void_p, c_void_p]
         L.pi_kvmeta_compact.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pi_kvmeta_read.argtypes = [c_void_p, c_void_p, c_void_p]
+        c_double = ctypes.c_double
+        L.pi_sched_create.argtypes = [c_double, c_double, c_double, POINTER(c_void_p)]
+        L.pi_sched_free.argtypes = [c_void_p]
+        L.pi_sched_begin_run.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                         c_int32, c_void_p, POINTER(c_int32)]
+        L.pi_sched_accept_tokens.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_int32,
+                                             POINTER(c_int32)]
+        L.pi_sched_complete_run.argtypes = [c_void_p, c_int32, POINTER(c_int32)]
+        L.pi_sched_want_speculation.argtypes = [c_void_p, c_double, POINTER(c_int32)]
+        L.pi_sched_on_speculated.argtypes = [c_void_p]
+        L.pi_sched_on_speculation_stopped.argtypes = [c_void_p, c_int32]
+        L.pi_sched_state.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int32), c_void_p, c_int32, POINTER(c_int32)]
         for name in EXPORTS:
             if name != "pi_strerror":
                 getattr(L, name).restype = c_int32
@@ -394,6 +409,76 @@ class KVMeta:
     def free(self):
         if self.handle:
             lib().pi_kvmeta_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Scheduler:
+    """pi_sched handle: the head node's run records, invalidation detection and reactive
+    cutoff (host only).  cancel_word_ptr: host-visible address of a run's cancel word."""
+
+    def __init__(self, base_cutoff: float, recovery: float, decay: float):
+        h = c_void_p()
+        _check(lib().pi_sched_create(base_cutoff, recovery, decay, byref(h)), "pi_sched_create")
+        self.handle = h
+
+    def begin_run(self, speculative, assumed, assumed_pos0, tokens, parent, positions, cancel_word_ptr=None) -> int:
+        a, t, p, q = _i32(assumed), _i32(tokens), _i32(parent), _i32(positions)
+        rid = c_int32()
+        _check(lib().pi_sched_begin_run(self.handle, int(bool(speculative)), c_void_p(a.ctypes.data) if len(a) else None,
+                                        len(a), assumed_pos0, c_void_p(t.ctypes.data), c_void_p(p.ctypes.data),
+                                        c_void_p(q.ctypes.data), len(t),
+                                        None if cancel_word_ptr is None else c_void_p(cancel_word_ptr), byref(rid)),
+               "pi_sched_begin_run")
+        return rid.value
+
+    def accept_tokens(self, tokens, run_completed: bool = True, cap: int = 64):
+        t = _i32(tokens)
+        ids, reasons, sig = (np.zeros(cap, dtype=np.int32) for _ in range(3))
+        found = c_int32()
+        _check(lib().pi_sched_accept_tokens(self.handle, c_void_p(t.ctypes.data) if len(t) else None, len(t),
+                                            int(bool(run_completed)), c_void_p(ids.ctypes.data),
+                                            c_void_p(reasons.ctypes.data), c_void_p(sig.ctypes.data), cap, byref(found)),
+               "pi_sched_accept_tokens")
+        k = min(found.value, cap)
+        return [(int(ids[i]), int(reasons[i]), bool(sig[i])) for i in range(k)]
+
+    def complete_run(self, run_id: int) -> int:
+        st = c_int32()
+        _check(lib().pi_sched_complete_run(self.handle, run_id, byref(st)), "pi_sched_complete_run")
+        return st.value
+
+    def want_speculation(self, confidence: float) -> bool:
+        yes = c_int32()
+        _check(lib().pi_sched_want_speculation(self.handle, confidence, byref(yes)), "pi_sched_want_speculation")
+        return bool(yes.value)
+
+    def on_speculated(self):
+        _check(lib().pi_sched_on_speculated(self.handle), "pi_sched_on_speculated")
+
+    def on_speculation_stopped(self, logits_waiting: bool):
+        _check(lib().pi_sched_on_speculation_stopped(self.handle, int(bool(logits_waiting))),
+               "pi_sched_on_speculation_stopped")
+
+    def state(self, cap: int = 64):
+        cutoff, na, nr = ctypes.c_double(), c_int32(), c_int32()
+        ids = np.zeros(cap, dtype=np.int32)
+        _check(lib().pi_sched_state(self.handle, byref(cutoff), byref(na), c_void_p(ids.ctypes.data), cap, byref(nr)),
+               "pi_sched_state")
+        return cutoff.value, na.value, [int(v) for v in ids[:min(nr.value, cap)]]
+
+    def free(self):
+        if self.handle:
+            lib().pi_sched_free(self.handle)
             self.handle = None
 
     def __del__(self):
