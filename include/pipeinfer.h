@@ -212,6 +212,21 @@ int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n,
                          int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
                          int32_t* result, void* stream);
 
+/* The same for a run that builds on another run's speculation (Section "Continuous
+ * Speculation": trees build on the previous trees, so a rejected speculation takes its
+ * descendants with it), decided on the device so that runs can be queued back to back:
+ *   prev_result (device, may be NULL): the result[2] of the run this one builds on, written
+ *     earlier on the same stream; this run counts only if that run accepted all of its
+ *     prev_n tokens, and its bonus token is then the expectation for this run's root
+ *     (root_expected is ignored).  NULL: root_expected is used as in pi_verify_greedy.
+ *   run_status (device, may be NULL): the run_status of this run's forward; the run counts
+ *     only if run_status[0] == PI_OK (a cancelled run's logits are not there).
+ * A run that does not count yields accepted_nodes all -1 and result = {0, -1}.  Calls share
+ * one scratch buffer: issue them on one stream.  Asynchronous. */
+int32_t pi_verify_greedy_chained(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                                 int32_t vocab, int32_t root_expected, const int32_t* prev_result, int32_t prev_n,
+                                 const int32_t* run_status, int32_t* accepted_nodes, int32_t* result, void* stream);
+
 /* Commit / roll back a run's cells (Sections "KV Cache" and "Pipelined KV Cache
  * Multibuffering / Sequence partitions"): the cells of the accepted path are copied, all
  * layers, to canonical cells kv_len .. kv_len+a-1 in path order, every other cell in
@@ -349,6 +364,11 @@ int32_t pi_sched_on_speculation_stopped(pi_sched* s, int32_t logits_waiting);
  * first; *n_runs is the queue length). */
 int32_t pi_sched_state(const pi_sched* s, double* cutoff, int32_t* n_accepted, int32_t* ids, int32_t cap,
                        int32_t* n_runs);
+
+/* Device-visible address of pinned, mapped host memory (e.g. a cancel word the head node
+ * stores into from the host): host_ptr must lie in memory allocated as pinned host memory.
+ * PI_E_HIP if it does not. */
+int32_t pi_mapped_device_pointer(void* host_ptr, void** device_ptr);
 
 const char* pi_strerror(int32_t status);
 

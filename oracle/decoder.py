@@ -238,6 +238,23 @@ def verify_greedy(draft: np.ndarray, parent: np.ndarray | None, logits: np.ndarr
     return len(acc), acc, expected
 
 
+def verify_greedy_chained(draft, parent, logits, root_expected, prev_result=None, prev_n=0, run_ok=True):
+    """Verification of a run that builds on another run's speculation (Section "Continuous
+    Speculation"): it counts only if the run it builds on accepted all prev_n of its tokens
+    -- that run's bonus token is then what the root is checked against -- and only if its own
+    forward ran to the end.  Otherwise nothing is accepted and there is no bonus token (-1).
+    prev_result: (accepted count, bonus token) of the earlier run, or None for a run that
+    starts at the accepted end (root_expected is used)."""
+    n = len(draft)
+    if prev_result is not None:
+        if int(prev_result[0]) != int(prev_n):
+            return 0, [], -1
+        root_expected = int(prev_result[1])
+    if not run_ok:
+        return 0, [], -1
+    return verify_greedy(draft, parent, logits, root_expected)
+
+
 def kv_rollback(kv: OracleKV, slots: np.ndarray, accepted_nodes: list[int]) -> None:
     """Commit the accepted path to canonical cells kv_len .. kv_len+a-1 (path order), free
     (zero) every other cell the run wrote, and advance kv_len by a.  A cancelled or fully

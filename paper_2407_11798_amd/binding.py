@@ -29,13 +29,14 @@ PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
-    "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
+    "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_verify_greedy_chained", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
     "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
     "pi_kvmeta_alloc", "pi_kvmeta_free", "pi_kvmeta_seq_acquire", "pi_kvmeta_seq_release", "pi_kvmeta_fill",
     "pi_kvmeta_place", "pi_kvmeta_seq_cp", "pi_kvmeta_seq_rm", "pi_kvmeta_accept", "pi_kvmeta_build_mask",
     "pi_kvmeta_compact", "pi_kvmeta_read",
     "pi_sched_create", "pi_sched_free", "pi_sched_begin_run", "pi_sched_accept_tokens", "pi_sched_complete_run",
     "pi_sched_want_speculation", "pi_sched_on_speculated", "pi_sched_on_speculation_stopped", "pi_sched_state",
+    "pi_mapped_device_pointer",
 ]
 
 
@@ -92,6 +93,8 @@ def lib():
                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_verify_greedy.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                        c_void_p, c_void_p]
+        L.pi_verify_greedy_chained.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p, c_int32,
+                                               c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_kv_rollback.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
         L.pi_strerror.argtypes = [c_int32]
         L.pi_strerror.restype = ctypes.c_char_p
@@ -114,6 +117,7 @@ def lib():
         L.pi_kvmeta_compact.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pi_kvmeta_read.argtypes = [c_void_p, c_void_p, c_void_p]
         c_double = ctypes.c_double
+        L.pi_mapped_device_pointer.argtypes = [c_void_p, POINTER(c_void_p)]
         L.pi_sched_create.argtypes = [c_double, c_double, c_double, POINTER(c_void_p)]
         L.pi_sched_free.argtypes = [c_void_p]
         L.pi_sched_begin_run.argtypes = [c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
@@ -333,6 +337,14 @@ def verify_greedy(draft, parent, n: int, logits, vocab: int, root_expected: int,
     return _check(st, "pi_verify_greedy")
 
 
+def verify_greedy_chained(draft, parent, n: int, logits, vocab: int, root_expected: int, prev_result, prev_n: int,
+                          run_status, accepted_nodes, result, stream=None) -> int:
+    st = lib().pi_verify_greedy_chained(_ptr(draft), _ptr(parent), n, _ptr(logits), vocab, root_expected,
+                                        _ptr(prev_result), prev_n, _ptr(run_status), _ptr(accepted_nodes), _ptr(result),
+                                        _stream_handle(stream))
+    return _check(st, "pi_verify_greedy_chained")
+
+
 def kv_rollback(kv: KVCache, slots, n: int, accepted_nodes=None, result=None, stream=None) -> int:
     st = lib().pi_kv_rollback(kv.handle, _ptr(slots), n, _ptr(accepted_nodes), _ptr(result),
                               _stream_handle(stream))
@@ -416,6 +428,13 @@ class KVMeta:
             self.free()
         except Exception:
             pass
+
+
+def mapped_device_pointer(pinned_tensor) -> int:
+    """Device-visible address of a pinned (mapped) host tensor."""
+    out = c_void_p()
+    _check(lib().pi_mapped_device_pointer(c_void_p(pinned_tensor.data_ptr()), byref(out)), "pi_mapped_device_pointer")
+    return out.value
 
 
 def _i32(a):

@@ -715,11 +715,12 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
 
 extern "C" {
 
-int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
-                         int32_t vocab, int32_t root_expected, int32_t* accepted_nodes, int32_t* result,
-                         void* stream) {
+int32_t pi_verify_greedy_chained(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                                 int32_t vocab, int32_t root_expected, const int32_t* prev_result, int32_t prev_n,
+                                 const int32_t* run_status, int32_t* accepted_nodes, int32_t* result, void* stream) {
   if (!draft || !logits || !accepted_nodes || !result) return PI_E_ARG;
   if (n < 1 || n > PI_MAX_BATCH || vocab < 1 || vocab > (1 << 24)) return PI_E_SHAPE;
+  if (prev_result && (prev_n < 1 || prev_n > PI_MAX_BATCH)) return PI_E_SHAPE;
   std::call_once(g_verify_once, [] {
     hipError_t e = hipMalloc((void**)&g_verify.best_val, PI_MAX_BATCH * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&g_verify.best_idx, PI_MAX_BATCH * sizeof(int32_t));
@@ -729,8 +730,22 @@ int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n,
     g_verify_err = e;
   });
   if (g_verify_err != hipSuccess) return hip_status(g_verify_err);
-  return hip_status(launch_verify(draft, parent, n, logits, vocab, root_expected, accepted_nodes, result,
-                                  g_verify.best_val, g_verify.best_idx, g_verify.cnt, (hipStream_t)stream));
+  return hip_status(launch_verify(draft, parent, n, logits, vocab, root_expected, prev_result, prev_n, run_status,
+                                  accepted_nodes, result, g_verify.best_val, g_verify.best_idx, g_verify.cnt,
+                                  (hipStream_t)stream));
+}
+
+int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                         int32_t vocab, int32_t root_expected, int32_t* accepted_nodes, int32_t* result,
+                         void* stream) {
+  return pi_verify_greedy_chained(draft, parent, n, logits, vocab, root_expected, nullptr, 0, nullptr, accepted_nodes,
+                                  result, stream);
+}
+
+int32_t pi_mapped_device_pointer(void* host_ptr, void** device_ptr) {
+  if (!host_ptr || !device_ptr) return PI_E_ARG;
+  *device_ptr = nullptr;
+  return hip_status(hipHostGetDevicePointer(device_ptr, host_ptr, 0));
 }
 
 int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t* accepted_nodes,

@@ -7,9 +7,12 @@ namespace {
 
 // ---- greedy verification -------------------------------------------------------------------
 // One block per logits row finds argmax (lowest id on ties); the last block to finish walks
-// the tree.
+// the tree.  Chained form: the expectation for the root comes from the result of the run this
+// one builds on, and counts only if that run was accepted whole and this run's forward ran to
+// its end; otherwise nothing is accepted and the bonus token is -1.
 __global__ void __launch_bounds__(256) verify_kernel(const int32_t* draft, const int32_t* parent, int n,
                                                      const float* logits, int vocab, int root_expected,
+                                                     const int32_t* prev_result, int prev_n, const int32_t* run_status,
                                                      int32_t* accepted, int32_t* result,
                                                      float* best_val, int32_t* best_idx, int* cnt) {
   __shared__ float sv[4];
@@ -67,7 +70,13 @@ __global__ void __launch_bounds__(256) verify_kernel(const int32_t* draft, const
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       *cnt = 0;
       int u = -1, expected = root_expected, a = 0;
-      for (;;) {
+      bool none = run_status && run_status[0] != PI_OK;
+      if (prev_result) {
+        none = none || prev_result[0] != prev_n;
+        expected = prev_result[1];
+      }
+      if (none) expected = -1;
+      while (!none) {
         int nxt = -1;
         for (int c = 0; c < n; ++c) {
           const int p = parent ? parent[c] : c - 1;
@@ -173,10 +182,11 @@ __global__ void __launch_bounds__(256) kv_get_kernel(const char* kbuf, const cha
 }  // namespace
 
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
-                         int vocab, int root_expected, int32_t* accepted, int32_t* result,
+                         int vocab, int root_expected, const int32_t* prev_result, int prev_n,
+                         const int32_t* run_status, int32_t* accepted, int32_t* result,
                          float* best_val, int32_t* best_idx, int* cnt, hipStream_t s) {
-  verify_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>(draft, parent, n, logits, vocab, root_expected,
-                                                        accepted, result, best_val, best_idx, cnt);
+  verify_kernel<<<dim3((unsigned)n), dim3(256), 0, s>>>(draft, parent, n, logits, vocab, root_expected, prev_result,
+                                                        prev_n, run_status, accepted, result, best_val, best_idx, cnt);
   return hipGetLastError();
 }
 

@@ -147,7 +147,8 @@ int stage_ring_size(int dtype, int min_nt);
 hipError_t stage_configure(int dtype, int ring, size_t max_lds, int* max_blocks_per_cu);
 hipError_t launch_stage(const StageArgs& a, int dtype, int ring, int grid, size_t lds, hipStream_t s);
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
-                         int vocab, int root_expected, int32_t* accepted, int32_t* result,
+                         int vocab, int root_expected, const int32_t* prev_result, int prev_n,
+                         const int32_t* run_status, int32_t* accepted, int32_t* result,
                          float* best_val, int32_t* best_idx, int* cnt, hipStream_t s);
 hipError_t launch_rollback(void* k, void* v, int kv_dtype, int n_layers, int n_kv_heads, int n_cells,
                            int head_dim, const int32_t* slots, int n, const int32_t* accepted,

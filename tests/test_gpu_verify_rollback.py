@@ -48,6 +48,48 @@ def test_verify_matches_oracle_on_random_trees(vocab):
         assert gacc[:a] == acc and all(v == -1 for v in gacc[a:])
 
 
+def test_chained_verification_matches_oracle():
+    """Three runs queued back to back, each checked against the bonus token of the one before
+    it, all on the device; every combination of: the earlier run accepted whole or not, this
+    run's forward finished or cancelled."""
+    rng = np.random.default_rng(5)
+    vocab = 1000
+    for trial in range(60):
+        ns = [int(rng.integers(1, 6)) for _ in range(3)]
+        logits = [rng.normal(size=(n, vocab)).astype(np.float32) for n in ns]
+        drafts = [rng.integers(0, vocab, size=n).astype(np.int32) for n in ns]
+        root_expected = int(rng.integers(0, vocab))
+        # plant agreement: each token is right with probability 0.8, given that all before it were
+        exp = root_expected
+        for k in range(3):
+            for i in range(ns[k]):
+                if rng.random() < 0.8:
+                    drafts[k][i] = exp
+                exp = int(np.argmax(logits[k][i]))
+        status = [[pi.PI_OK, 2] if rng.random() < 0.8 else [pi.PI_CANCELLED, 1] for _ in range(3)]
+        # oracle
+        want, prev = [], None
+        for k in range(3):
+            a, acc, bonus = oracle.verify_greedy_chained(drafts[k], None, logits[k], root_expected, prev,
+                                                         ns[k - 1] if k else 0, status[k][0] == pi.PI_OK)
+            want.append((a, acc, bonus))
+            prev = (a, bonus)
+        # device: results never leave the GPU between the three calls
+        res = [torch.full((2,), -7, dtype=torch.int32, device="cuda") for _ in range(3)]
+        acc = [torch.full((ns[k],), -7, dtype=torch.int32, device="cuda") for k in range(3)]
+        for k in range(3):
+            pi.verify_greedy_chained(torch.as_tensor(drafts[k], device="cuda"), None, ns[k],
+                                     torch.as_tensor(logits[k], device="cuda"), vocab, root_expected,
+                                     res[k - 1] if k else None, ns[k - 1] if k else 0,
+                                     torch.as_tensor(np.asarray(status[k], dtype=np.int32), device="cuda"), acc[k], res[k])
+        torch.cuda.synchronize()
+        for k in range(3):
+            a, path, bonus = want[k]
+            assert res[k].cpu().tolist() == [a, bonus], (trial, k)
+            assert acc[k].cpu().tolist() == path + [-1] * (ns[k] - a)
+    assert pi.lib().pi_verify_greedy_chained(None, None, 1, None, 16, 0, None, 0, None, None, None, None) == pi.PI_E_ARG
+
+
 def test_verify_linear_chain_without_parent_array_and_ties():
     vocab = 4096
     logits = np.zeros((4, vocab), dtype=np.float32)

@@ -246,6 +246,28 @@ def test_verify_tree_walk_and_ties():
     assert (a, acc, bonus) == (1, [0], 4)
 
 
+def test_chained_verification_counts_only_behind_a_fully_accepted_run():
+    vocab = 32
+    lg = _onehot_logits(3, vocab, [8, 6, 5])            # the target's choice after node i
+    draft = np.array([3, 8, 6], dtype=np.int32)         # right if the root is expected to be 3
+    # the earlier run accepted all 4 of its tokens and predicts 3 next: this run counts in full
+    assert oracle.verify_greedy_chained(draft, None, lg, 99, prev_result=(4, 3), prev_n=4) == (3, [0, 1, 2], 5)
+    # ... predicts 7 next: the root is wrong, the target's own token stands
+    assert oracle.verify_greedy_chained(draft, None, lg, 99, prev_result=(4, 7), prev_n=4) == (0, [], 7)
+    # the earlier run was cut short at 2 of 4: whatever this run says, it built on a wrong token
+    assert oracle.verify_greedy_chained(draft, None, lg, 3, prev_result=(2, 3), prev_n=4) == (0, [], -1)
+    # a cancelled forward has no logits to speak of
+    assert oracle.verify_greedy_chained(draft, None, lg, 3, run_ok=False) == (0, [], -1)
+    # no earlier run: the plain rule
+    assert oracle.verify_greedy_chained(draft, None, lg, 3) == oracle.verify_greedy(draft, None, lg, 3) == (3, [0, 1, 2], 5)
+    # splitting a chain into two runs gives the same tokens as verifying it whole
+    whole = oracle.verify_greedy(np.array([3, 8, 6, 5, 1]), None, _onehot_logits(5, vocab, [8, 6, 5, 1, 2]), 3)
+    first = oracle.verify_greedy(np.array([3, 8, 6]), None, _onehot_logits(3, vocab, [8, 6, 5]), 3)
+    second = oracle.verify_greedy_chained(np.array([5, 1]), None, _onehot_logits(2, vocab, [1, 2]), 0,
+                                          prev_result=(first[0], first[2]), prev_n=3)
+    assert whole == (5, [0, 1, 2, 3, 4], 2) and first[0] + second[0] == 5 and second[2] == whole[2]
+
+
 def test_planted_draft_end_to_end_and_rollback_equals_sequential_decode():
     """Tiny configuration: 64 prefilled positions, 4 draft tokens planted to agree with the
     target for the first 2.  Accepted = 2, bonus = target's choice after node 1, and the
