@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--no-cancel", action="store_true", help="skip the cancellation latency trials")
     ap.add_argument("--no-multi-run", action="store_true", help="skip the several-runs-per-pass comparison")
     ap.add_argument("--no-kv-metadata", action="store_true", help="skip the cell-metadata bookkeeping timing")
+    ap.add_argument("--no-continuous", action="store_true", help="skip the continuous-speculation generation loop")
     ap.add_argument("--slice-layers", type=int, default=0,
                     help="also time a pipeline stage's share: the first this-many layers as one stage call")
     ap.add_argument("--calibrate-copy", type=int, default=0,
@@ -343,6 +344,69 @@ def main():
             kvmeta["oracle_us_per_round"] = (time.perf_counter() - t0) * 1e6
         meta.free()
 
+    # Continuous asynchronous speculation (the paper's end-to-end method on this one GPU): plain
+    # greedy decoding of 64 tokens first (one token per forward: the baseline, and the sequence
+    # the synthetic draft source is planted on), then the same 64 tokens generated by queued
+    # speculative micro-batches whose draft tokens agree with the target with probability alpha.
+    # No trained model pair exists here, so alpha stands in for the draft model's quality; the
+    # paper's model pairs report acceptance rates of 0.52 to 0.79.
+    contin = None
+    if not args.no_continuous:
+        from paper_2407_11798_amd.pipeline import ContinuousSpeculation
+        n_gen = 64
+        cells2 = ((T + 64 + 2 * n_gen + 15) // 16) * 16
+        kv2 = pi.KVCache(model, cells2)
+        first = int(synth.tokens_host(shape, args.seed, 1, synth.T_MISC, salt=77)[0])
+        lg1 = torch.empty((1, shape.vocab), device="cuda")
+        acc1 = torch.zeros(1, dtype=torch.int32, device="cuda")
+        res1 = torch.zeros(2, dtype=torch.int32, device="cuda")
+        res_h = torch.zeros(2, dtype=torch.int32, pin_memory=True)
+
+        def naive():
+            gpu_loader.prefill_kv_synthetic(kv2, shape, args.seed, T)
+            torch.cuda.synchronize()
+            toks, t = [], first
+            t0 = time.perf_counter()
+            for i in range(n_gen):
+                run1 = gpu_loader.make_run(synth.linear_run(1, T + i), np.array([t], dtype=np.int32))
+                pi.stage_forward(model, kv2, run1, 0, shape.n_layers, logits_out=lg1, run_status=status)
+                pi.verify_greedy(run1.tokens, None, 1, lg1, shape.vocab, t, acc1, res1)
+                pi.kv_rollback(kv2, run1.slots, 1, acc1, res1)
+                res_h.copy_(res1, non_blocking=True)
+                torch.cuda.synchronize()
+                t = int(res_h[1])
+                toks.append(t)
+            return toks, time.perf_counter() - t0
+
+        G, t_naive = naive()
+        contin = {"tokens": n_gen, "depth": 3, "micro_batch": 4, "cutoff": {"base": 0.0, "recovery": 0.05, "decay": 0.05},
+                  "plain_decoding": {"tokens_per_s": n_gen / t_naive, "ms_per_token": t_naive * 1e3 / n_gen},
+                  "by_alpha": {}}
+        for alpha in (0.52, 0.66, 0.79, 1.0):
+            gpu_loader.prefill_kv_synthetic(kv2, shape, args.seed, T)
+            u = synth.uniform_int_host(2 * (n_gen + 64), args.seed, synth.stream_id(synth.T_MISC, int(alpha * 100)), 1 << 20)
+
+            def draft(pos, u=u, alpha=alpha):
+                i = pos - (T + 1)
+                g = G[i] if i < len(G) else 0
+                right = u[2 * i] < alpha * (1 << 20)
+                return (g if right else (g + 1 + int(u[2 * i]) % 7) % shape.vocab), float(u[2 * i + 1]) / (1 << 20)
+
+            cs = ContinuousSpeculation(model, kv2, T, first, draft, depth=3, micro_batch=4, base_cutoff=0.0,
+                                       recovery=0.05, decay=0.05)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            got = cs.generate(n_gen)
+            dt = time.perf_counter() - t0
+            st = dict(cs.stats)
+            cs.close()
+            contin["by_alpha"]["%.2f" % alpha] = {
+                "tokens_per_s": n_gen / dt, "speedup_vs_plain": t_naive / dt, "same_tokens_as_plain": got == G,
+                "runs": st["runs"], "speculative_runs": st["speculative"], "cancelled_runs": st["cancelled"],
+                "layers_skipped": st["layers_skipped"], "draft_tokens_accepted": st["tokens_accepted_from_drafts"],
+                "draft_tokens_issued": st["tokens_speculated"]}
+        kv2.free()
+
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
         "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
@@ -356,6 +420,7 @@ def main():
         "cancellation": cancel,
         "multi_run": multi,
         "kv_metadata": kvmeta,
+        "continuous_speculation": contin,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": hb["frac_of_peak"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get((shape.name, T, int(head))),
