@@ -14,6 +14,30 @@ _NAME_TO_KIND = {
 }
 
 
+def _e4m3_table() -> np.ndarray:
+    """Value of every FP8 E4M3 byte (sign, 4 exponent bits with bias 7, 3 mantissa bits,
+    subnormals at exponent 0, no infinities; 0x7f and 0xff are NaN)."""
+    t = np.empty(256, dtype=np.float64)
+    for b in range(256):
+        sign = -1.0 if b & 0x80 else 1.0
+        e, m = (b >> 3) & 0xF, b & 7
+        if e == 15 and m == 7:
+            t[b] = np.nan
+        elif e == 0:
+            t[b] = sign * (m / 8.0) * 2.0 ** -6
+        else:
+            t[b] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return t
+
+
+E4M3 = _e4m3_table()
+
+
+def dequantise_fp8(codes: np.ndarray, scale_exp2: int) -> np.ndarray:
+    """8-bit weights as the model defines them: e4m3(byte) * 2^scale_exp2 (exact in float32)."""
+    return (E4M3[codes] * 2.0 ** scale_exp2).astype(np.float32)
+
+
 def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
                     cache: bool = True) -> OracleModel:
     """Weights are regenerated from the seed when asked for; `cache` keeps them (small models)."""
@@ -24,6 +48,8 @@ def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
         if key in store:
             return store[key]
         t = synth.weight_host(shape, seed, _NAME_TO_KIND[name], layer, gain_sigma)
+        if t.dtype == np.uint8:
+            t = dequantise_fp8(t, shape.weight_scale_exp2)
         if cache:
             store[key] = t
         return t

@@ -43,6 +43,8 @@ struct pi_model {
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
   size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
+  int wdtype = PI_DTYPE_BF16;  // format of the weight matrices (cfg.dtype, or 8-bit)
+  int kt32() const { return weight_tile_cols(wdtype) / 32; }  // 32-column tiles per weight tile
   int n_q_rows() const { return cfg.n_q_heads * cfg.head_dim; }
   int n_kv_rows() const { return cfg.n_kv_heads * cfg.head_dim; }
 };
@@ -77,8 +79,8 @@ PackedMat make_packed(int N, int K, int dtype) {
   p.N = N;
   p.K = K;
   p.NRB = (N + kRowBlock - 1) / kRowBlock;
-  p.KT = (K + kKTile - 1) / kKTile;
-  p.bytes = (size_t)p.NRB * p.KT * (dtype == PI_DTYPE_BF16 ? 1024 : 2048);
+  p.KT = (K + weight_tile_cols(dtype) - 1) / weight_tile_cols(dtype);
+  p.bytes = (size_t)p.NRB * p.KT * weight_tile_bytes(dtype);
   return p;
 }
 
@@ -103,7 +105,7 @@ int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t bu
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
     if (w.KT % sk || m->grid % sk) continue;
     const int gs = m->grid / sk;
-    if (stage_proj_lds_bytes(n, w.KT / sk, (w.NRB + gs - 1) / gs) > budget) continue;
+    if (stage_proj_lds_bytes(n, m->kt32() * (w.KT / sk), (w.NRB + gs - 1) / gs) > budget) continue;
     if (ov > sk) continue;  // an override asks for at least this many slices
     if (fits && w.KT / sk < 16) break;  // more slices would starve the ring
     fits = sk;
@@ -133,7 +135,7 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
     const int nt = mats[ph]->KT / sk;
     if (nt < p->min_nt) p->min_nt = nt;
     const int gs = m->grid / sk;
-    const size_t lds = stage_proj_lds_bytes(n, nt, (mats[ph]->NRB + gs - 1) / gs);
+    const size_t lds = stage_proj_lds_bytes(n, m->kt32() * nt, (mats[ph]->NRB + gs - 1) / gs);
     if (lds > p->lds) p->lds = lds;
     if (sk > 1 && (size_t)sk * mats[ph]->NRB > p->part_tiles) p->part_tiles = (size_t)sk * mats[ph]->NRB;
   }
@@ -191,11 +193,17 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (c.d_model % 32 || (c.n_q_heads * c.head_dim) % 32 || c.ffn % 16 || c.vocab % 16) return PI_E_SHAPE;
   if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8) return PI_E_SHAPE;
   if (c.dtype != PI_DTYPE_F32 && c.dtype != PI_DTYPE_BF16) return PI_E_SHAPE;
+  const bool w8 = c.weight_dtype == PI_DTYPE_FP8_E4M3;
+  if (w8 ? (c.dtype != PI_DTYPE_BF16 || c.weight_scale_exp2 < -32 || c.weight_scale_exp2 > 32)
+         : (c.weight_dtype != c.dtype && !(c.weight_dtype == 0 && c.dtype == PI_DTYPE_BF16)))
+    return PI_E_SHAPE;
   if (c.vocab > (1 << 24) || !(c.rms_eps >= 0.0f) || !(c.rope_base > 1.0f)) return PI_E_SHAPE;
 
   pi_model* m = new (std::nothrow) pi_model();
   if (!m) return PI_E_OOM;
   m->cfg = c;
+  m->wdtype = w8 ? kWeightFP8 : c.dtype;
+  const int wd = m->wdtype;
   const int d = c.d_model, nq = c.n_q_heads * c.head_dim, nkv = c.n_kv_heads * c.head_dim;
   const int es = c.dtype == PI_DTYPE_BF16 ? 2 : 4;
   hipError_t e = hipSuccess;
@@ -206,17 +214,17 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   m->layers.resize(c.n_layers);
   for (int l = 0; l < c.n_layers && e == hipSuccess; ++l) {
     LayerWeights& L = m->layers[l];
-    L.qkv = make_packed(nq + 2 * nkv, d, c.dtype);
-    L.o = make_packed(d, nq, c.dtype);
-    L.gateup = make_packed(2 * c.ffn, d, c.dtype);
-    L.down = make_packed(d, c.ffn, c.dtype);
+    L.qkv = make_packed(nq + 2 * nkv, d, wd);
+    L.o = make_packed(d, nq, wd);
+    L.gateup = make_packed(2 * c.ffn, d, wd);
+    L.down = make_packed(d, c.ffn, wd);
     for (PackedMat* p : {&L.qkv, &L.o, &L.gateup, &L.down}) {
       if (e == hipSuccess) e = dev_alloc(m, (char**)&p->data, p->bytes, true);
     }
     if (e == hipSuccess) e = dev_alloc(m, &L.attn_gain, d * sizeof(float), true);
     if (e == hipSuccess) e = dev_alloc(m, &L.ffn_gain, d * sizeof(float), true);
   }
-  m->lm_head = make_packed(c.vocab, d, c.dtype);
+  m->lm_head = make_packed(c.vocab, d, wd);
   if (e == hipSuccess) e = dev_alloc(m, (char**)&m->lm_head.data, m->lm_head.bytes, true);
   if (e == hipSuccess) e = dev_alloc(m, (char**)&m->embed, (size_t)c.vocab * d * es, true);
   if (e == hipSuccess) e = dev_alloc(m, &m->final_gain, d * sizeof(float), true);
@@ -313,7 +321,7 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
                             int32_t src_loc) {
   if (!m || !src) return PI_E_ARG;
   if (kind < PI_T_EMBED || kind > PI_T_LM_HEAD) return PI_E_ARG;
-  if (src_dtype != PI_DTYPE_F32 && src_dtype != PI_DTYPE_BF16) return PI_E_ARG;
+  if (src_dtype != PI_DTYPE_F32 && src_dtype != PI_DTYPE_BF16 && src_dtype != PI_DTYPE_FP8_E4M3) return PI_E_ARG;
   if (src_loc != PI_LOC_HOST && src_loc != PI_LOC_DEVICE) return PI_E_ARG;
   if (is_layer_kind(kind) && (layer < 0 || layer >= m->cfg.n_layers)) return PI_E_ARG;
   const pi_model_config& c = m->cfg;
@@ -321,6 +329,10 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
   const bool is_gain = kind == PI_T_ATTN_NORM || kind == PI_T_FFN_NORM || kind == PI_T_FINAL_NORM;
   if (is_gain && src_dtype != PI_DTYPE_F32) return PI_E_ARG;
   if (!is_gain && src_dtype == PI_DTYPE_BF16 && c.dtype == PI_DTYPE_F32) return PI_E_ARG;
+  // 8-bit weights: the streamed matrices come as bytes and nothing else does
+  const bool is_matrix = !is_gain && kind != PI_T_EMBED;
+  if ((src_dtype == PI_DTYPE_FP8_E4M3) != (is_matrix && m->wdtype == kWeightFP8)) return PI_E_ARG;
+  const int wd = m->wdtype;
   int rows = 1, cols = d;
   switch (kind) {
     case PI_T_EMBED: case PI_T_LM_HEAD: rows = c.vocab; break;
@@ -331,7 +343,7 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
     case PI_T_WD: rows = d; cols = c.ffn; break;
     default: break;
   }
-  const size_t src_bytes = (size_t)rows * cols * (src_dtype == PI_DTYPE_BF16 ? 2 : 4);
+  const size_t src_bytes = (size_t)rows * cols * (src_dtype == PI_DTYPE_FP8_E4M3 ? 1 : src_dtype == PI_DTYPE_BF16 ? 2 : 4);
   const void* dsrc = src;
   void* staging = nullptr;
   hipError_t e = hipSuccess;
@@ -351,14 +363,14 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
         e = launch_convert(dsrc, src_dtype, m->embed, c.dtype, (size_t)rows * cols, nullptr);
         break;
       }
-      case PI_T_WQ: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, c.dtype, 1, 0, nullptr); break;
-      case PI_T_WK: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, c.dtype, 1, nq, nullptr); break;
-      case PI_T_WV: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, c.dtype, 1, nq + nkv, nullptr); break;
-      case PI_T_WO: e = launch_repack(dsrc, src_dtype, rows, cols, L->o, c.dtype, 1, 0, nullptr); break;
-      case PI_T_WG: e = launch_repack(dsrc, src_dtype, rows, cols, L->gateup, c.dtype, 2, 0, nullptr); break;
-      case PI_T_WU: e = launch_repack(dsrc, src_dtype, rows, cols, L->gateup, c.dtype, 2, 1, nullptr); break;
-      case PI_T_WD: e = launch_repack(dsrc, src_dtype, rows, cols, L->down, c.dtype, 1, 0, nullptr); break;
-      case PI_T_LM_HEAD: e = launch_repack(dsrc, src_dtype, rows, cols, m->lm_head, c.dtype, 1, 0, nullptr); break;
+      case PI_T_WQ: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, wd, 1, 0, nullptr); break;
+      case PI_T_WK: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, wd, 1, nq, nullptr); break;
+      case PI_T_WV: e = launch_repack(dsrc, src_dtype, rows, cols, L->qkv, wd, 1, nq + nkv, nullptr); break;
+      case PI_T_WO: e = launch_repack(dsrc, src_dtype, rows, cols, L->o, wd, 1, 0, nullptr); break;
+      case PI_T_WG: e = launch_repack(dsrc, src_dtype, rows, cols, L->gateup, wd, 2, 0, nullptr); break;
+      case PI_T_WU: e = launch_repack(dsrc, src_dtype, rows, cols, L->gateup, wd, 2, 1, nullptr); break;
+      case PI_T_WD: e = launch_repack(dsrc, src_dtype, rows, cols, L->down, wd, 1, 0, nullptr); break;
+      case PI_T_LM_HEAD: e = launch_repack(dsrc, src_dtype, rows, cols, m->lm_head, wd, 1, 0, nullptr); break;
       default: break;
     }
   }
@@ -611,7 +623,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   StagePlan sp;
   if (!make_stage_plan(m, n, &sp)) return PI_E_SHAPE;
   if (sp.part_tiles > m->part_tiles) return PI_E_SHAPE;  // the plan's cross-slice tiles must fit what was allocated
-  const int ring = stage_ring_size(c.dtype, sp.min_nt);
+  const int ring = stage_ring_size(m->wdtype, sp.min_nt);
   if (ring == 0) return PI_E_SHAPE;
   // attention work units: per kv head, the prefix in chunks (multiples of 32 cells) sized so that
   // about one unit per workgroup exists and a unit's K/V (chunk + window) fits in LDS; the last
@@ -636,7 +648,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   }
   if (sp.lds > m->configured_lds[ring]) {
     int blocks = 0;
-    hipError_t ce = stage_configure(c.dtype, ring, sp.lds, &blocks);
+    hipError_t ce = stage_configure(m->wdtype, ring, sp.lds, &blocks);
     if (ce != hipSuccess) return hip_status(ce);
     if (blocks < 1) return PI_E_SHAPE;
     m->configured_lds[ring] = sp.lds;
@@ -661,6 +673,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.vocab = c.vocab;
   a.n_layers = L;
   a.eps = c.rms_eps;
+  a.wscale = m->wdtype == kWeightFP8 ? std::ldexp(1.0f, c.weight_scale_exp2) : 1.0f;
   a.n = n;
   a.tokens = run->tokens;
   a.positions = run->positions;
@@ -708,7 +721,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.trace_cap = m->trace_cap;
   a.wgtrace = m->wgtrace_layer >= 0 ? m->wgtrace : nullptr;
   a.wgtrace_layer = m->wgtrace_layer;
-  return hip_status(launch_stage(a, c.dtype, ring, m->grid, sp.lds, (hipStream_t)stream));
+  return hip_status(launch_stage(a, m->wdtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
 
 }  // namespace

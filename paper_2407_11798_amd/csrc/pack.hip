@@ -1,4 +1,4 @@
-// Weight repacking: logical row-major tensor -> the 16x32-tile streaming layout (PackedMat).
+// Weight repacking: logical row-major tensor -> the tiled streaming layout (PackedMat).
 #include "pi_internal.h"
 
 namespace pi {
@@ -41,6 +41,27 @@ __global__ void __launch_bounds__(256) repack_kernel(const void* src, int src_dt
   }
 }
 
+// 8-bit weights: one thread per (source row, 8 bytes of the row); bytes are copied, not converted.
+__global__ void __launch_bounds__(256) repack_fp8_kernel(const uint8_t* src, int rows, int cols, char* dst, int KT,
+                                                         int row_mul, int row_add) {
+  const int chunks_per_row = KT * 8;  // 64 columns per tile
+  const size_t total = (size_t)rows * chunks_per_row;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / chunks_per_row);
+    const int c = (int)(i % chunks_per_row);
+    const int pr = r * row_mul + row_add;
+    const int rb = pr / kRowBlock, lr = pr % kRowBlock;
+    const int k0 = c * 8;
+    uint32_t w[2] = {0u, 0u};
+    for (int j = 0; j < 8; ++j)
+      if (k0 + j < cols) w[j >> 2] |= (uint32_t)src[(size_t)r * cols + k0 + j] << (8 * (j & 3));
+    const int t = c / 8, q = c % 8, half = q / 4, g = q % 4;  // 32-column half of the tile, 8-column group
+    const size_t off = ((size_t)rb * KT + t) * 1024 + (size_t)(g * 16 + lr) * 16 + (size_t)half * 8;
+    *(uint2*)(dst + off) = make_uint2(w[0], w[1]);
+  }
+}
+
 __global__ void __launch_bounds__(256) convert_kernel(const void* src, int src_dtype, void* dst,
                                                       int dst_dtype, size_t count) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
@@ -64,6 +85,15 @@ hipError_t launch_convert(const void* src, int src_dtype, void* dst, int dst_dty
 
 hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, PackedMat dst,
                          int dst_dtype, int row_mul, int row_add, hipStream_t s) {
+  if (dst_dtype == kWeightFP8) {
+    const size_t total8 = (size_t)rows * dst.KT * 8;
+    size_t blocks8 = (total8 + 255) / 256;
+    if (blocks8 > 16384) blocks8 = 16384;
+    if (blocks8 == 0) return hipSuccess;
+    repack_fp8_kernel<<<dim3((unsigned)blocks8), dim3(256), 0, s>>>((const uint8_t*)src, rows, cols, (char*)dst.data,
+                                                                    dst.KT, row_mul, row_add);
+    return hipGetLastError();
+  }
   const int per_chunk = dst_dtype == PI_DTYPE_BF16 ? 8 : 4;
   const size_t total = (size_t)rows * (dst.KT * kKTile / per_chunk);
   size_t blocks = (total + 255) / 256;

@@ -22,13 +22,22 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 //   bf16 tile (1 KiB): lane l holds the 8 values W[16rb + (l&15)][32t + 8(l>>4) + 0..7]
 //                      -- exactly the A operand of v_mfma_f32_16x16x32_bf16.
 //   fp32 tile (2 KiB): two 1 KiB halves h=0,1; lane l holds W[..][32t + 8(l>>4) + 4h + 0..3].
-// Rows >= N and columns >= K are zero.
+//   fp8 tile  (1 KiB): 16 rows x 64 columns, one byte per weight; lane l holds, in bytes 0..7,
+//                      W[16rb + (l&15)][64t + 8(l>>4) + 0..7] and, in bytes 8..15, the same for
+//                      columns 64t + 32 + ...: two consecutive bf16-shaped tiles in one 16-byte piece.
+// Rows >= N and columns >= K are zero.  KT counts tiles of the matrix's own width.
 struct PackedMat {
   void* data = nullptr;
   int N = 0, K = 0;    // logical
   int NRB = 0, KT = 0; // row blocks, k tiles
   size_t bytes = 0;
 };
+
+// Weight format of a model as the kernels see it: the activation side of PI_DTYPE_FP8_E4M3 is
+// that of a bf16 model; only the matrices differ.
+constexpr int kWeightF32 = PI_DTYPE_F32, kWeightBF16 = PI_DTYPE_BF16, kWeightFP8 = PI_DTYPE_FP8_E4M3;
+__host__ __device__ constexpr int weight_tile_cols(int wd) { return wd == kWeightFP8 ? 64 : 32; }
+__host__ __device__ constexpr int weight_tile_bytes(int wd) { return wd == kWeightF32 ? 2048 : 1024; }
 
 struct LayerWeights {
   PackedMat qkv, o, gateup, down;
@@ -83,6 +92,7 @@ struct StageArgs {
   const float2* rope;  // [max_pos][hd/2] (cos, sin)
   int dtype, d, n_q_heads, n_kv_heads, head_dim, ffn, vocab, n_layers;
   float eps;
+  float wscale;  // 8-bit weights: the model's power-of-two scale (1 otherwise)
   // run
   int n;
   const int32_t* tokens;
@@ -142,10 +152,10 @@ hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, Pac
 hipError_t launch_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t count,
                           hipStream_t s);
 size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells);
-size_t stage_proj_lds_bytes(int n, int nt, int r_max);
-int stage_ring_size(int dtype, int min_nt);
-hipError_t stage_configure(int dtype, int ring, size_t max_lds, int* max_blocks_per_cu);
-hipError_t launch_stage(const StageArgs& a, int dtype, int ring, int grid, size_t lds, hipStream_t s);
+size_t stage_proj_lds_bytes(int n, int nt, int r_max);  // nt in 32-column tiles
+int stage_ring_size(int wdtype, int min_nt);
+hipError_t stage_configure(int wdtype, int ring, size_t max_lds, int* max_blocks_per_cu);
+hipError_t launch_stage(const StageArgs& a, int wdtype, int ring, int grid, size_t lds, hipStream_t s);
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
                          int vocab, int root_expected, const int32_t* prev_result, int prev_n,
                          const int32_t* run_status, int32_t* accepted, int32_t* result,

@@ -255,7 +255,7 @@ __device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
 template <int DT>
 __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int S_k, int wave) {
   const int wg = blockIdx.x, G = gridDim.x;
-  constexpr int kTileBytes = DT == PI_DTYPE_BF16 ? 1024 : 2048;
+  constexpr int kTileBytes = weight_tile_bytes(DT);
   S.w = M.w;
   S.bytes = (uint32_t)M.NRB * (uint32_t)M.KT * kTileBytes;
   S.KT = M.KT;
@@ -283,8 +283,8 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
 template <int DT, int UR>
 struct Ring {
   static constexpr int U = UR;
-  static constexpr int kTileBytes = DT == PI_DTYPE_BF16 ? 1024 : 2048;
-  static constexpr int kRegs = DT == PI_DTYPE_BF16 ? UR : 2 * UR;
+  static constexpr int kTileBytes = weight_tile_bytes(DT);
+  static constexpr int kRegs = DT == kWeightF32 ? 2 * UR : UR;
   u32x4 r[kRegs];
 };
 
@@ -314,7 +314,7 @@ __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, const WaveStream& S,
   const int soff = (int)((J < P.el ? P.lbaseA : P.lbaseB) + (uint32_t)(J * TB)) & mask;
   const int voff = (lane16 & mask) | (0x7ffffff0 & ~mask);
   const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(S.w, S.bytes);
-  if constexpr (DT == PI_DTYPE_BF16) {
+  if constexpr (DT != kWeightF32) {
     R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
   } else {
     R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
@@ -466,7 +466,7 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
         v[j] = in_k[q] ? p[q][0][j] * (gain ? gq[q][0][j] : 1.0f) : 0.0f;
         v[4 + j] = in_k[q] ? p[q][1][j] * (gain ? gq[q][1][j] : 1.0f) : 0.0f;
       }
-      if (DT == PI_DTYPE_BF16) {
+      if (DT != kWeightF32) {
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -719,6 +719,7 @@ struct PassLane {
   int lane16;      // byte offset of the lane's 16 bytes in a weight tile
   const char* b0;  // the lane's operand halves of tile 0
   const char* b1;
+  float wscale;    // 8-bit weights: the power-of-two scale the conversion applies
 };
 
 // A group of slots is consumed in a straight line behind one wave-uniform branch.  All operand
@@ -729,24 +730,45 @@ template <int DT, int UR, int J0, int J1>
 __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeState& C, const PassPlan& P,
                                               const PassLane& PLn) {
   constexpr int NG = J1 - J0;
-  u32x4 x0[NG], x1[NG];
+  constexpr int NX = DT == kWeightFP8 ? 2 : 1;  // 32-column operand slots per weight tile
+  u32x4 x0[NG][NX], x1[NG][NX];
 #pragma unroll
   for (int j = 0; j < NG; ++j) {
     const int J = J0 + j;
     const int off = J < P.nc ? (J < P.ec ? P.cbaseA : P.cbaseB) + J * P.stride : P.zoff;
-    x0[j] = *(const u32x4*)(PLn.b0 + off);
-    x1[j] = *(const u32x4*)(PLn.b1 + off);
+    x0[j][0] = *(const u32x4*)(PLn.b0 + off);
+    x1[j][0] = *(const u32x4*)(PLn.b1 + off);
+    if constexpr (NX == 2) {  // the tile's second half: the next operand slot (the zero slot has no neighbour)
+      const int off2 = J < P.nc ? off + (P.stride >> 1) : P.zoff;
+      x0[j][1] = *(const u32x4*)(PLn.b0 + off2);
+      x1[j][1] = *(const u32x4*)(PLn.b1 + off2);
+    }
   }
 #pragma unroll
   for (int j = 0; j < NG; ++j) {
     const int J = J0 + j;
-    if constexpr (DT == PI_DTYPE_BF16) {
+    if constexpr (DT == kWeightBF16) {
       const bf16x8 av = __builtin_bit_cast(bf16x8, R.r[J]);
-      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j]), C.acc0, 0, 0, 0);
-      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j]), C.acc1, 0, 0, 0);
+      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][0]), C.acc0, 0, 0, 0);
+      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][0]), C.acc1, 0, 0, 0);
+    } else if constexpr (DT == kWeightFP8) {
+      // sixteen bytes -> two bf16 operands; the conversion is exact (three mantissa bits) and
+      // applies the model's power-of-two scale on the way
+      const u32x4 w = R.r[J];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        u32x4 o;
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], PLn.wscale, false));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], PLn.wscale, true));
+        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, false));
+        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, true));
+        const bf16x8 av = __builtin_bit_cast(bf16x8, o);
+        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
+        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
+      }
     } else {
       const f32x4 w0 = __builtin_bit_cast(f32x4, R.r[2 * J]), w1 = __builtin_bit_cast(f32x4, R.r[2 * J + 1]);
-      const f32x4 a0 = __builtin_bit_cast(f32x4, x0[j]), a1 = __builtin_bit_cast(f32x4, x1[j]);
+      const f32x4 a0 = __builtin_bit_cast(f32x4, x0[j][0]), a1 = __builtin_bit_cast(f32x4, x1[j][0]);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         C.acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], a0[q], C.acc0, 0, 0, 0);
@@ -795,14 +817,16 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   PassLane PLn;
   PLn.lane16 = lane * 16;
   PLn.b0 = lds + ((lane >> 4) * n + min(lane & 15, n - 1)) * 16;
-  PLn.b1 = PLn.b0 + (S.nt + 1) * 64 * n;
+  constexpr int KX = weight_tile_cols(DT) / 32;  // 32-column operand slots per weight tile
+  PLn.b1 = PLn.b0 + (KX * S.nt + 1) * 64 * n;
+  PLn.wscale = A.wscale;
   // The compiler treats the vector memory counter as unordered while loads AND stores are pending
   // and then waits for everything before it touches a ring slot -- in every pass of the loop, once
   // that state has reached the loop header.  So stores are waited for, in a form the compiler sees,
   // before the loop and after every flush; between flushes the passes wait for exactly one slot.
   while (C.f < S.f1) {
     PassPlan P;
-    P.stride = 64 * n;
+    P.stride = KX * 64 * n;
     P.zoff = S.nt * P.stride;
     P.nc = min(UR, S.f1 - C.f);
     P.ec = S.nt - C.t;
@@ -900,8 +924,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 template <int HD, int DT>
 __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds, unsigned tag) {
-  constexpr int NS = DT == PI_DTYPE_BF16 ? 1 : 2;  // bf16 terms per cache value
-  constexpr int ES = DT == PI_DTYPE_BF16 ? 2 : 4;
+  constexpr int NS = DT != kWeightF32 ? 1 : 2;  // bf16 terms per cache value
+  constexpr int ES = DT != kWeightF32 ? 2 : 4;
   constexpr int KSTEPS = HD / 32;
   constexpr int DTILES = HD / 16;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -1323,7 +1347,8 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            bool poll_x, int kind) {
   if (poll_x) __syncthreads();  // no grid barrier came before: the workgroup's slower waves are done with LDS
   stream_make_uniform(S);
-  const size_t xbytes = (size_t)(S.nt + 1) * 128 * A.n;
+  constexpr int KX = weight_tile_cols(DT) / 32;  // activations are staged in 32-column slots whatever the weight tile
+  const size_t xbytes = (size_t)(KX * S.nt + 1) * 128 * A.n;
   float* red = (float*)(lds + xbytes);
   float* rscale = red + kThreads;
   FlushCtx F;
@@ -1363,7 +1388,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   EpiCtx e2 = e;
   e2.resid = stage_resid ? resid : nullptr;
   e2.rb0 = S.rb0;
-  stage_x<DT>(xin, gain, K, A.n, S.t0, S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
+  stage_x<DT>(xin, gain, K, A.n, KX * S.t0, KX * S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
               [&] { ring_prefetch<DT, UR>(R, S, lane); },
               [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; },
               poll_x ? kPollLimit : 0u, &timed_out);
@@ -1570,6 +1595,11 @@ size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
 
 namespace {
 const void* stage_fn(int dtype, int ring) {
+  if (dtype == kWeightFP8) {
+    if (ring == 16) return (const void*)stage_kernel<kWeightFP8, 16>;
+    if (ring == 8) return (const void*)stage_kernel<kWeightFP8, 8>;
+    return (const void*)stage_kernel<kWeightFP8, 4>;
+  }
   if (dtype == PI_DTYPE_BF16) {
     if (ring == 16) return (const void*)stage_kernel<PI_DTYPE_BF16, 16>;
     if (ring == 8) return (const void*)stage_kernel<PI_DTYPE_BF16, 8>;
@@ -1581,7 +1611,7 @@ const void* stage_fn(int dtype, int ring) {
 }  // namespace
 
 int stage_ring_size(int dtype, int min_nt) {
-  if (dtype == PI_DTYPE_BF16 && min_nt >= 16) return 16;
+  if (dtype != kWeightF32 && min_nt >= 16) return 16;
   if (min_nt >= 8) return 8;
   return min_nt >= 4 ? 4 : 0;
 }

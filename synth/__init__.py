@@ -39,6 +39,10 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     dtype: str = "bf16"  # storage type of weights and KV cache: "f32" or "bf16"
+    # "fp8": the weight matrices (not the embedding table) are FP8 E4M3 bytes and the weight is
+    # e4m3(byte) * 2^weight_scale_exp2; everything else follows `dtype`
+    weight_format: str = "native"
+    weight_scale_exp2: int = 0
 
     def as_dict(self):
         return asdict(self)
@@ -52,6 +56,10 @@ class ModelShape:
     def bytes_per_weight(self) -> int:
         return 4 if self.dtype == "f32" else 2
 
+    @property
+    def bytes_per_matrix_weight(self) -> int:
+        return 1 if self.weight_format == "fp8" else self.bytes_per_weight
+
 
 SHAPES = {
     "tiny": ModelShape("tiny", 2, 256, 4, 4, 64, 688, 1024, dtype="f32"),
@@ -60,6 +68,13 @@ SHAPES = {
     "llama7b": ModelShape("llama7b", 32, 4096, 32, 32, 128, 11008, 32000),
     "tinyllama": ModelShape("tinyllama", 22, 2048, 32, 4, 64, 5632, 32000),
     "llama70b": ModelShape("llama70b", 80, 8192, 64, 8, 128, 28672, 32000),
+    # the same shapes with 8-bit weight matrices; N(0, 0.02) times 2^11 sits well inside +-448
+    "tiny_w8": ModelShape("tiny_w8", 2, 256, 4, 4, 64, 688, 1024, weight_format="fp8", weight_scale_exp2=-11),
+    "tiny_gqa_w8": ModelShape("tiny_gqa_w8", 3, 256, 8, 2, 32, 352, 512, weight_format="fp8", weight_scale_exp2=-11),
+    "llama7b_w8": ModelShape("llama7b_w8", 32, 4096, 32, 32, 128, 11008, 32000, weight_format="fp8",
+                             weight_scale_exp2=-11),
+    "llama70b_w8": ModelShape("llama70b_w8", 80, 8192, 64, 8, 128, 28672, 32000, weight_format="fp8",
+                              weight_scale_exp2=-11),
 }
 
 # Tensor kinds (also the upper part of the generator stream id).
@@ -125,6 +140,7 @@ def host_lib():
                                                       ctypes.c_uint32]
         _host.synth_debug_pair_host.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                                 ctypes.c_void_p]
+        _host.synth_debug_e4m3_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
     return _host
 
 
@@ -147,11 +163,15 @@ def hip_lib():
 # ----------------------------------------------------------------------------- host fills
 
 
+_CODE = {"f32": 0, "bf16": 1, "fp8": 2}
+_NP = {"f32": np.float32, "bf16": np.uint16, "fp8": np.uint8}
+
+
 def normal_host(n: int, seed: int, sid: int, sigma: float, dtype: str) -> np.ndarray:
-    """n values ~ N(0, sigma^2); dtype "f32" -> float32 array, "bf16" -> uint16 bit patterns."""
-    out = np.empty(n, dtype=np.float32 if dtype == "f32" else np.uint16)
-    rc = host_lib().synth_fill_normal_host(out.ctypes.data, n, seed, sid, float(sigma),
-                                           0 if dtype == "f32" else 1)
+    """n values ~ N(0, sigma^2); dtype "f32" -> float32 array, "bf16" -> uint16 bit patterns,
+    "fp8" -> FP8 E4M3 bytes (round to nearest even, saturating)."""
+    out = np.empty(n, dtype=_NP[dtype])
+    rc = host_lib().synth_fill_normal_host(out.ctypes.data, n, seed, sid, float(sigma), _CODE[dtype])
     if rc != 0:
         raise RuntimeError("synth_fill_normal_host failed")
     return out
@@ -163,6 +183,14 @@ def uniform_int_host(n: int, seed: int, sid: int, rng: int) -> np.ndarray:
     if rc != 0:
         raise RuntimeError("synth_fill_uniform_int_host failed")
     return out
+
+
+def f32_to_e4m3_host(x: np.ndarray) -> np.ndarray:
+    """The generator's FP8 rounding applied to given floats (for pin tests)."""
+    src = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(src.size, dtype=np.uint8)
+    host_lib().synth_debug_e4m3_host(src.ctypes.data, out.ctypes.data, src.size)
+    return out.reshape(src.shape)
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -178,7 +206,8 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
 
 def weight_host(shape: ModelShape, seed: int, kind: int, layer: int = 0,
                 gain_sigma: float = 0.0) -> np.ndarray:
-    """One weight tensor in its storage dtype (float32, or uint16 bf16 bits).
+    """One weight tensor in its storage dtype (float32, uint16 bf16 bits, or -- the matrices of
+    a shape with 8-bit weights -- FP8 E4M3 bytes of the value times 2^-weight_scale_exp2).
 
     Matrices ~ N(0, 0.02^2).  RMSNorm gains are exactly 1 (gain_sigma = 0, the default
     recipe) or 1 + N(0, gain_sigma^2) (used by tests so that a dropped gain is visible);
@@ -191,6 +220,9 @@ def weight_host(shape: ModelShape, seed: int, kind: int, layer: int = 0,
             return np.ones(dims, dtype=np.float32)
         return (1.0 + normal_host(n, seed, stream_id(kind, layer), gain_sigma, "f32")).astype(
             np.float32).reshape(dims)
+    if shape.weight_format == "fp8" and kind != T_EMBED:
+        return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2,
+                           "fp8").reshape(dims)
     return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA, shape.dtype).reshape(dims)
 
 
@@ -213,8 +245,7 @@ def tokens_host(shape: ModelShape, seed: int, n: int, kind: int = T_TOKENS, salt
 
 def normal_device(ptr: int, n: int, seed: int, sid: int, sigma: float, dtype: str,
                   stream: int = 0) -> None:
-    rc = hip_lib().synth_fill_normal_device(ptr, n, seed, sid, float(sigma),
-                                            0 if dtype == "f32" else 1, stream)
+    rc = hip_lib().synth_fill_normal_device(ptr, n, seed, sid, float(sigma), _CODE[dtype], stream)
     if rc != 0:
         raise RuntimeError("synth_fill_normal_device failed (%d)" % rc)
 

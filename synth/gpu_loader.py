@@ -17,8 +17,9 @@ _KIND_TO_PI = {
 
 
 def device_normal(n: int, seed: int, sid: int, sigma: float, dtype: str) -> torch.Tensor:
-    """Device tensor of n generator values: float32, or int16 holding bf16 bit patterns."""
-    t = torch.empty(n, dtype=torch.float32 if dtype == "f32" else torch.int16, device="cuda")
+    """Device tensor of n generator values: float32, int16 holding bf16 bit patterns, or uint8
+    holding FP8 E4M3 bytes."""
+    t = torch.empty(n, dtype={"f32": torch.float32, "bf16": torch.int16, "fp8": torch.uint8}[dtype], device="cuda")
     synth.normal_device(t.data_ptr(), n, seed, sid, sigma, dtype, torch.cuda.current_stream().cuda_stream)
     return t
 
@@ -34,6 +35,12 @@ def load_model(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0, max_
             m.set_tensor(_KIND_TO_PI[kind], layer, synth.weight_host(shape, seed, kind, layer, gain_sigma))
             return
         rows, cols = synth.tensor_shape(shape, kind)
+        if shape.weight_format == "fp8" and kind != synth.T_EMBED:
+            t = device_normal(rows * cols, seed, synth.stream_id(kind, layer),
+                              synth.WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2, "fp8")
+            torch.cuda.current_stream().synchronize()
+            m.set_tensor(_KIND_TO_PI[kind], layer, t)
+            return
         t = device_normal(rows * cols, seed, synth.stream_id(kind, layer), synth.WEIGHT_SIGMA, shape.dtype)
         torch.cuda.current_stream().synchronize()
         if shape.dtype == "bf16":

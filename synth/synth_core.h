@@ -15,7 +15,8 @@
  *   h1 = mix(key + 2p), h2 = mix(key + 2p + 1)
  *   u1 = ((h1 >> 11) + 1) * 2^-53  in (0,1],  u2 = (h2 >> 11) * 2^-53 in [0,1)
  *   r = sqrt(-2 ln u1);  z = r cos(2 pi u2) for even i,  r sin(2 pi u2) for odd i
- * (Box-Muller).  value = (float)(sigma * z), optionally rounded to bf16 (RNE).
+ * (Box-Muller).  value = (float)(sigma * z), optionally rounded to bf16 (RNE) or to an FP8 E4M3
+ * byte (RNE, saturating).
  */
 #ifndef PI_SYNTH_CORE_H
 #define PI_SYNTH_CORE_H
@@ -143,6 +144,27 @@ SYNTH_FN uint16_t synth_f32_to_bf16(float f) {
   uint32_t u = c.u;
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
+}
+
+/* fp32 -> FP8 E4M3 byte (4 exponent bits with bias 7, 3 mantissa bits, subnormals, no infinity;
+ * the OCP 8-bit format): round to nearest even, magnitudes beyond the largest finite value
+ * (448) saturate to it.  Finite inputs only.  Integer arithmetic except one exact rounding of a
+ * value below 8 to an integer, so host and device agree bit for bit. */
+SYNTH_FN uint8_t synth_f32_to_e4m3(float f) {
+  union { float f; uint32_t u; } c;
+  c.f = f;
+  const uint32_t sign = (c.u >> 24) & 0x80u;
+  const uint32_t a = c.u & 0x7fffffffu;
+  uint32_t b;
+  if (a < 0x3c800000u) {             /* |f| < 2^-6: subnormal range, steps of 2^-9 */
+    c.u = a;
+    b = (uint32_t)__builtin_rintf(c.f * 512.0f); /* 0..8; 8 is the smallest normal, bit pattern 0x08 */
+  } else {
+    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u); /* RNE at three mantissa bits */
+    b = (r >> 20) - (120u << 3);     /* rebias 127 -> 7 */
+    if (b > 0x7eu) b = 0x7eu;        /* 448 */
+  }
+  return (uint8_t)(sign | b);
 }
 
 /* Uniform integer in [0, range) for element i. */

@@ -20,6 +20,11 @@ ODD_SHAPES = {
     "odd_bf16_hd64": synth.ModelShape("odd_bf16_hd64", 2, 160, 5, 5, 64, 176, 112, dtype="bf16"),
     "odd_bf16_hd128": synth.ModelShape("odd_bf16_hd128", 1, 384, 3, 3, 128, 1040, 2000, dtype="bf16"),
     "odd_f32_gqa8": synth.ModelShape("odd_f32_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="f32"),
+    # 8-bit weight matrices (64-column tiles): feature counts that end inside a tile's first and second half
+    "odd_w8_hd128": synth.ModelShape("odd_w8_hd128", 1, 384, 3, 3, 128, 1040, 2000, dtype="bf16", weight_format="fp8",
+                                     weight_scale_exp2=-11),
+    "odd_w8_gqa8": synth.ModelShape("odd_w8_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="bf16", weight_format="fp8",
+                                    weight_scale_exp2=-9),
 }
 
 

@@ -26,11 +26,12 @@ def check_logits(gpu, ref, dtype):
 
 
 def test_device_fill_equals_host_fill():
-    for dtype in ("f32", "bf16"):
+    for dtype in ("f32", "bf16", "fp8"):
         n = 1_000_003
         sid = synth.stream_id(synth.T_WD, 7)
-        host = synth.normal_host(n, 3, sid, 0.02, dtype)
-        dev = gpu_loader.device_normal(n, 3, sid, 0.02, dtype).cpu().numpy()
+        sigma = 0.02 * (2048 if dtype == "fp8" else 1)       # 8-bit weights are stored scaled up
+        host = synth.normal_host(n, 3, sid, sigma, dtype)
+        dev = gpu_loader.device_normal(n, 3, sid, sigma, dtype).cpu().numpy()
         if dtype == "bf16":
             dev = dev.view(np.uint16)
         assert np.array_equal(host, dev)
@@ -60,7 +61,8 @@ def _true_prefill(sh, seed, gain_sigma, n_prefill, n_cells):
     return om, okv, gm, gkv, last_o, last_g
 
 
-@pytest.mark.parametrize("shape_name,gain_sigma", [("tiny", 0.0), ("tiny", 0.1), ("tiny_bf16", 0.1), ("tiny_gqa", 0.1)])
+@pytest.mark.parametrize("shape_name,gain_sigma", [("tiny", 0.0), ("tiny", 0.1), ("tiny_bf16", 0.1), ("tiny_gqa", 0.1),
+                                                   ("tiny_w8", 0.1), ("tiny_gqa_w8", 0.1)])
 def test_planted_draft_verify_and_rollback(shape_name, gain_sigma):
     """Tiny configuration: 64 prefilled positions, 4 draft tokens planted to agree with the
     oracle's argmax for the first 2; accepted count, bonus token and kv_len must match."""

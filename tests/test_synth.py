@@ -84,3 +84,57 @@ def test_tree_structure():
 def test_cancel_schedule_half():
     s = synth.cancel_schedule(0, 8, 32)
     assert sum(1 for v in s if v >= 0) == 4 and all(-1 <= v < 32 for v in s)
+
+
+# ---- 8-bit weights: rounding to FP8 E4M3 and its decode table --------------------------------------
+
+def test_e4m3_decode_table_matches_library_type_and_closed_forms():
+    import torch
+    from oracle import from_synth
+    t = from_synth.E4M3
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy().astype(np.float64)
+    finite = ~np.isnan(ref)
+    assert np.array_equal(np.isnan(t), ~finite) and np.array_equal(t[finite], ref[finite])
+    assert np.isnan(t[0x7f]) and np.isnan(t[0xff]) and finite.sum() == 254
+    assert t[0x7e] == 448.0 and t[0x08] == 2.0 ** -6 and t[0x01] == 2.0 ** -9 and t[0x38] == 1.0
+    assert np.all(np.diff(t[:0x7f]) > 0) and np.array_equal(t[0x80:0xff], -t[:0x7f])
+    # exact in float32, scale included
+    assert np.array_equal(from_synth.dequantise_fp8(np.arange(0x7f, dtype=np.uint8), -11).astype(np.float64), t[:0x7f] / 2048)
+
+
+def test_e4m3_rounding_is_nearest_even_and_saturates():
+    import torch
+    from oracle import from_synth
+    t = from_synth.E4M3
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.normal(size=20000) * s for s in (1e-3, 0.02, 1.0, 40.0, 150.0)]).astype(np.float32)
+    x = np.concatenate([x, np.array([0.0, -0.0, 2.0 ** -10, 3 * 2.0 ** -10, 2.0 ** -6, 447.9, 448.0, 464.0, 479.9, 1e6, -1e6],
+                                    dtype=np.float32)])
+    got = synth.f32_to_e4m3_host(x)
+    # brute force: the nearest finite code; ties go to the even code (even mantissa); beyond 448: 448
+    vals = t[:0x7f]
+    ax = np.abs(x.astype(np.float64))
+    d = np.abs(ax[:, None] - vals[None, :])
+    best = d.min(axis=1)
+    want = np.empty(len(x), dtype=np.int64)
+    for i in range(len(x)):
+        c = np.flatnonzero(d[i] == best[i])
+        want[i] = c[0] if len(c) == 1 else (c[0] if c[0] % 2 == 0 else c[1])
+    want = want | np.where(np.signbit(x), 0x80, 0)
+    assert np.array_equal(got.astype(np.int64), want)
+    # the library's own conversion agrees wherever it does not overflow
+    inr = ax <= 448.0
+    lib = torch.from_numpy(x[inr]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(got[inr], lib)
+    # ties, written out: 2^-10 lies between 0 and 2^-9 -> even code 0; 3*2^-10 between codes 1 and 2 -> 2
+    assert synth.f32_to_e4m3_host(np.array([2.0 ** -10, 3 * 2.0 ** -10, 464.0, -1e6], dtype=np.float32)).tolist() == [0, 2, 0x7e, 0xfe]
+
+
+def test_fp8_weight_stream_is_the_rounded_float_stream():
+    from oracle import from_synth
+    sid = synth.stream_id(synth.T_WQ, 3)
+    f = synth.normal_host(5001, 7, sid, 0.02, "f32")
+    q = synth.normal_host(5001, 7, sid, 0.02 * 2048, "fp8")
+    assert np.array_equal(q, synth.f32_to_e4m3_host(f * np.float32(2048)))
+    w = from_synth.dequantise_fp8(q, -11)
+    assert np.max(np.abs(w - f) / np.maximum(np.abs(f), 2.0 ** -17)) <= 2.0 ** -4     # half a step of three mantissa bits
