@@ -70,6 +70,33 @@ def test_llama7b_linear_runs_match_oracle(llama7b):
     assert len(kv) == T
 
 
+def test_llama7b_with_8bit_weights_matches_oracle():
+    """The same shape with FP8 E4M3 weight matrices streamed at one byte per weight: sampled
+    logits against the oracle evaluated on the dequantised weights."""
+    sh = synth.SHAPES["llama7b_w8"]
+    g = _load("llama7b_w8_linear")
+    m = gpu_loader.load_model(sh, g["seed"])
+    layer_bytes, lm_bytes = m.weight_bytes()
+    assert layer_bytes == sh.layer_params and lm_bytes == sh.vocab * sh.d_model      # one byte per weight
+    T = g["prefix"]
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
+    cols = np.asarray(g["cols"])
+    for n_str, rec in g["runs"].items():
+        n = int(n_str)
+        toks = np.asarray(rec["tokens"], dtype=np.int32)
+        run = gpu_loader.make_run(synth.linear_run(n, T), toks)
+        logits = torch.zeros((n, sh.vocab), device="cuda")
+        status = torch.zeros(2, dtype=torch.int32, device="cuda")
+        pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=logits, run_status=status)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
+        worst = _check_rows(logits.cpu().numpy(), rec["rows"], cols)
+        print("8-bit weights n=%d worst sampled logit error / row max: %.2e" % (n, worst))
+        pi.kv_rollback(kv, run.slots, n)
+    m.free()
+
+
 def test_llama7b_concurrent_runs_with_cancellation(llama7b):
     """Eight 4-token tree runs over a shared 1024-cell prefix; half are cancelled before a seeded
     layer (stack issued as two stage calls with the flag stored in between).  Survivors must match
