@@ -49,6 +49,9 @@ extern "C" {
 #define PI_DTYPE_BF16 1
 #define PI_DTYPE_FP8_E4M3 2 /* weight matrices only: 8-bit floats, 4 exponent bits (bias 7), 3 mantissa
                              * bits, subnormals, no infinities, 0x7f/0xff = NaN (the OCP FP8 E4M3 format) */
+#define PI_DTYPE_FP4_E2M1 3 /* weight matrices only: 4-bit floats, sign, 2 exponent bits (bias 1), 1 mantissa
+                             * bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives (the OCP FP4 E2M1 format);
+                             * two weights per byte, the lower-numbered column in the low nibble */
 #define PI_LOC_HOST 0
 #define PI_LOC_DEVICE 1
 
@@ -87,16 +90,18 @@ typedef struct pi_kv pi_kv;
  * PI_DTYPE_BF16 and weight_dtype PI_DTYPE_FP8_E4M3 the seven weight matrices of every layer
  * and the LM head are stored and streamed as 8-bit floats, one byte per weight, and decoded
  * inside the projection kernels: weight = e4m3(byte) * 2^weight_scale_exp2 (one power-of-two
- * scale for the whole model; -32 <= weight_scale_exp2 <= 32).  Everything else (activations,
- * embedding rows, KV cache, accumulation) is as in a bf16 model.  weight_dtype 0 with
- * dtype PI_DTYPE_BF16 is read as "same as dtype". */
+ * scale for the whole model; -32 <= weight_scale_exp2 <= 32).  With weight_dtype
+ * PI_DTYPE_FP4_E2M1 they are stored and streamed at half a byte per weight: weight =
+ * e2m1(nibble) * 2^weight_scale_exp2.  Everything else (activations, embedding rows, KV cache,
+ * accumulation) is as in a bf16 model.  weight_dtype 0 with dtype PI_DTYPE_BF16 is read as
+ * "same as dtype". */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
   float rms_eps, rope_base;
   int32_t dtype;   /* PI_DTYPE_F32 | PI_DTYPE_BF16 */
   int32_t max_pos; /* positions must be < max_pos */
-  int32_t weight_dtype;      /* 0 or == dtype: matrices in `dtype`; PI_DTYPE_FP8_E4M3 (bf16 models only) */
-  int32_t weight_scale_exp2; /* used with PI_DTYPE_FP8_E4M3 */
+  int32_t weight_dtype;      /* 0 or == dtype: matrices in `dtype`; PI_DTYPE_FP8_E4M3 / PI_DTYPE_FP4_E2M1 (bf16 models only) */
+  int32_t weight_scale_exp2; /* used with the 8-bit and 4-bit formats */
 } pi_model_config;
 
 /* Create a model: allocates device storage for all weights (in the library's own tiled
@@ -108,8 +113,9 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out);
 /* Supply one tensor.  `src` holds the logical row-major tensor in `src_dtype`
  * (PI_DTYPE_F32: float; PI_DTYPE_BF16: 16-bit bf16 patterns) at `src_loc` (host or device).
  * Matrices must come in the model's dtype or in fp32 (rounded to bf16, nearest-even, for
- * a bf16 model); the matrices of a model with 8-bit weights must come as PI_DTYPE_FP8_E4M3
- * bytes (the library does not quantise; the embedding table still comes in bf16 or fp32);
+ * a bf16 model); the matrices of a model with 8-bit or 4-bit weights must come in that format
+ * (PI_DTYPE_FP8_E4M3: [out][in] bytes; PI_DTYPE_FP4_E2M1: [out][in/2] bytes; the library does
+ * not quantise; the embedding table still comes in bf16 or fp32);
  * gains must be fp32.  `layer` is ignored for the three global tensors.
  * The tensor is repacked into the internal layout; `src` may be reused after return.
  * Blocking. */

@@ -38,6 +38,20 @@ def dequantise_fp8(codes: np.ndarray, scale_exp2: int) -> np.ndarray:
     return (E4M3[codes] * 2.0 ** scale_exp2).astype(np.float32)
 
 
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0] + [-0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0])
+
+
+def dequantise_fp4(packed: np.ndarray, scale_exp2: int) -> np.ndarray:
+    """4-bit weights as the model defines them: packed[r][j] holds columns 2j (low nibble) and
+    2j+1 (high nibble) of row r as FP4 E2M1 codes (sign, 2 exponent bits, 1 mantissa bit);
+    weight = e2m1(code) * 2^scale_exp2."""
+    rows, half = packed.shape
+    out = np.empty((rows, 2 * half), dtype=np.float64)
+    out[:, 0::2] = E2M1[packed & 0xF]
+    out[:, 1::2] = E2M1[packed >> 4]
+    return (out * 2.0 ** scale_exp2).astype(np.float32)
+
+
 def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
                     cache: bool = True) -> OracleModel:
     """Weights are regenerated from the seed when asked for; `cache` keeps them (small models)."""
@@ -49,7 +63,7 @@ def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
             return store[key]
         t = synth.weight_host(shape, seed, _NAME_TO_KIND[name], layer, gain_sigma)
         if t.dtype == np.uint8:
-            t = dequantise_fp8(t, shape.weight_scale_exp2)
+            t = (dequantise_fp4 if shape.weight_format == "fp4" else dequantise_fp8)(t, shape.weight_scale_exp2)
         if cache:
             store[key] = t
         return t

@@ -21,7 +21,7 @@ PI_E_FULL, PI_E_BUSY = -7, -8
 PI_MAX_BATCH, PI_WINDOW = 16, 64
 PI_MAX_SEQ, PI_SEQ_CANONICAL, PI_POS_MAX = 32, 0, 0x7FFFFFFF
 PI_RUN_SUPERFLUOUS, PI_RUN_INVALIDATED = 1, 2
-PI_DTYPE_F32, PI_DTYPE_BF16, PI_DTYPE_FP8_E4M3 = 0, 1, 2
+PI_DTYPE_F32, PI_DTYPE_BF16, PI_DTYPE_FP8_E4M3, PI_DTYPE_FP4_E2M1 = 0, 1, 2, 3
 PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 (PI_T_EMBED, PI_T_ATTN_NORM, PI_T_WQ, PI_T_WK, PI_T_WV, PI_T_WO, PI_T_FFN_NORM, PI_T_WG, PI_T_WU,
  PI_T_WD, PI_T_FINAL_NORM, PI_T_LM_HEAD) = range(12)
@@ -168,29 +168,32 @@ class Model:
 
     def __init__(self, shape, max_pos: int = 4096):
         self.shape = shape
-        fp8 = getattr(shape, "weight_format", "native") == "fp8"
+        wf = getattr(shape, "weight_format", "native")
+        fp8 = wf in ("fp8", "fp4")
         cfg = PiModelConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
                             shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps, shape.rope_base,
                             _dtype_code(shape.dtype), max_pos,
-                            PI_DTYPE_FP8_E4M3 if fp8 else _dtype_code(shape.dtype),
+                            {"fp8": PI_DTYPE_FP8_E4M3, "fp4": PI_DTYPE_FP4_E2M1}.get(wf, _dtype_code(shape.dtype)),
                             getattr(shape, "weight_scale_exp2", 0) if fp8 else 0)
         h = c_void_p()
         _check(lib().pi_model_load(byref(cfg), byref(h)), "pi_model_load")
         self.handle = h
 
-    def set_tensor(self, kind: int, layer: int, src):
+    def set_tensor(self, kind: int, layer: int, src, src_dtype=None):
         """src: numpy array (host; float32, uint16 bf16 bits or uint8 FP8 E4M3 bytes) or a torch
         device tensor (float32, bfloat16, int16/uint16 holding bf16 bits, or uint8 FP8 bytes)."""
         if isinstance(src, np.ndarray):
             src = np.ascontiguousarray(src)
             code = {np.dtype(np.float32): PI_DTYPE_F32, np.dtype(np.uint16): PI_DTYPE_BF16,
                     np.dtype(np.uint8): PI_DTYPE_FP8_E4M3}[src.dtype]
+            code = code if src_dtype is None else src_dtype
             st = lib().pi_model_set_tensor(self.handle, kind, layer, c_void_p(src.ctypes.data), code, PI_LOC_HOST)
         else:
             import torch
             assert src.is_cuda and src.is_contiguous()
             code = (PI_DTYPE_F32 if src.dtype == torch.float32 else
                     PI_DTYPE_FP8_E4M3 if src.dtype == torch.uint8 else PI_DTYPE_BF16)
+            code = code if src_dtype is None else src_dtype
             st = lib().pi_model_set_tensor(self.handle, kind, layer, _ptr(src), code, PI_LOC_DEVICE)
         _check(st, "pi_model_set_tensor")
 

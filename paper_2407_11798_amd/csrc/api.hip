@@ -80,6 +80,9 @@ PackedMat make_packed(int N, int K, int dtype) {
   p.K = K;
   p.NRB = (N + kRowBlock - 1) / kRowBlock;
   p.KT = (K + weight_tile_cols(dtype) - 1) / weight_tile_cols(dtype);
+  // 4-bit tiles are 128 columns wide: rounded up to a multiple of eight tiles (zero weights), so that the
+  // tile count still splits into power-of-two column slices and a short contraction still fills a ring
+  if (dtype == kWeightFP4) p.KT = (p.KT + 7) / 8 * 8;
   p.bytes = (size_t)p.NRB * p.KT * weight_tile_bytes(dtype);
   return p;
 }
@@ -193,7 +196,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (c.d_model % 32 || (c.n_q_heads * c.head_dim) % 32 || c.ffn % 16 || c.vocab % 16) return PI_E_SHAPE;
   if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8) return PI_E_SHAPE;
   if (c.dtype != PI_DTYPE_F32 && c.dtype != PI_DTYPE_BF16) return PI_E_SHAPE;
-  const bool w8 = c.weight_dtype == PI_DTYPE_FP8_E4M3;
+  const bool w8 = c.weight_dtype == PI_DTYPE_FP8_E4M3 || c.weight_dtype == PI_DTYPE_FP4_E2M1;
   if (w8 ? (c.dtype != PI_DTYPE_BF16 || c.weight_scale_exp2 < -32 || c.weight_scale_exp2 > 32)
          : (c.weight_dtype != c.dtype && !(c.weight_dtype == 0 && c.dtype == PI_DTYPE_BF16)))
     return PI_E_SHAPE;
@@ -202,7 +205,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   pi_model* m = new (std::nothrow) pi_model();
   if (!m) return PI_E_OOM;
   m->cfg = c;
-  m->wdtype = w8 ? kWeightFP8 : c.dtype;
+  m->wdtype = w8 ? c.weight_dtype : c.dtype;
   const int wd = m->wdtype;
   const int d = c.d_model, nq = c.n_q_heads * c.head_dim, nkv = c.n_kv_heads * c.head_dim;
   const int es = c.dtype == PI_DTYPE_BF16 ? 2 : 4;
@@ -321,7 +324,7 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
                             int32_t src_loc) {
   if (!m || !src) return PI_E_ARG;
   if (kind < PI_T_EMBED || kind > PI_T_LM_HEAD) return PI_E_ARG;
-  if (src_dtype != PI_DTYPE_F32 && src_dtype != PI_DTYPE_BF16 && src_dtype != PI_DTYPE_FP8_E4M3) return PI_E_ARG;
+  if (src_dtype < PI_DTYPE_F32 || src_dtype > PI_DTYPE_FP4_E2M1) return PI_E_ARG;
   if (src_loc != PI_LOC_HOST && src_loc != PI_LOC_DEVICE) return PI_E_ARG;
   if (is_layer_kind(kind) && (layer < 0 || layer >= m->cfg.n_layers)) return PI_E_ARG;
   const pi_model_config& c = m->cfg;
@@ -329,9 +332,11 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
   const bool is_gain = kind == PI_T_ATTN_NORM || kind == PI_T_FFN_NORM || kind == PI_T_FINAL_NORM;
   if (is_gain && src_dtype != PI_DTYPE_F32) return PI_E_ARG;
   if (!is_gain && src_dtype == PI_DTYPE_BF16 && c.dtype == PI_DTYPE_F32) return PI_E_ARG;
-  // 8-bit weights: the streamed matrices come as bytes and nothing else does
+  // quantised weights: the streamed matrices come in the model's weight format and nothing else does
   const bool is_matrix = !is_gain && kind != PI_T_EMBED;
-  if ((src_dtype == PI_DTYPE_FP8_E4M3) != (is_matrix && m->wdtype == kWeightFP8)) return PI_E_ARG;
+  const bool quantised_src = src_dtype == PI_DTYPE_FP8_E4M3 || src_dtype == PI_DTYPE_FP4_E2M1;
+  const bool quantised_dst = is_matrix && (m->wdtype == kWeightFP8 || m->wdtype == kWeightFP4);
+  if (quantised_src != quantised_dst || (quantised_src && src_dtype != m->wdtype)) return PI_E_ARG;
   const int wd = m->wdtype;
   int rows = 1, cols = d;
   switch (kind) {
@@ -343,7 +348,9 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
     case PI_T_WD: rows = d; cols = c.ffn; break;
     default: break;
   }
-  const size_t src_bytes = (size_t)rows * cols * (src_dtype == PI_DTYPE_FP8_E4M3 ? 1 : src_dtype == PI_DTYPE_BF16 ? 2 : 4);
+  if (src_dtype == PI_DTYPE_FP4_E2M1 && cols % 2) return PI_E_SHAPE;
+  const size_t src_bytes = src_dtype == PI_DTYPE_FP4_E2M1 ? (size_t)rows * cols / 2
+                           : (size_t)rows * cols * (src_dtype == PI_DTYPE_FP8_E4M3 ? 1 : src_dtype == PI_DTYPE_BF16 ? 2 : 4);
   const void* dsrc = src;
   void* staging = nullptr;
   hipError_t e = hipSuccess;
@@ -673,7 +680,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.vocab = c.vocab;
   a.n_layers = L;
   a.eps = c.rms_eps;
-  a.wscale = m->wdtype == kWeightFP8 ? std::ldexp(1.0f, c.weight_scale_exp2) : 1.0f;
+  a.wscale = m->wdtype == kWeightFP8 || m->wdtype == kWeightFP4 ? std::ldexp(1.0f, c.weight_scale_exp2) : 1.0f;
   a.n = n;
   a.tokens = run->tokens;
   a.positions = run->positions;

@@ -62,6 +62,27 @@ __global__ void __launch_bounds__(256) repack_fp8_kernel(const uint8_t* src, int
   }
 }
 
+// 4-bit weights: one thread per (source row, 4 bytes = 8 weights of the row); nibbles are copied.
+__global__ void __launch_bounds__(256) repack_fp4_kernel(const uint8_t* src, int rows, int cols, char* dst, int KT,
+                                                         int row_mul, int row_add) {
+  const int chunks_per_row = KT * 16;  // 128 columns per tile
+  const size_t total = (size_t)rows * chunks_per_row;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / chunks_per_row);
+    const int c = (int)(i % chunks_per_row);
+    const int pr = r * row_mul + row_add;
+    const int rb = pr / kRowBlock, lr = pr % kRowBlock;
+    const int k0 = c * 8;
+    uint32_t w = 0u;
+    for (int j = 0; j < 4; ++j)  // cols is even: a byte is inside the row or outside it as a whole
+      if (k0 + 2 * j < cols) w |= (uint32_t)src[((size_t)r * cols + k0) / 2 + j] << (8 * j);
+    const int t = c / 16, q = c % 16, h = q / 4, g = q % 4;  // 32-column quarter of the tile, 8-column group
+    const size_t off = ((size_t)rb * KT + t) * 1024 + (size_t)(g * 16 + lr) * 16 + (size_t)h * 4;
+    *(uint32_t*)(dst + off) = w;
+  }
+}
+
 __global__ void __launch_bounds__(256) convert_kernel(const void* src, int src_dtype, void* dst,
                                                       int dst_dtype, size_t count) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
@@ -91,6 +112,15 @@ hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, Pac
     if (blocks8 > 16384) blocks8 = 16384;
     if (blocks8 == 0) return hipSuccess;
     repack_fp8_kernel<<<dim3((unsigned)blocks8), dim3(256), 0, s>>>((const uint8_t*)src, rows, cols, (char*)dst.data,
+                                                                    dst.KT, row_mul, row_add);
+    return hipGetLastError();
+  }
+  if (dst_dtype == kWeightFP4) {
+    const size_t total4 = (size_t)rows * dst.KT * 16;
+    size_t blocks4 = (total4 + 255) / 256;
+    if (blocks4 > 16384) blocks4 = 16384;
+    if (blocks4 == 0) return hipSuccess;
+    repack_fp4_kernel<<<dim3((unsigned)blocks4), dim3(256), 0, s>>>((const uint8_t*)src, rows, cols, (char*)dst.data,
                                                                     dst.KT, row_mul, row_add);
     return hipGetLastError();
   }

@@ -25,6 +25,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 //   fp8 tile  (1 KiB): 16 rows x 64 columns, one byte per weight; lane l holds, in bytes 0..7,
 //                      W[16rb + (l&15)][64t + 8(l>>4) + 0..7] and, in bytes 8..15, the same for
 //                      columns 64t + 32 + ...: two consecutive bf16-shaped tiles in one 16-byte piece.
+//   fp4 tile  (1 KiB): 16 rows x 128 columns, two weights per byte; lane l holds, in bytes 4h..4h+3
+//                      (h = 0..3), W[16rb + (l&15)][128t + 32h + 8(l>>4) + 0..7], lower column in the
+//                      low nibble: four consecutive bf16-shaped tiles in one 16-byte piece.
 // Rows >= N and columns >= K are zero.  KT counts tiles of the matrix's own width.
 struct PackedMat {
   void* data = nullptr;
@@ -35,8 +38,9 @@ struct PackedMat {
 
 // Weight format of a model as the kernels see it: the activation side of PI_DTYPE_FP8_E4M3 is
 // that of a bf16 model; only the matrices differ.
-constexpr int kWeightF32 = PI_DTYPE_F32, kWeightBF16 = PI_DTYPE_BF16, kWeightFP8 = PI_DTYPE_FP8_E4M3;
-__host__ __device__ constexpr int weight_tile_cols(int wd) { return wd == kWeightFP8 ? 64 : 32; }
+constexpr int kWeightF32 = PI_DTYPE_F32, kWeightBF16 = PI_DTYPE_BF16, kWeightFP8 = PI_DTYPE_FP8_E4M3,
+              kWeightFP4 = PI_DTYPE_FP4_E2M1;
+__host__ __device__ constexpr int weight_tile_cols(int wd) { return wd == kWeightFP4 ? 128 : wd == kWeightFP8 ? 64 : 32; }
 __host__ __device__ constexpr int weight_tile_bytes(int wd) { return wd == kWeightF32 ? 2048 : 1024; }
 
 struct LayerWeights {

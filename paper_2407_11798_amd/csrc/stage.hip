@@ -730,7 +730,7 @@ template <int DT, int UR, int J0, int J1>
 __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeState& C, const PassPlan& P,
                                               const PassLane& PLn) {
   constexpr int NG = J1 - J0;
-  constexpr int NX = DT == kWeightFP8 ? 2 : 1;  // 32-column operand slots per weight tile
+  constexpr int NX = weight_tile_cols(DT) / 32;  // 32-column operand slots per weight tile
   u32x4 x0[NG][NX], x1[NG][NX];
 #pragma unroll
   for (int j = 0; j < NG; ++j) {
@@ -738,10 +738,11 @@ __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeStat
     const int off = J < P.nc ? (J < P.ec ? P.cbaseA : P.cbaseB) + J * P.stride : P.zoff;
     x0[j][0] = *(const u32x4*)(PLn.b0 + off);
     x1[j][0] = *(const u32x4*)(PLn.b1 + off);
-    if constexpr (NX == 2) {  // the tile's second half: the next operand slot (the zero slot has no neighbour)
-      const int off2 = J < P.nc ? off + (P.stride >> 1) : P.zoff;
-      x0[j][1] = *(const u32x4*)(PLn.b0 + off2);
-      x1[j][1] = *(const u32x4*)(PLn.b1 + off2);
+#pragma unroll
+    for (int h = 1; h < NX; ++h) {  // the tile's further parts: the next operand slots (the zero slot has no neighbours)
+      const int offh = J < P.nc ? off + h * (P.stride / NX) : P.zoff;
+      x0[j][h] = *(const u32x4*)(PLn.b0 + offh);
+      x1[j][h] = *(const u32x4*)(PLn.b1 + offh);
     }
   }
 #pragma unroll
@@ -762,6 +763,20 @@ __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeStat
         o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], PLn.wscale, true));
         o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, false));
         o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, true));
+        const bf16x8 av = __builtin_bit_cast(bf16x8, o);
+        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
+        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
+      }
+    } else if constexpr (DT == kWeightFP4) {
+      // sixteen bytes -> four bf16 operands (one per 32 columns), one byte = two weights
+      const u32x4 w = R.r[J];
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        u32x4 o;
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 0));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 1));
+        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 2));
+        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 3));
         const bf16x8 av = __builtin_bit_cast(bf16x8, o);
         C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
         C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
@@ -1595,6 +1610,11 @@ size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
 
 namespace {
 const void* stage_fn(int dtype, int ring) {
+  if (dtype == kWeightFP4) {
+    if (ring == 16) return (const void*)stage_kernel<kWeightFP4, 16>;
+    if (ring == 8) return (const void*)stage_kernel<kWeightFP4, 8>;
+    return (const void*)stage_kernel<kWeightFP4, 4>;
+  }
   if (dtype == kWeightFP8) {
     if (ring == 16) return (const void*)stage_kernel<kWeightFP8, 16>;
     if (ring == 8) return (const void*)stage_kernel<kWeightFP8, 8>;

@@ -39,8 +39,9 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
     dtype: str = "bf16"  # storage type of weights and KV cache: "f32" or "bf16"
-    # "fp8": the weight matrices (not the embedding table) are FP8 E4M3 bytes and the weight is
-    # e4m3(byte) * 2^weight_scale_exp2; everything else follows `dtype`
+    # "fp8" / "fp4": the weight matrices (not the embedding table) are FP8 E4M3 bytes / FP4 E2M1
+    # nibbles (two per byte) and the weight is code value * 2^weight_scale_exp2; everything else
+    # follows `dtype`
     weight_format: str = "native"
     weight_scale_exp2: int = 0
 
@@ -58,7 +59,7 @@ class ModelShape:
 
     @property
     def bytes_per_matrix_weight(self) -> int:
-        return 1 if self.weight_format == "fp8" else self.bytes_per_weight
+        return {"fp8": 1, "fp4": 0.5}.get(self.weight_format, self.bytes_per_weight)
 
 
 SHAPES = {
@@ -75,6 +76,13 @@ SHAPES = {
                              weight_scale_exp2=-11),
     "llama70b_w8": ModelShape("llama70b_w8", 80, 8192, 64, 8, 128, 28672, 32000, weight_format="fp8",
                               weight_scale_exp2=-11),
+    # 4-bit weight matrices; N(0, 0.02) times 2^6 has its standard deviation at 1.28 of a range of +-6
+    "tiny_w4": ModelShape("tiny_w4", 2, 256, 4, 4, 64, 688, 1024, weight_format="fp4", weight_scale_exp2=-6),
+    "tiny_gqa_w4": ModelShape("tiny_gqa_w4", 3, 256, 8, 2, 32, 352, 512, weight_format="fp4", weight_scale_exp2=-6),
+    "llama7b_w4": ModelShape("llama7b_w4", 32, 4096, 32, 32, 128, 11008, 32000, weight_format="fp4",
+                             weight_scale_exp2=-6),
+    "llama70b_w4": ModelShape("llama70b_w4", 80, 8192, 64, 8, 128, 28672, 32000, weight_format="fp4",
+                              weight_scale_exp2=-6),
 }
 
 # Tensor kinds (also the upper part of the generator stream id).
@@ -141,6 +149,7 @@ def host_lib():
         _host.synth_debug_pair_host.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
                                                 ctypes.c_void_p]
         _host.synth_debug_e4m3_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        _host.synth_debug_e2m1_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
     return _host
 
 
@@ -163,14 +172,15 @@ def hip_lib():
 # ----------------------------------------------------------------------------- host fills
 
 
-_CODE = {"f32": 0, "bf16": 1, "fp8": 2}
-_NP = {"f32": np.float32, "bf16": np.uint16, "fp8": np.uint8}
+_CODE = {"f32": 0, "bf16": 1, "fp8": 2, "fp4": 3}
+_NP = {"f32": np.float32, "bf16": np.uint16, "fp8": np.uint8, "fp4": np.uint8}
 
 
 def normal_host(n: int, seed: int, sid: int, sigma: float, dtype: str) -> np.ndarray:
     """n values ~ N(0, sigma^2); dtype "f32" -> float32 array, "bf16" -> uint16 bit patterns,
-    "fp8" -> FP8 E4M3 bytes (round to nearest even, saturating)."""
-    out = np.empty(n, dtype=_NP[dtype])
+    "fp8" -> FP8 E4M3 bytes, "fp4" -> n/2 bytes of two FP4 E2M1 nibbles each, element 2p in the
+    low nibble (both round to nearest even, saturating)."""
+    out = np.empty(n // 2 if dtype == "fp4" else n, dtype=_NP[dtype])
     rc = host_lib().synth_fill_normal_host(out.ctypes.data, n, seed, sid, float(sigma), _CODE[dtype])
     if rc != 0:
         raise RuntimeError("synth_fill_normal_host failed")
@@ -190,6 +200,14 @@ def f32_to_e4m3_host(x: np.ndarray) -> np.ndarray:
     src = np.ascontiguousarray(x, dtype=np.float32)
     out = np.empty(src.size, dtype=np.uint8)
     host_lib().synth_debug_e4m3_host(src.ctypes.data, out.ctypes.data, src.size)
+    return out.reshape(src.shape)
+
+
+def f32_to_e2m1_host(x: np.ndarray) -> np.ndarray:
+    """The generator's FP4 rounding applied to given floats: one nibble per element (for pin tests)."""
+    src = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(src.size, dtype=np.uint8)
+    host_lib().synth_debug_e2m1_host(src.ctypes.data, out.ctypes.data, src.size)
     return out.reshape(src.shape)
 
 
@@ -223,6 +241,9 @@ def weight_host(shape: ModelShape, seed: int, kind: int, layer: int = 0,
     if shape.weight_format == "fp8" and kind != T_EMBED:
         return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2,
                            "fp8").reshape(dims)
+    if shape.weight_format == "fp4" and kind != T_EMBED:
+        return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2,
+                           "fp4").reshape(dims[0], dims[1] // 2)
     return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA, shape.dtype).reshape(dims)
 
 

@@ -19,7 +19,8 @@ _KIND_TO_PI = {
 def device_normal(n: int, seed: int, sid: int, sigma: float, dtype: str) -> torch.Tensor:
     """Device tensor of n generator values: float32, int16 holding bf16 bit patterns, or uint8
     holding FP8 E4M3 bytes."""
-    t = torch.empty(n, dtype={"f32": torch.float32, "bf16": torch.int16, "fp8": torch.uint8}[dtype], device="cuda")
+    t = torch.empty(n // 2 if dtype == "fp4" else n, dtype={"f32": torch.float32, "bf16": torch.int16, "fp8": torch.uint8, "fp4": torch.uint8}[dtype],
+                    device="cuda")
     synth.normal_device(t.data_ptr(), n, seed, sid, sigma, dtype, torch.cuda.current_stream().cuda_stream)
     return t
 
@@ -32,14 +33,19 @@ def load_model(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0, max_
 
     def put(kind, layer):
         if kind in synth.NORM_KINDS or from_host:
-            m.set_tensor(_KIND_TO_PI[kind], layer, synth.weight_host(shape, seed, kind, layer, gain_sigma))
+            t = synth.weight_host(shape, seed, kind, layer, gain_sigma)
+            code = None
+            if t.dtype == np.uint8:
+                code = pi.PI_DTYPE_FP4_E2M1 if shape.weight_format == "fp4" else pi.PI_DTYPE_FP8_E4M3
+            m.set_tensor(_KIND_TO_PI[kind], layer, t, src_dtype=code)
             return
         rows, cols = synth.tensor_shape(shape, kind)
-        if shape.weight_format == "fp8" and kind != synth.T_EMBED:
+        if shape.weight_format in ("fp8", "fp4") and kind != synth.T_EMBED:
             t = device_normal(rows * cols, seed, synth.stream_id(kind, layer),
-                              synth.WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2, "fp8")
+                              synth.WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2, shape.weight_format)
             torch.cuda.current_stream().synchronize()
-            m.set_tensor(_KIND_TO_PI[kind], layer, t)
+            m.set_tensor(_KIND_TO_PI[kind], layer, t,
+                         src_dtype=pi.PI_DTYPE_FP4_E2M1 if shape.weight_format == "fp4" else pi.PI_DTYPE_FP8_E4M3)
             return
         t = device_normal(rows * cols, seed, synth.stream_id(kind, layer), synth.WEIGHT_SIGMA, shape.dtype)
         torch.cuda.current_stream().synchronize()

@@ -16,7 +16,7 @@
  *   u1 = ((h1 >> 11) + 1) * 2^-53  in (0,1],  u2 = (h2 >> 11) * 2^-53 in [0,1)
  *   r = sqrt(-2 ln u1);  z = r cos(2 pi u2) for even i,  r sin(2 pi u2) for odd i
  * (Box-Muller).  value = (float)(sigma * z), optionally rounded to bf16 (RNE) or to an FP8 E4M3
- * byte (RNE, saturating).
+ * byte or an FP4 E2M1 nibble (both RNE, saturating; two nibbles per byte, even element low).
  */
 #ifndef PI_SYNTH_CORE_H
 #define PI_SYNTH_CORE_H
@@ -165,6 +165,20 @@ SYNTH_FN uint8_t synth_f32_to_e4m3(float f) {
     if (b > 0x7eu) b = 0x7eu;        /* 448 */
   }
   return (uint8_t)(sign | b);
+}
+
+/* fp32 -> FP4 E2M1 nibble (sign, 2 exponent bits with bias 1, 1 mantissa bit: magnitudes 0, 0.5,
+ * 1, 1.5, 2, 3, 4, 6; the OCP 4-bit format): round to nearest, ties to the code with mantissa
+ * bit 0, magnitudes beyond 6 saturate.  Finite inputs only; comparisons with exactly
+ * representable constants, so host and device agree. */
+SYNTH_FN uint8_t synth_f32_to_e2m1(float f) {
+  union { float f; uint32_t u; } c;
+  c.f = f;
+  const uint8_t sign = (uint8_t)((c.u >> 28) & 0x8u);
+  c.u &= 0x7fffffffu;
+  const float a = c.f;
+  const int code = (a > 0.25f) + (a >= 0.75f) + (a > 1.25f) + (a >= 1.75f) + (a > 2.5f) + (a >= 3.5f) + (a > 5.0f);
+  return (uint8_t)(sign | (uint8_t)code);
 }
 
 /* Uniform integer in [0, range) for element i. */

@@ -31,7 +31,7 @@ __global__ void __launch_bounds__(256) fill_normal_kernel(void* dst, int64_t n, 
       } else {
         d[i] = (uint16_t)lo;
       }
-    } else {
+    } else if (DTYPE == 2) {
       uint8_t* d = (uint8_t*)dst;
       const uint8_t lo = synth_f32_to_e4m3(f0), hi = synth_f32_to_e4m3(f1);
       if (i + 1 < n) {
@@ -39,6 +39,8 @@ __global__ void __launch_bounds__(256) fill_normal_kernel(void* dst, int64_t n, 
       } else {
         d[i] = lo;
       }
+    } else {
+      ((uint8_t*)dst)[p] = (uint8_t)(synth_f32_to_e2m1(f0) | (synth_f32_to_e2m1(f1) << 4));
     }
   }
 }
@@ -52,10 +54,10 @@ __global__ void __launch_bounds__(256) fill_uniform_int_kernel(int32_t* dst, int
 
 }  // namespace
 
-// dst: device pointer, 4-byte aligned. dtype: 0 = fp32, 1 = bf16, 2 = FP8 E4M3 bytes. Asynchronous on `stream`.
+// dst: device pointer, 4-byte aligned. dtype: 0 = fp32, 1 = bf16, 2 = FP8 E4M3 bytes, 3 = FP4 E2M1 (two per byte, n even). Asynchronous on `stream`.
 extern "C" int synth_fill_normal_device(void* dst, int64_t n, uint64_t seed, uint64_t stream_id,
                                         double sigma, int dtype, void* stream) {
-  if (!dst || n < 0 || dtype < 0 || dtype > 2) return -1;
+  if (!dst || n < 0 || dtype < 0 || dtype > 3 || (dtype == 3 && (n & 1))) return -1;
   if (n == 0) return 0;
   const uint64_t key = synth_key(seed, stream_id);
   const int64_t pairs = (n + 1) / 2;
@@ -66,8 +68,10 @@ extern "C" int synth_fill_normal_device(void* dst, int64_t n, uint64_t seed, uin
     fill_normal_kernel<0><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
   else if (dtype == 1)
     fill_normal_kernel<1><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
-  else
+  else if (dtype == 2)
     fill_normal_kernel<2><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
+  else
+    fill_normal_kernel<3><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 

@@ -3,10 +3,11 @@
 #include "synth_core.h"
 #include <stddef.h>
 
-/* dtype: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns), 2 = FP8 E4M3 (bytes) */
+/* dtype: 0 = fp32 (float), 1 = bf16 (uint16 bit patterns), 2 = FP8 E4M3 (bytes),
+ * 3 = FP4 E2M1 (two per byte, element 2p in the low nibble; n must be even) */
 int synth_fill_normal_host(void* dst, int64_t n, uint64_t seed, uint64_t stream_id,
                            double sigma, int dtype) {
-  if (!dst || n < 0 || dtype < 0 || dtype > 2) return -1;
+  if (!dst || n < 0 || dtype < 0 || dtype > 3 || (dtype == 3 && (n & 1))) return -1;
   const uint64_t key = synth_key(seed, stream_id);
   const int64_t pairs = (n + 1) / 2;
 #pragma omp parallel for schedule(static)
@@ -21,9 +22,11 @@ int synth_fill_normal_host(void* dst, int64_t n, uint64_t seed, uint64_t stream_
     } else if (dtype == 1) {
       ((uint16_t*)dst)[i] = synth_f32_to_bf16(f0);
       if (i + 1 < n) ((uint16_t*)dst)[i + 1] = synth_f32_to_bf16(f1);
-    } else {
+    } else if (dtype == 2) {
       ((uint8_t*)dst)[i] = synth_f32_to_e4m3(f0);
       if (i + 1 < n) ((uint8_t*)dst)[i + 1] = synth_f32_to_e4m3(f1);
+    } else {
+      ((uint8_t*)dst)[p] = (uint8_t)(synth_f32_to_e2m1(f0) | (synth_f32_to_e2m1(f1) << 4));
     }
   }
   return 0;
@@ -40,6 +43,11 @@ int synth_fill_uniform_int_host(int32_t* dst, int64_t n, uint64_t seed, uint64_t
 /* Exposed for pin tests: the FP8 rounding of arbitrary floats. */
 int synth_debug_e4m3_host(const float* src, uint8_t* dst, int64_t n) {
   for (int64_t i = 0; i < n; ++i) dst[i] = synth_f32_to_e4m3(src[i]);
+  return 0;
+}
+
+int synth_debug_e2m1_host(const float* src, uint8_t* dst, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) dst[i] = synth_f32_to_e2m1(src[i]);
   return 0;
 }
 

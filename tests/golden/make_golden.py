@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Writes the stored expected values under tests/golden/ by running the CPU oracle only.
 
-Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_w8_linear, llama7b_runs,
+Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_w8_linear, llama7b_w4_linear, llama7b_runs,
 tinyllama_decode, llama70b_layer)
 Every value comes from oracle/ on the seeded synthetic inputs of synth/; nothing here touches
 the HIP library.  The files are small JSON: per logits row the argmax, the top-2 gap, the row's
@@ -53,10 +53,11 @@ def llama7b_linear():
     return out
 
 
-def llama7b_w8_linear():
-    """The Llama-7B shape with 8-bit (FP8 E4M3, one power-of-two scale) weight matrices, bf16
-    activations and cache, 512 synthetic prefix cells, linear runs of 1 and 8 draft tokens."""
-    sh = synth.SHAPES["llama7b_w8"]
+def llama7b_w8_linear(shape_name="llama7b_w8"):
+    """The Llama-7B shape with 8-bit (FP8 E4M3) or 4-bit (FP4 E2M1) weight matrices under one
+    power-of-two scale, bf16 activations and cache, 512 synthetic prefix cells, linear runs of 1
+    and 8 draft tokens."""
+    sh = synth.SHAPES[shape_name]
     seed, T = 0, 512
     om = from_synth.model_from_seed(sh, seed)
     base = from_synth.kv_synthetic(sh, seed, T + 64, T)
@@ -68,8 +69,12 @@ def llama7b_w8_linear():
         toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT, salt=n)
         lg = oracle.stage_forward(om, base.clone(), run, 0, sh.n_layers, tokens=toks)["logits"]
         out["runs"][str(n)] = {"tokens": [int(t) for t in toks], "rows": [row_record(lg[i], cols) for i in range(n)]}
-        print("llama7b_w8_linear n=%d done in %.0fs" % (n, time.time() - t0), flush=True)
+        print("%s_linear n=%d done in %.0fs" % (shape_name, n, time.time() - t0), flush=True)
     return out
+
+
+def llama7b_w4_linear():
+    return llama7b_w8_linear("llama7b_w4")
 
 
 def llama7b_runs():
@@ -163,7 +168,7 @@ def llama70b_layer():
     return out
 
 
-CASES = {"llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
+CASES = {"llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_w4_linear": llama7b_w4_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
          "llama70b_layer": llama70b_layer}
 
 if __name__ == "__main__":

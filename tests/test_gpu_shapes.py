@@ -25,6 +25,11 @@ ODD_SHAPES = {
                                      weight_scale_exp2=-11),
     "odd_w8_gqa8": synth.ModelShape("odd_w8_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="bf16", weight_format="fp8",
                                     weight_scale_exp2=-9),
+    # 4-bit weight matrices (128-column tiles, tile counts padded to a multiple of eight)
+    "odd_w4_hd128": synth.ModelShape("odd_w4_hd128", 1, 384, 3, 3, 128, 1040, 2000, dtype="bf16", weight_format="fp4",
+                                     weight_scale_exp2=-6),
+    "odd_w4_gqa8": synth.ModelShape("odd_w4_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="bf16", weight_format="fp4",
+                                    weight_scale_exp2=-5),
 }
 
 

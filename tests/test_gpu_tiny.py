@@ -26,10 +26,10 @@ def check_logits(gpu, ref, dtype):
 
 
 def test_device_fill_equals_host_fill():
-    for dtype in ("f32", "bf16", "fp8"):
-        n = 1_000_003
+    for dtype in ("f32", "bf16", "fp8", "fp4"):
+        n = 1_000_003 if dtype != "fp4" else 1_000_004        # two 4-bit values per byte
         sid = synth.stream_id(synth.T_WD, 7)
-        sigma = 0.02 * (2048 if dtype == "fp8" else 1)       # 8-bit weights are stored scaled up
+        sigma = 0.02 * {"fp8": 2048, "fp4": 64}.get(dtype, 1)  # quantised weights are stored scaled up
         host = synth.normal_host(n, 3, sid, sigma, dtype)
         dev = gpu_loader.device_normal(n, 3, sid, sigma, dtype).cpu().numpy()
         if dtype == "bf16":
@@ -62,7 +62,8 @@ def _true_prefill(sh, seed, gain_sigma, n_prefill, n_cells):
 
 
 @pytest.mark.parametrize("shape_name,gain_sigma", [("tiny", 0.0), ("tiny", 0.1), ("tiny_bf16", 0.1), ("tiny_gqa", 0.1),
-                                                   ("tiny_w8", 0.1), ("tiny_gqa_w8", 0.1)])
+                                                   ("tiny_w8", 0.1), ("tiny_gqa_w8", 0.1), ("tiny_w4", 0.1),
+                                                   ("tiny_gqa_w4", 0.1)])
 def test_planted_draft_verify_and_rollback(shape_name, gain_sigma):
     """Tiny configuration: 64 prefilled positions, 4 draft tokens planted to agree with the
     oracle's argmax for the first 2; accepted count, bonus token and kv_len must match."""

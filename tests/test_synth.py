@@ -138,3 +138,40 @@ def test_fp8_weight_stream_is_the_rounded_float_stream():
     assert np.array_equal(q, synth.f32_to_e4m3_host(f * np.float32(2048)))
     w = from_synth.dequantise_fp8(q, -11)
     assert np.max(np.abs(w - f) / np.maximum(np.abs(f), 2.0 ** -17)) <= 2.0 ** -4     # half a step of three mantissa bits
+
+
+# ---- 4-bit weights: FP4 E2M1 ---------------------------------------------------------------------------
+
+def test_e2m1_codes_rounding_and_packing():
+    from oracle import from_synth
+    t = from_synth.E2M1
+    assert t[:8].tolist() == [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0] and np.array_equal(t[8:], -t[:8])
+    # value = (-1)^s * 2^(e-1) * (1 + m/2) for e > 0, m/2 for e = 0: the format's definition, code by code
+    for c in range(16):
+        s_, e, m = c >> 3, (c >> 1) & 3, c & 1
+        v = (m / 2.0 if e == 0 else 2.0 ** (e - 1) * (1 + m / 2.0)) * (-1.0 if s_ else 1.0)
+        assert t[c] == v and np.signbit(t[c]) == bool(s_)
+    # nearest code, ties to the code with mantissa bit 0 (even code), saturation at 6: by brute force
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.normal(size=20000) * s for s in (0.3, 1.3, 4.0)] +
+                       [np.array([0.0, -0.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 5.0001, 6.0, 7.0, 1e9, -0.25, -5.0, -1e9])]).astype(np.float32)
+    got = synth.f32_to_e2m1_host(x)
+    ax = np.abs(x.astype(np.float64))
+    d = np.abs(ax[:, None] - t[None, :8])
+    want = np.empty(len(x), dtype=np.int64)
+    for i in range(len(x)):
+        c = np.flatnonzero(d[i] == d[i].min())
+        want[i] = c[0] if len(c) == 1 else (c[0] if c[0] % 2 == 0 else c[1])
+    want |= np.where(np.signbit(x), 8, 0)
+    assert np.array_equal(got.astype(np.int64), want)
+    # the ties written out
+    ties = synth.f32_to_e2m1_host(np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 100.0, -0.75], dtype=np.float32))
+    assert ties.tolist() == [0, 2, 2, 4, 4, 6, 6, 7, 10]
+    # packing: element 2p in the low nibble, 2p+1 in the high nibble; the stream is the rounded float stream
+    sid = synth.stream_id(synth.T_WU, 1)
+    f = synth.normal_host(4000, 9, sid, 0.02, "f32")
+    q = synth.normal_host(4000, 9, sid, 0.02 * 64, "fp4")
+    codes = synth.f32_to_e2m1_host(f * np.float32(64))
+    assert q.shape == (2000,) and np.array_equal(q & 0xF, codes[0::2]) and np.array_equal(q >> 4, codes[1::2])
+    w = from_synth.dequantise_fp4(q.reshape(40, 50), -6)
+    assert w.shape == (40, 100) and np.array_equal(w.reshape(-1).astype(np.float64), t[codes] / 64)
