@@ -408,37 +408,44 @@ def main():
                 "draft_tokens_issued": st["tokens_speculated"]}
         kv2.free()
 
-    # Quantised weight streaming: the same workload on the same shape with 8-bit (FP8 E4M3) weight
-    # matrices, one byte per weight, decoded in the projection kernels; bf16 activations and cache.
+    # Quantised weight streaming: the same workload on the same shape with 8-bit (FP8 E4M3) and 4-bit
+    # (FP4 E2M1) weight matrices, decoded in the projection kernels; bf16 activations and cache.
     w8 = None
-    if not args.no_w8 and shape.weight_format == "native" and shape.name + "_w8" in synth.SHAPES:
-        sh8 = synth.SHAPES[shape.name + "_w8"]
-        m8 = gpu_loader.load_model(sh8, args.seed)
-        kv8 = pi.KVCache(m8, n_cells)
-        gpu_loader.prefill_kv_synthetic(kv8, sh8, args.seed, T)
-        lb8, lm8 = m8.weight_bytes()
-        w8 = {"weights": "fp8-e4m3 x 2^%d" % sh8.weight_scale_exp2, "per_batch": {}}
-        for n in batches:
-            run8 = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(sh8, args.seed, n, synth.T_DRAFT, salt=n))
-            lg8 = torch.empty((n, sh8.vocab), device="cuda")
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-            for k in range(args.warmup + args.steps):
-                e = evs[k - args.warmup] if k >= args.warmup else None
-                if e:
-                    e[0].record()
-                pi.stage_forward(m8, kv8, run8, 0, sh8.n_layers, logits_out=lg8, run_status=status)
-                if e:
-                    e[1].record()
-                pi.kv_rollback(kv8, run8.slots, n)
-            torch.cuda.synchronize()
-            assert status.cpu().tolist() == [0, sh8.n_layers]
-            f8 = sum(e0.elapsed_time(e1) for e0, e1 in evs) / args.steps
-            ab8 = algorithmic_bytes(sh8, lb8, lm8, T, n)
-            w8["per_batch"][str(n)] = {"forward_ms": f8, "algorithmic_GB": ab8 / 1e9, "achieved_GBps": ab8 / 1e9 / (f8 * 1e-3),
-                                       "frac_of_peak": ab8 / 1e9 / (f8 * 1e-3) / HBM_PEAK_GBS,
-                                       "speedup_vs_%s_weights" % shape.dtype: per_batch[str(n)]["forward_ms"] / f8}
-        kv8.free()
-        m8.free()
+    if not args.no_w8 and shape.weight_format == "native":
+        w8 = {}
+        for suffix in ("_w8", "_w4"):
+            if shape.name + suffix not in synth.SHAPES:
+                continue
+            sh8 = synth.SHAPES[shape.name + suffix]
+            m8 = gpu_loader.load_model(sh8, args.seed)
+            kv8 = pi.KVCache(m8, n_cells)
+            gpu_loader.prefill_kv_synthetic(kv8, sh8, args.seed, T)
+            lb8, lm8 = m8.weight_bytes()
+            leg = {"weights": "%s x 2^%d" % ({"fp8": "fp8-e4m3", "fp4": "fp4-e2m1"}[sh8.weight_format], sh8.weight_scale_exp2),
+                   "per_batch": {}}
+            for n in batches:
+                run8 = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(sh8, args.seed, n, synth.T_DRAFT, salt=n))
+                lg8 = torch.empty((n, sh8.vocab), device="cuda")
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+                for k in range(args.warmup + args.steps):
+                    e = evs[k - args.warmup] if k >= args.warmup else None
+                    if e:
+                        e[0].record()
+                    pi.stage_forward(m8, kv8, run8, 0, sh8.n_layers, logits_out=lg8, run_status=status)
+                    if e:
+                        e[1].record()
+                    pi.kv_rollback(kv8, run8.slots, n)
+                torch.cuda.synchronize()
+                assert status.cpu().tolist() == [0, sh8.n_layers]
+                f8 = sum(e0.elapsed_time(e1) for e0, e1 in evs) / args.steps
+                ab8 = algorithmic_bytes(sh8, lb8, lm8, T, n)
+                leg["per_batch"][str(n)] = {"forward_ms": f8, "verified_tokens_per_s_forward_only": n / (f8 * 1e-3),
+                                            "algorithmic_GB": ab8 / 1e9, "achieved_GBps": ab8 / 1e9 / (f8 * 1e-3),
+                                            "frac_of_peak": ab8 / 1e9 / (f8 * 1e-3) / HBM_PEAK_GBS,
+                                            "speedup_vs_%s_weights" % shape.dtype: per_batch[str(n)]["forward_ms"] / f8}
+            w8[sh8.weight_format] = leg
+            kv8.free()
+            m8.free()
 
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",

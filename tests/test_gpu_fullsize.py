@@ -70,14 +70,19 @@ def test_llama7b_linear_runs_match_oracle(llama7b):
     assert len(kv) == T
 
 
-def test_llama7b_with_8bit_weights_matches_oracle():
-    """The same shape with FP8 E4M3 weight matrices streamed at one byte per weight: sampled
-    logits against the oracle evaluated on the dequantised weights."""
-    sh = synth.SHAPES["llama7b_w8"]
-    g = _load("llama7b_w8_linear")
+@pytest.mark.parametrize("shape_name", ["llama7b_w8", "llama7b_w4"])
+def test_llama7b_with_quantised_weights_matches_oracle(shape_name):
+    """The same shape with FP8 E4M3 (one byte per weight) or FP4 E2M1 (half a byte) weight
+    matrices: sampled logits against the oracle evaluated on the dequantised weights."""
+    sh = synth.SHAPES[shape_name]
+    g = _load(shape_name + "_linear")
     m = gpu_loader.load_model(sh, g["seed"])
     layer_bytes, lm_bytes = m.weight_bytes()
-    assert layer_bytes == sh.layer_params and lm_bytes == sh.vocab * sh.d_model      # one byte per weight
+    if sh.weight_format == "fp8":
+        assert layer_bytes == sh.layer_params and lm_bytes == sh.vocab * sh.d_model  # one byte per weight
+    else:   # half a byte per weight; the down projection's 86 tiles of 128 columns are padded to 88
+        pad = sh.d_model * (88 * 128 - sh.ffn) // 2
+        assert layer_bytes == sh.layer_params // 2 + pad and lm_bytes == sh.vocab * sh.d_model // 2
     T = g["prefix"]
     kv = pi.KVCache(m, T + 64)
     gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
@@ -92,7 +97,7 @@ def test_llama7b_with_8bit_weights_matches_oracle():
         torch.cuda.synchronize()
         assert status.cpu().tolist() == [pi.PI_OK, sh.n_layers]
         worst = _check_rows(logits.cpu().numpy(), rec["rows"], cols)
-        print("8-bit weights n=%d worst sampled logit error / row max: %.2e" % (n, worst))
+        print("%s n=%d worst sampled logit error / row max: %.2e" % (shape_name, n, worst))
         pi.kv_rollback(kv, run.slots, n)
     m.free()
 
