@@ -272,7 +272,9 @@ int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t
  * identifiers is host state.  A pi_kvmeta is not tied to one pi_kv: it describes cells by
  * index.  Device arguments: positions[n] int32, tok_seq[n] uint32 (the sequences token i
  * belongs to: one bit for a linear run, one bit per branch through the node for a tree),
- * slots/masks/status words as stated.  n is 1 .. PI_MAX_BATCH.
+ * slots/masks/status words as stated.  n is 1 .. PI_MAX_BATCH.  The calls on one table share
+ * its device state (and the mask builder its counters): issue them on one stream, or order
+ * them with events; the host-side queue is not thread-safe.
  *
  * Token i sees cell c iff seq[c] & tok_seq[i] != 0 and pos[c] <= positions[i]. */
 #define PI_MAX_SEQ 32

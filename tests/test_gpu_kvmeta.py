@@ -147,6 +147,38 @@ def test_refusals_reported_on_the_device():
     p.check("refused compaction")
 
 
+def test_degenerate_tables_and_windows():
+    """No prefix at all, the largest batch, a table with a single partition, a window of one
+    cell at the very end of the cache, compaction with nothing to move."""
+    p = Pair(80, 2)                                   # sequence 0 and one partition
+    s = p.acquire()
+    assert s == 1 and p.acquire() is None
+    st, _ = p.place(list(range(16)), [[s]] * 16, 0)   # empty prefix: positions 0..15 in cells 0..15
+    assert st == 0
+    mask, bad = p.build_mask(list(range(16)), [[s]] * 16, 0, 0)
+    assert bad == 0 and mask.cpu().tolist() == [(2 << i) - 1 for i in range(16)]
+    assert p.compact(0)[0] == pi.PI_E_BUSY
+    p.accept(list(range(16)), [[s]] * 16, list(range(16)))
+    p.release(s)
+    assert p.compact(0) == (0, 16)
+    assert p.compact(16) == (0, 16)                   # nothing in the window: nothing moves
+    p.check("empty prefix")
+    s = p.acquire()
+    st, _ = p.place([16], [[s]], 79)                  # the window is the cache's last cell
+    assert st == 0
+    st, _ = p.place([17], [[s]], 79)
+    assert st == pi.PI_E_FULL
+    mask, bad = p.build_mask([16], [[s]], 16, 79)
+    assert bad == 0 and mask.cpu().tolist() == [1]
+    p.check("last cell")
+    # calls that edit nothing are accepted and change nothing
+    p.g.fill(0, 0, 0, 3)
+    p.g.seq_cp(0, 0)
+    p.g.seq_rm(0)
+    p.g.seq_cp(1, 1, 5, 5)
+    p.check("no-ops")
+
+
 # ---- random edit sequences --------------------------------------------------------------------------
 
 @pytest.mark.parametrize("n_cells,n_seq,seed", [(70, 4, 0), (200, 32, 1), (1152, 8, 2), (2112, 32, 3), (40000, 16, 4)])

@@ -150,3 +150,20 @@ def test_random_speculation_streams(seed, alpha, vocab):
             b.g.on_speculation_stopped(w)
         b.check()
     assert sum(b.want_words) > 0                              # the stream did cancel speculative runs
+
+
+def test_largest_batch_empty_sampling_phase_and_short_report_buffer():
+    b = Both(0.5, 0.0, 0.0)
+    b.accept([1, 2, 3], completed=False)
+    parent = synth.random_tree(5, 1, 16, max_children=3, max_depth=6)
+    depth = np.zeros(16, dtype=np.int64)
+    for i in range(16):
+        depth[i] = 0 if parent[i] < 0 else depth[parent[i]] + 1
+    ids = [b.begin(True, [], 0, list(range(100, 116)), parent.tolist(), (3 + depth).tolist()) for _ in range(5)]
+    assert b.accept([], completed=True) == []                       # nothing sampled: nothing to find
+    # one wrong token takes all five runs; a report buffer of two still cancels all of them
+    want = b.o.accept_tokens([7], True)
+    got = b.g.accept_tokens([7], True, cap=2)
+    assert [w[0] for w in want] == ids and got == want[:2]
+    assert list(b.words)[:5] == [1] * 5
+    b.check()
