@@ -84,6 +84,7 @@ def main():
     ap.add_argument("--no-multi-run", action="store_true", help="skip the several-runs-per-pass comparison")
     ap.add_argument("--no-kv-metadata", action="store_true", help="skip the cell-metadata bookkeeping timing")
     ap.add_argument("--no-continuous", action="store_true", help="skip the continuous-speculation generation loop")
+    ap.add_argument("--no-c4", action="store_true", help="skip the eight-runs-half-cancelled workload")
     ap.add_argument("--no-w8", action="store_true", help="skip the same workload with 8-bit weight matrices")
     ap.add_argument("--slice-layers", type=int, default=0,
                     help="also time a pipeline stage's share: the first this-many layers as one stage call")
@@ -274,6 +275,62 @@ def main():
                  "one_run_per_pass": {"passes": 8, "ms": t8 * 1e3, "verified_tokens_per_s": 32 / t8},
                  "four_runs_per_pass": {"passes": 2, "ms": t2 * 1e3, "verified_tokens_per_s": 32 / t2}}
 
+    # Eight runs in flight, half of them cancelled (Section "Early Inference Cancellation"): eight
+    # 4-token tree runs over a 1024-cell prefix, one forward each; a seeded half of them has its
+    # cancel word raised before a seeded layer (the stack is issued as two stage calls with the
+    # store of the word in between, in stream order).  Timed with and without the cancellations.
+    c4 = None
+    if not args.no_c4:
+        T4 = 1024
+        kv4 = pi.KVCache(model, T4 + 64)
+        gpu_loader.prefill_kv_synthetic(kv4, shape, args.seed, T4)
+        stops = synth.cancel_schedule(args.seed, 8, shape.n_layers)
+        runs4 = []
+        for r in range(8):
+            parent = synth.random_tree(args.seed, r, 4)
+            runs4.append(gpu_loader.make_run(synth.tree_run(parent, T4, T4, offset=4 * r),
+                                             synth.sibling_distinct_tokens(shape, args.seed, r, parent)))
+        lg4 = torch.empty((4, shape.vocab), device="cuda")
+        hid4 = torch.empty((4, shape.d_model), device="cuda")
+        flag4 = torch.zeros(1, dtype=torch.int32, device="cuda")
+        st4 = torch.zeros((8, 2), dtype=torch.int32, device="cuda")
+
+        def eight_runs(cancel):
+            for r, run in enumerate(runs4):
+                stop = stops[r] if cancel else -1
+                flag4.zero_()
+                if stop > 0:
+                    pi.stage_forward(model, kv4, run, 0, stop, hidden_out=hid4, cancel_flag=flag4, run_status=st4[r])
+                if stop >= 0:
+                    flag4.fill_(1)
+                pi.stage_forward(model, kv4, run, max(stop, 0), shape.n_layers, hidden_in=hid4 if stop > 0 else None,
+                                 logits_out=lg4, cancel_flag=flag4, run_status=st4[r])
+                pi.kv_rollback(kv4, run.slots, 4)
+
+        def timed4(cancel, reps):
+            eight_runs(cancel)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                eight_runs(cancel)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+
+        reps = max(2, args.steps // 10)
+        t_all = timed4(False, reps)
+        t_cut = timed4(True, reps)
+        done = st4.cpu().tolist()
+        assert [d[0] for d in done] == [1 if s >= 0 else 0 for s in stops]
+        assert [d[1] for d in done] == [s if s >= 0 else shape.n_layers for s in stops]
+        layers_run = sum(d[1] for d in done)
+        c4 = {"runs": 8, "tokens_per_run": 4, "prefix": T4, "cancel_before_layer": stops,
+              "ms_without_cancellation": t_all * 1e3, "ms_with_cancellation": t_cut * 1e3,
+              "layers_evaluated": layers_run, "layers_total": 8 * shape.n_layers,
+              "weight_GB_streamed": (layers_run * layer_bytes + sum(1 for s in stops if s < 0) * lm_bytes) / 1e9,
+              "weight_GB_without_cancellation": 8 * (shape.n_layers * layer_bytes + lm_bytes) / 1e9,
+              "time_saved_fraction": 1.0 - t_cut / t_all, "layers_saved_fraction": 1.0 - layers_run / (8.0 * shape.n_layers)}
+        kv4.free()
+
     # Cell metadata and sequence partitions: the bookkeeping of one round of eight 4-token tree
     # runs -- per run: partitions from the queue, cells from the window, window words from the
     # table; then the best run accepted, every partition given back, and the accepted entries
@@ -462,6 +519,7 @@ def main():
         "per_batch": per_batch,
         "cancellation": cancel,
         "multi_run": multi,
+        "eight_runs_half_cancelled": c4,
         "kv_metadata": kvmeta,
         "continuous_speculation": contin,
         "quantised_weights": w8,
