@@ -440,30 +440,33 @@ def main():
         G, t_naive = naive()
         contin = {"tokens": n_gen, "depth": 3, "micro_batch": 4, "cutoff": {"base": 0.0, "recovery": 0.05, "decay": 0.05},
                   "plain_decoding": {"tokens_per_s": n_gen / t_naive, "ms_per_token": t_naive * 1e3 / n_gen},
-                  "by_alpha": {}}
-        for alpha in (0.52, 0.66, 0.79, 1.0):
-            gpu_loader.prefill_kv_synthetic(kv2, shape, args.seed, T)
-            u = synth.uniform_int_host(2 * (n_gen + 64), args.seed, synth.stream_id(synth.T_MISC, int(alpha * 100)), 1 << 20)
+                  "note": "by_alpha: every run is a pass over the weights (3 passes in flight); "
+                          "by_alpha_four_runs_per_pass: up to four consecutive runs share a pass (2 passes in flight)"}
+        for rpp, key in ((1, "by_alpha"), (4, "by_alpha_four_runs_per_pass")):
+            contin[key] = {}
+            for alpha in (0.52, 0.66, 0.79, 1.0):
+                gpu_loader.prefill_kv_synthetic(kv2, shape, args.seed, T)
+                u = synth.uniform_int_host(2 * (n_gen + 64), args.seed, synth.stream_id(synth.T_MISC, int(alpha * 100)), 1 << 20)
 
-            def draft(pos, u=u, alpha=alpha):
-                i = pos - (T + 1)
-                g = G[i] if i < len(G) else 0
-                right = u[2 * i] < alpha * (1 << 20)
-                return (g if right else (g + 1 + int(u[2 * i]) % 7) % shape.vocab), float(u[2 * i + 1]) / (1 << 20)
+                def draft(pos, u=u, alpha=alpha):
+                    i = pos - (T + 1)
+                    g = G[i] if i < len(G) else 0
+                    right = u[2 * i] < alpha * (1 << 20)
+                    return (g if right else (g + 1 + int(u[2 * i]) % 7) % shape.vocab), float(u[2 * i + 1]) / (1 << 20)
 
-            cs = ContinuousSpeculation(model, kv2, T, first, draft, depth=3, micro_batch=4, base_cutoff=0.0,
-                                       recovery=0.05, decay=0.05)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            got = cs.generate(n_gen)
-            dt = time.perf_counter() - t0
-            st = dict(cs.stats)
-            cs.close()
-            contin["by_alpha"]["%.2f" % alpha] = {
-                "tokens_per_s": n_gen / dt, "speedup_vs_plain": t_naive / dt, "same_tokens_as_plain": got == G,
-                "runs": st["runs"], "speculative_runs": st["speculative"], "cancelled_runs": st["cancelled"],
-                "layers_skipped": st["layers_skipped"], "draft_tokens_accepted": st["tokens_accepted_from_drafts"],
-                "draft_tokens_issued": st["tokens_speculated"]}
+                cs = ContinuousSpeculation(model, kv2, T, first, draft, depth=3 if rpp == 1 else 2, micro_batch=4,
+                                           base_cutoff=0.0, recovery=0.05, decay=0.05, runs_per_pass=rpp)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                got = cs.generate(n_gen)
+                dt = time.perf_counter() - t0
+                st = dict(cs.stats)
+                cs.close()
+                contin[key]["%.2f" % alpha] = {
+                    "tokens_per_s": n_gen / dt, "speedup_vs_plain": t_naive / dt, "same_tokens_as_plain": got == G,
+                    "passes": st["passes"], "runs": st["runs"], "speculative_runs": st["speculative"],
+                    "cancelled_runs": st["cancelled"], "layers_skipped": st["layers_skipped"],
+                    "draft_tokens_accepted": st["tokens_accepted_from_drafts"], "draft_tokens_issued": st["tokens_speculated"]}
         kv2.free()
 
     # Quantised weight streaming: the same workload on the same shape with 8-bit (FP8 E4M3) and 4-bit

@@ -4,10 +4,12 @@ What the paper's head node does (Sections "Asynchronous Speculation", "Continuou
 "Pipelined KV Cache Multibuffering", "Early Inference Cancellation"), with the one GPU's
 stream in the role of the pipeline: verification runs are queued back to back and executed in
 order; while the oldest has not finished the head node keeps issuing further micro-batches of
-draft tokens, each in a sequence partition of its own and each building on the entries of the
-one before it; when a result arrives it is sampled (greedy), the accepted entries join every
-sequence, and every queued run that the new tokens contradict is cancelled through its cancel
-word, which the stage kernel polls at every layer boundary.
+draft tokens, each a run with a sequence partition, a record and a cancel word of its own and
+each building on the entries of the one before it; when a result arrives it is sampled
+(greedy), the accepted entries join every sequence, and every queued run that the new tokens
+contradict is cancelled through its cancel word, which the stage kernel polls at every layer
+boundary.  On one GPU several consecutive runs can also share one pass over the weights
+(`runs_per_pass` > 1, pi_stage_forward_multi): they stay separate runs in every other respect.
 
 This module only sequences calls: every decision about runs comes from the native
 bookkeeping (pi_sched_*), every array is produced by the library's kernels, and nothing is
@@ -21,48 +23,61 @@ import torch
 
 from . import binding as pi
 
+_MAX_RUNS = 8       # runs per weight pass the buffers are laid out for
+_GS, _RES, _PATH, _OUT = 8, 24, 40, 56   # offsets in a pass's result words: group status, results, paths; size
 
-class _Slot:
-    """Device and pinned buffers of one run in flight (reused round robin)."""
 
-    def __init__(self, vocab: int, mb: int):
-        dev = "cuda"
-        self.tokens = torch.zeros(mb, dtype=torch.int32, device=dev)
-        self.positions = torch.zeros(mb, dtype=torch.int32, device=dev)
-        self.tok_seq = torch.zeros(mb, dtype=torch.int32, device=dev)
-        self.slots = torch.zeros(mb, dtype=torch.int32, device=dev)
-        self.mask = torch.zeros(mb, dtype=torch.int64, device=dev)
-        self.logits = torch.zeros((mb, vocab), dtype=torch.float32, device=dev)
-        # [0:2] run_status, [2:4] verification result, [4] place status, [5] inexpressible pairs, [8:8+mb] path
-        self.out = torch.zeros(8 + mb, dtype=torch.int32, device=dev)
-        self.out_host = torch.zeros(8 + mb, dtype=torch.int32, pin_memory=True)
-        self.cancel = torch.zeros(1, dtype=torch.int32, pin_memory=True)
+class _Pass:
+    """Device and pinned buffers of one weight pass in flight (reused round robin)."""
+
+    def __init__(self, vocab: int):
+        dev, nb = "cuda", pi.PI_MAX_BATCH
+        self.tokens = torch.zeros(nb, dtype=torch.int32, device=dev)
+        self.positions = torch.zeros(nb, dtype=torch.int32, device=dev)
+        self.cell_seq = torch.zeros(nb, dtype=torch.int32, device=dev)   # sequences each new entry belongs to
+        self.sees_seq = torch.zeros(nb, dtype=torch.int32, device=dev)   # sequences each token reads
+        self.slots = torch.zeros(nb, dtype=torch.int32, device=dev)
+        self.mask = torch.zeros(nb, dtype=torch.int64, device=dev)
+        self.logits = torch.zeros((nb, vocab), dtype=torch.float32, device=dev)
+        # [0:2] status of the pass, [2] place status, [3] inexpressible pairs, [_GS + 2k ..] status of run k,
+        # [_RES + 2k ..] verification result of run k, [_PATH + first token of run k ..] its accepted path
+        self.out = torch.zeros(_OUT, dtype=torch.int32, device=dev)
+        self.out_host = torch.zeros(_OUT, dtype=torch.int32, pin_memory=True)
+        self.cancel = torch.zeros(_MAX_RUNS, dtype=torch.int32, pin_memory=True)
         self.cancel_dev = pi.mapped_device_pointer(self.cancel)
         self.event = torch.cuda.Event()
-        self.h_tokens = torch.zeros(mb, dtype=torch.int32, pin_memory=True)
-        self.h_positions = torch.zeros(mb, dtype=torch.int32, pin_memory=True)
-        self.h_seq = torch.zeros(mb, dtype=torch.int32, pin_memory=True)
-        self.canonical_only = torch.ones(mb, dtype=torch.int32, device=dev)      # sequence 0 alone
+        self.h_in = torch.zeros((4, nb), dtype=torch.int32, pin_memory=True)  # tokens, positions, cell_seq, sees_seq
+        self.runs = []
 
 
 class _Run:
-    def __init__(self, rid, slot, speculative, tokens, start, seq):
-        self.id, self.slot, self.speculative = rid, slot, speculative
-        self.tokens, self.start, self.seq = tokens, start, seq
+    def __init__(self, speculative, tokens, start, seq):
+        self.speculative, self.tokens, self.start, self.seq = speculative, [int(t) for t in tokens], start, seq
         self.n = len(tokens)
+        self.id = -1
         self.cancelled = False
+        self.pass_ = None
+        self.k = 0            # index in its pass
+        self.first = 0        # index of its first token in the pass
+
+
+def _i32(v):
+    return int(np.uint32(v).astype(np.int32))
 
 
 class ContinuousSpeculation:
     """model/kv: the target and its cache, holding `prefix_len` canonical cells (positions
     0 .. prefix_len-1); first_token: the accepted token at position prefix_len whose entry
-    is not in the cache yet; draft(pos) -> (token, confidence) for pos > prefix_len."""
+    is not in the cache yet; draft(pos) -> (token, confidence) for pos > prefix_len.
+    depth: weight passes in flight; micro_batch: draft tokens per run (1..4); runs_per_pass:
+    consecutive runs sharing one pass over the weights (1 = every run is a pass of its own)."""
 
     def __init__(self, model, kv, prefix_len: int, first_token: int, draft, depth: int = 3, micro_batch: int = 4,
-                 base_cutoff: float = 0.3, recovery: float = 0.05, decay: float = 0.05, n_seq: int = 32):
-        assert 1 <= micro_batch <= 4 and depth >= 1
+                 base_cutoff: float = 0.3, recovery: float = 0.05, decay: float = 0.05, n_seq: int = 32,
+                 runs_per_pass: int = 1):
+        assert 1 <= micro_batch <= 4 and depth >= 1 and 1 <= runs_per_pass <= _MAX_RUNS
         self.model, self.kv, self.draft = model, kv, draft
-        self.depth, self.mb = depth, micro_batch
+        self.depth, self.mb, self.rpp = depth, micro_batch, runs_per_pass
         self.L = model.shape.n_layers
         self.vocab = model.shape.vocab
         self.meta = pi.KVMeta(kv.n_cells, n_seq)
@@ -73,119 +88,177 @@ class ContinuousSpeculation:
         self.accepted = [0] * prefix_len + [int(first_token)]    # prompt tokens are not known here: placeholders
         self.sched.accept_tokens(self.accepted, run_completed=False)
         self.first_generated = prefix_len + 1
-        self.free_slots = [_Slot(self.vocab, micro_batch) for _ in range(depth + 3)]
-        self.fifo = []                                # runs in flight, oldest first
+        self.free = [_Pass(self.vocab) for _ in range(depth + 2)]
+        self.fifo = []                                # passes in flight, oldest first
         self.tail = None                              # last run issued, while the chain it ends is intact
         self.issued_cells = 0                         # window cells handed out since the last compaction
         self.compact_out = torch.zeros(2, dtype=torch.int32, device="cuda")
-        self.stats = {"runs": 0, "non_speculative": 0, "speculative": 0, "discarded": 0, "cancelled": 0, "layers_skipped": 0,
-                      "tokens_speculated": 0, "tokens_accepted_from_drafts": 0, "compactions": 0, "cutoff_stops": 0}
+        self._cutoff_stop = False
+        self.stats = {"passes": 0, "runs": 0, "non_speculative": 0, "speculative": 0, "discarded": 0, "cancelled": 0,
+                      "layers_skipped": 0, "tokens_speculated": 0, "tokens_accepted_from_drafts": 0, "compactions": 0,
+                      "cutoff_stops": 0}
 
     # ---- issuing ---------------------------------------------------------------------------
-    def _issue(self, tokens, start, speculative):
-        n = len(tokens)
-        slot = self.free_slots.pop()
-        prev = self.tail
-        seq = self.all_seq
-        if speculative:
-            sid = self.meta.acquire()
-            assert sid is not None, "out of sequence partitions"
-            seq = 1 << sid
-            if prev is not None and prev.speculative:
-                self.meta.seq_cp(prev.seq.bit_length() - 1, seq)      # early sharing: build on the run before
-        slot.h_tokens[:n] = torch.as_tensor(np.asarray(tokens, dtype=np.int32))
-        slot.h_positions[:n] = torch.arange(start, start + n, dtype=torch.int32)
-        slot.h_seq[:n] = int(np.uint32(seq).astype(np.int32))
-        slot.tokens.copy_(slot.h_tokens, non_blocking=True)
-        slot.positions.copy_(slot.h_positions, non_blocking=True)
-        slot.tok_seq.copy_(slot.h_seq, non_blocking=True)
-        slot.cancel[0] = 0
-        self.meta.place(n, slot.positions, slot.tok_seq, self.dense, slot.slots, slot.out[4:5])
-        # a non-speculative run's entry belongs to every sequence at once (it is known to be right),
-        # but the run itself reads the canonical sequence only: never another run's speculation
-        sees = slot.tok_seq if speculative else slot.canonical_only
-        self.meta.build_mask(n, slot.positions, sees, self.dense, self.dense, slot.mask, slot.out[5:6])
-        run_desc = pi.Run.__new__(pi.Run)
-        run_desc.n, run_desc.tokens, run_desc.positions = n, slot.tokens, slot.positions
-        run_desc.slots, run_desc.mask, run_desc.parent = slot.slots, slot.mask, None
-        run_desc.prefix_len, run_desc.window_base = self.dense, self.dense
-        # a non-speculative run is never cancelled: its entries are what later runs build on
-        pi.stage_forward(self.model, self.kv, run_desc, 0, self.L, logits_out=slot.logits, run_status=slot.out[0:2],
-                         cancel_flag_ptr=slot.cancel_dev if speculative else None)
-        if prev is None:
-            pi.verify_greedy_chained(slot.tokens, None, n, slot.logits, self.vocab, int(tokens[0]), None, 0,
-                                     slot.out[0:2], slot.out[8:8 + n], slot.out[2:4])
-        else:
-            pi.verify_greedy_chained(slot.tokens, None, n, slot.logits, self.vocab, 0, prev.slot.out[2:4], prev.n,
-                                     slot.out[0:2], slot.out[8:8 + n], slot.out[2:4])
-        if speculative:
-            self.meta.accept(n, slot.positions, slot.tok_seq, slot.out[8:8 + n], slot.out[2:4])
-        slot.out_host.copy_(slot.out, non_blocking=True)
-        slot.event.record()
-        assumed = self.accepted_frontier(start)
-        rid = self.sched.begin_run(speculative, assumed, start - len(assumed), tokens, list(range(-1, n - 1)),
-                                   list(range(start, start + n)), cancel_word_ptr=slot.cancel.data_ptr())
-        run = _Run(rid, slot, speculative, [int(t) for t in tokens], start, seq)
-        self.fifo.append(run)
-        self.tail = run
-        self.issued_cells += n
-        self.stats["runs"] += 1
-        self.stats["speculative" if speculative else "non_speculative"] += 1
-        if speculative:
-            self.stats["tokens_speculated"] += n
-        return run
+    def _runs_in_flight(self):
+        return [r for p in self.fifo for r in p.runs]
 
-    def accepted_frontier(self, start):
-        """Speculated tokens between the accepted end and `start` (what a run at `start`
-        builds on): the tokens of the intact chain of runs in flight."""
+    def _assumed(self, start, extra):
+        """Speculated tokens between the accepted end and `start` (what a run at `start` builds
+        on): the tokens of the intact chain of runs in flight and of this pass so far."""
         A = len(self.accepted)
         out = []
-        for r in self.fifo:
+        for r in self._runs_in_flight() + extra:
             if not r.cancelled:
                 for k, t in enumerate(r.tokens):
                     if A <= r.start + k < start:
                         out.append(t)
         return out
 
-    def _room(self, n):
-        return len(self.fifo) < self.depth and self.issued_cells + n <= pi.PI_WINDOW and self.free_slots
+    def _plan_pass(self):
+        """The runs of the next weight pass: the non-speculative run if nothing in flight covers
+        the accepted end, then micro-batches of draft tokens while their confidence clears the
+        cutoff (which rises with each one)."""
+        runs, n_tok = [], 0
+        self._cutoff_stop = False
+        last = self.tail
+        if last is None:
+            runs.append(_Run(False, [self.accepted[-1]], len(self.accepted) - 1, self.all_seq))
+            n_tok, last = 1, runs[0]
+        while len(runs) < self.rpp and n_tok + 1 <= pi.PI_MAX_BATCH and self.issued_cells + n_tok + 1 <= pi.PI_WINDOW:
+            start = last.start + last.n
+            batch = []
+            room = min(self.mb, pi.PI_MAX_BATCH - n_tok, pi.PI_WINDOW - self.issued_cells - n_tok)
+            while len(batch) < room:
+                tok, conf = self.draft(start + len(batch))
+                if not self.sched.want_speculation(conf):
+                    break
+                batch.append(int(tok))
+            if not batch:
+                self._cutoff_stop = room > 0
+                self.stats["cutoff_stops"] += 1 if room > 0 else 0
+                break
+            self.sched.on_speculated()
+            last = _Run(True, batch, start, 0)
+            runs.append(last)
+            n_tok += len(batch)
+        return runs
+
+    def _issue(self, runs):
+        if self.dense + pi.PI_WINDOW > self.kv.n_cells:
+            raise RuntimeError("KV cache too small: the window [%d, %d) does not fit %d cells"
+                               % (self.dense, self.dense + pi.PI_WINDOW, self.kv.n_cells))
+        P = self.free.pop()
+        P.out.zero_()     # a run whose status word already says "cancelled" stays cancelled: start every pass clean
+        n_tot = sum(r.n for r in runs)
+        first = 0
+        prev = self.tail
+        copies = []
+        for k, r in enumerate(runs):
+            r.pass_, r.k, r.first = P, k, first
+            if r.speculative:
+                sid = self.meta.acquire()
+                assert sid is not None, "out of sequence partitions"
+                r.seq = 1 << sid
+                if prev is not None and prev.speculative:
+                    copies.append((prev.seq.bit_length() - 1, r.seq))   # early sharing: build on the run before
+            P.h_in[0, first:first + r.n] = torch.as_tensor(np.asarray(r.tokens, dtype=np.int32))
+            P.h_in[1, first:first + r.n] = torch.arange(r.start, r.start + r.n, dtype=torch.int32)
+            P.h_in[2, first:first + r.n] = _i32(r.seq)
+            # a non-speculative run's entry belongs to every sequence at once (it is known to be right),
+            # but the run itself reads the canonical sequence only: never another run's speculation
+            P.h_in[3, first:first + r.n] = _i32(r.seq) if r.speculative else 1
+            P.cancel[k] = 0
+            first += r.n
+            prev = r
+        for dst, src in ((P.tokens, 0), (P.positions, 1), (P.cell_seq, 2), (P.sees_seq, 3)):
+            dst.copy_(P.h_in[src], non_blocking=True)
+        self.meta.place(n_tot, P.positions, P.cell_seq, self.dense, P.slots, P.out[2:3])
+        for src_id, dst_mask in copies:
+            self.meta.seq_cp(src_id, dst_mask)
+        self.meta.build_mask(n_tot, P.positions, P.sees_seq, self.dense, self.dense, P.mask, P.out[3:4])
+        desc = pi.Run.__new__(pi.Run)
+        desc.n, desc.tokens, desc.positions = n_tot, P.tokens, P.positions
+        desc.slots, desc.mask, desc.parent = P.slots, P.mask, None
+        desc.prefix_len, desc.window_base = self.dense, self.dense
+        groups = [k for k, r in enumerate(runs) for _ in range(r.n)]
+        # (a non-speculative run is never cancelled -- its entries are what later runs build on --
+        # because the bookkeeping never stores into its word)
+        pi.stage_forward_multi(self.model, self.kv, desc, groups, 0, self.L, logits_out=P.logits,
+                               cancel_flags_ptr=P.cancel_dev, group_status=P.out[_GS:_GS + 2 * len(runs)],
+                               run_status=P.out[0:2])
+        prev = self.tail
+        for k, r in enumerate(runs):
+            a, b = r.first, r.first + r.n
+            res = P.out[_RES + 2 * k:_RES + 2 * k + 2]
+            gst = P.out[_GS + 2 * k:_GS + 2 * k + 2]
+            if prev is None:
+                pi.verify_greedy_chained(P.tokens[a:b], None, r.n, P.logits[a:b], self.vocab, r.tokens[0], None, 0, gst,
+                                         P.out[_PATH + a:_PATH + b], res)
+            else:
+                pres = prev.pass_.out[_RES + 2 * prev.k:_RES + 2 * prev.k + 2]
+                pi.verify_greedy_chained(P.tokens[a:b], None, r.n, P.logits[a:b], self.vocab, 0, pres, prev.n, gst,
+                                         P.out[_PATH + a:_PATH + b], res)
+            if r.speculative:
+                self.meta.accept(r.n, P.positions[a:b], P.cell_seq[a:b], P.out[_PATH + a:_PATH + b], res)
+            prev = r
+        P.out_host.copy_(P.out, non_blocking=True)
+        P.event.record()
+        done = []
+        for k, r in enumerate(runs):
+            assumed = self._assumed(r.start, done)
+            r.id = self.sched.begin_run(r.speculative, assumed, r.start - len(assumed), r.tokens, list(range(-1, r.n - 1)),
+                                        list(range(r.start, r.start + r.n)),
+                                        cancel_word_ptr=P.cancel.data_ptr() + 4 * k)
+            done.append(r)
+            self.stats["runs"] += 1
+            self.stats["speculative" if r.speculative else "non_speculative"] += 1
+            if r.speculative:
+                self.stats["tokens_speculated"] += r.n
+        P.runs = runs
+        self.fifo.append(P)
+        self.tail = runs[-1]
+        self.issued_cells += n_tot
+        self.stats["passes"] += 1
 
     # ---- results ---------------------------------------------------------------------------
     def _process_head(self):
-        run = self.fifo.pop(0)
-        run.slot.event.synchronize()
-        out = run.slot.out_host.numpy()
-        status, layers_done, a, bonus, placed, bad = (int(out[i]) for i in range(6))
-        state = self.sched.complete_run(run.id)
-        if placed != pi.PI_OK or bad != 0:
-            raise RuntimeError("run %d: place status %d, %d inexpressible pairs" % (run.id, placed, bad))
-        if status not in (pi.PI_OK, pi.PI_CANCELLED):
-            raise pi.PiError(status, "stage forward of run %d" % run.id)
-        counted = state == 0 and status == pi.PI_OK and a >= 1
-        if state != 0:
-            self.stats["discarded"] += 1
-        if status == pi.PI_CANCELLED:
-            self.stats["cancelled"] += 1
-            self.stats["layers_skipped"] += self.L - layers_done
-        if counted:
-            # positions start .. start+a-1 hold the run's accepted tokens (the first of them is the
-            # accepted end already), position start+a the target's own token
-            new = run.tokens[1:a] + [bonus]
-            assert len(self.accepted) == run.start + 1 and self.accepted[run.start] == run.tokens[0]
-            self.accepted += new
-            if run.speculative:
-                self.stats["tokens_accepted_from_drafts"] += a
-            for rid, _, _ in self.sched.accept_tokens(new, run_completed=True):
-                for r in self.fifo:
-                    if r.id == rid:
-                        r.cancelled = True
-        if run.speculative:
-            self.meta.release(run.seq.bit_length() - 1)
+        P = self.fifo.pop(0)
+        P.event.synchronize()
+        out = P.out_host.numpy()
+        if int(out[2]) != pi.PI_OK or int(out[3]) != 0:
+            raise RuntimeError("pass: place status %d, %d inexpressible pairs" % (int(out[2]), int(out[3])))
+        if int(out[0]) not in (pi.PI_OK, pi.PI_CANCELLED):
+            raise pi.PiError(int(out[0]), "stage forward")
+        for r in P.runs:
+            status, layers_done = int(out[_GS + 2 * r.k]), int(out[_GS + 2 * r.k + 1])
+            a, bonus = int(out[_RES + 2 * r.k]), int(out[_RES + 2 * r.k + 1])
+            state = self.sched.complete_run(r.id)
+            counted = state == 0 and status == pi.PI_OK and a >= 1
+            if state != 0:
+                self.stats["discarded"] += 1
+            if status == pi.PI_CANCELLED:
+                self.stats["cancelled"] += 1
+                self.stats["layers_skipped"] += self.L - layers_done
+            if counted:
+                # positions start .. start+a-1 hold the run's accepted tokens (the first of them is
+                # the accepted end already), position start+a the target's own token
+                new = r.tokens[1:a] + [bonus]
+                assert len(self.accepted) == r.start + 1 and self.accepted[r.start] == r.tokens[0]
+                self.accepted += new
+                if r.speculative:
+                    self.stats["tokens_accepted_from_drafts"] += a
+                hit = {rid for rid, _, _ in self.sched.accept_tokens(new, run_completed=True)}
+                for q in P.runs + self._runs_in_flight():
+                    if q.id in hit:
+                        q.cancelled = True
+            if r.speculative:
+                self.meta.release(r.seq.bit_length() - 1)
         # the chain can be continued only while its last run is in flight and still stands (a
         # rejected token takes every run built on it along, so the last run tells)
-        if self.tail is run or (self.tail is not None and self.tail.cancelled):
+        if self.tail is not None and (self.tail.pass_ is P or self.tail.cancelled):
             self.tail = None
-        self.free_slots.append(run.slot)
+        P.runs = []
+        self.free.append(P)
 
     def _compact(self):
         assert not self.fifo
@@ -201,35 +274,24 @@ class ContinuousSpeculation:
         """Run until n_tokens have been generated after first_token; returns them."""
         goal = self.first_generated + n_tokens
         while len(self.accepted) < goal:
-            if self.fifo and self.fifo[0].slot.event.query():
+            if self.fifo and self.fifo[0].event.query():
                 self._process_head()                       # logits are waiting: sample and verify
                 continue
             if not self.fifo and self.issued_cells + 1 + self.mb > pi.PI_WINDOW:
                 self._compact()
                 continue
-            if self.tail is None and self._room(1):
-                # nothing in flight covers the accepted end: the non-speculative run
-                self._issue([self.accepted[-1]], len(self.accepted) - 1, speculative=False)
-                continue
-            if self.tail is not None and self._room(self.mb):
-                start = self.tail.start + self.tail.n
-                batch = []
-                while len(batch) < self.mb:
-                    tok, conf = self.draft(start + len(batch))
-                    if not self.sched.want_speculation(conf):
-                        break
-                    batch.append(int(tok))
-                if batch:
-                    self._issue(batch, start, speculative=True)
-                    self.sched.on_speculated()
+            if len(self.fifo) < self.depth and self.free and self.issued_cells + 1 <= pi.PI_WINDOW:
+                runs = self._plan_pass()
+                if runs:
+                    self._issue(runs)
                     continue
-                self.stats["cutoff_stops"] += 1
-                waiting = bool(self.fifo) and self.fifo[0].slot.event.query()
-                self.sched.on_speculation_stopped(waiting)
-                if not waiting and not self.fifo:
-                    continue                               # idle: the cutoff decays until speculation resumes
+                if self._cutoff_stop:                      # speculation stopped for lack of confidence: one decay per stop
+                    waiting = bool(self.fifo) and self.fifo[0].event.query()
+                    self.sched.on_speculation_stopped(waiting)
+                    if not self.fifo:
+                        continue                           # idle: the cutoff decays until speculation resumes
             if self.fifo:
-                self._process_head()                       # nothing to issue: wait for the oldest run
+                self._process_head()                       # nothing to issue: wait for the oldest pass
         while self.fifo:
             self._process_head()
         torch.cuda.synchronize()

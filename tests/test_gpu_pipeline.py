@@ -45,19 +45,23 @@ def tiny_truth():
     gm.free()
 
 
-@pytest.mark.parametrize("alpha,depth,mb,cutoff", [
-    (0.7, 3, 4, (0.3, 0.05, 0.05)),
-    (0.3, 2, 2, (0.5, 0.1, 0.2)),
-    (1.0, 4, 4, (0.0, 0.0, 0.0)),        # every draft right, never a cutoff stop
-    (0.0, 3, 3, (0.2, 0.0, 0.1)),        # every draft wrong: one token per non-speculative run
-    (0.8, 2, 4, (0.3, 0.02, 0.05)),      # the shortest queue: one run behind the non-speculative one
+@pytest.mark.parametrize("alpha,depth,mb,cutoff,rpp", [
+    (0.7, 3, 4, (0.3, 0.05, 0.05), 1),
+    (0.3, 2, 2, (0.5, 0.1, 0.2), 1),
+    (1.0, 4, 4, (0.0, 0.0, 0.0), 1),        # every draft right, never a cutoff stop
+    (0.0, 3, 3, (0.2, 0.0, 0.1), 1),        # every draft wrong: one token per non-speculative run
+    (0.8, 2, 4, (0.3, 0.02, 0.05), 1),      # the shortest queue: one run behind the non-speculative one
+    (0.7, 2, 4, (0.1, 0.03, 0.05), 4),      # several runs share a pass over the weights
+    (0.9, 1, 3, (0.0, 0.0, 0.0), 6),        # one pass in flight, up to six runs and sixteen tokens in it
+    (0.3, 3, 1, (0.2, 0.05, 0.05), 3),      # one-token micro-batches
 ])
-def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutoff):
+def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutoff, rpp):
     sh, T, first, G, safe, gm = tiny_truth
     n_gen = min(safe, 64)
     gkv = pi.KVCache(gm, 176)
     gpu_loader.prefill_kv_synthetic(gkv, sh, 3, T)
-    u = synth.uniform_int_host(2 * (len(G) + 64), 17, synth.stream_id(synth.T_MISC, int(alpha * 100) + depth), 1 << 20)
+    u = synth.uniform_int_host(2 * (len(G) + 64), 17, synth.stream_id(synth.T_MISC, int(alpha * 100) + depth + 10 * rpp),
+                               1 << 20)
 
     def draft(pos):
         i = pos - (T + 1)
@@ -66,7 +70,7 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
         return (g if right else (g + 1 + int(u[2 * i]) % 7) % sh.vocab), float(u[2 * i + 1]) / (1 << 20)
 
     cs = ContinuousSpeculation(gm, gkv, T, first, draft, depth=depth, micro_batch=mb, base_cutoff=cutoff[0],
-                               recovery=cutoff[1], decay=cutoff[2])
+                               recovery=cutoff[1], decay=cutoff[2], runs_per_pass=rpp)
     out = cs.generate(n_gen)
     st = cs.stats
     assert out == G[:n_gen], "first difference at %d" % next(i for i in range(n_gen) if out[i] != G[i])
@@ -79,6 +83,8 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
     assert pos[:n_acc - 1].tolist() == list(range(n_acc - 1)) and not (pos[n_acc - 1:] >= 0).any()
     assert len(gkv) == n_acc - 1
     assert st["runs"] == st["speculative"] + st["non_speculative"]
+    if rpp > 1:
+        assert st["passes"] < st["runs"]
     if alpha == 1.0:
         assert st["cancelled"] == 0 and st["tokens_accepted_from_drafts"] >= n_gen - st["non_speculative"] - 4
     if alpha == 0.0:
@@ -89,4 +95,4 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
         assert st["discarded"] > 0                                    # runs built on a rejected token were thrown away
     assert st["compactions"] >= 1
     cs.close()
-    print("alpha %.1f depth %d mb %d: %s" % (alpha, depth, mb, st))
+    print("alpha %.1f depth %d mb %d runs/pass %d: %s" % (alpha, depth, mb, rpp, st))
