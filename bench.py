@@ -34,7 +34,7 @@ def algorithmic_bytes(shape, layer_bytes, lm_bytes, prefix_len, n):
 
 
 def cpu_baseline(shape, prefix_len, n, seed):
-    """The CPU oracle timed on a bounded sample: a 1-layer and a 3-layer model of the same
+    """The CPU oracle timed on a bounded sample: a 2-layer and a 10-layer model of the same
     layer shape (KV prefix included), extrapolated linearly to the full depth."""
     import dataclasses
     import numpy as np
@@ -47,7 +47,8 @@ def cpu_baseline(shape, prefix_len, n, seed):
     except Exception:
         cores = os.cpu_count() or 1
     times = {}
-    for nl in (1, 3):
+    lo, hi = (2, 10) if shape.n_layers >= 10 else (1, shape.n_layers)
+    for nl in (lo, hi):
         sh = dataclasses.replace(shape, n_layers=nl, name="%s_l%d" % (shape.name, nl))
         om = from_synth.model_from_seed(sh, seed)
         for name in ("embed", "final_norm", "lm_head"):
@@ -62,11 +63,11 @@ def cpu_baseline(shape, prefix_len, n, seed):
         out = oracle.stage_forward(om, okv, run, 0, nl, tokens=toks)
         oracle.verify_greedy(toks, run["parent"], out["logits"].astype(np.float32), int(toks[0]))
         times[nl] = time.perf_counter() - t0
-    per_layer = (times[3] - times[1]) / 2.0
-    full = times[1] + per_layer * (shape.n_layers - 1)
+    per_layer = (times[hi] - times[lo]) / float(hi - lo) if hi > lo else times[lo] / lo
+    full = times[lo] + per_layer * (shape.n_layers - lo)
     return {"value": n / full, "unit": "verified tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "n=%d, T=%d: timed 1-layer (%.2fs) and 3-layer (%.2fs) models of the same layer shape, "
-                      "extrapolated to %d layers (%.1fs per forward)" % (n, prefix_len, times[1], times[3],
+            "sample": "n=%d, T=%d: timed %d-layer (%.2fs) and %d-layer (%.2fs) models of the same layer shape, "
+                      "extrapolated to %d layers (%.1fs per forward)" % (n, prefix_len, lo, times[lo], hi, times[hi],
                                                                          shape.n_layers, full)}
 
 
