@@ -2,7 +2,7 @@
 """Writes the stored expected values under tests/golden/ by running the CPU oracle only.
 
 Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_w8_linear, llama7b_w4_linear, llama7b_runs,
-tinyllama_decode, llama70b_layer)
+tinyllama_decode, llama70b_layer, llama70b_w8_layer, llama70b_w4_layer)
 Every value comes from oracle/ on the seeded synthetic inputs of synth/; nothing here touches
 the HIP library.  The files are small JSON: per logits row the argmax, the top-2 gap, the row's
 max |logit| and the logits at a fixed sample of columns.
@@ -148,28 +148,38 @@ def tinyllama_decode():
     return out
 
 
-def llama70b_layer():
+def llama70b_layer(shape_name="llama70b"):
     """One layer plus the LM head of the Llama-70B shape (d 8192, 64 query / 8 KV heads x 128,
-    FFN 28672), bf16, 2048 synthetic prefix cells: speculative batches of 1 and 16 tokens."""
+    FFN 28672), bf16 (or 8-bit / 4-bit weight matrices), 2048 synthetic prefix cells: speculative
+    batches of 1 and 16 tokens."""
     import dataclasses
-    sh = dataclasses.replace(synth.SHAPES["llama70b"], n_layers=1, name="llama70b_l1")
+    sh = dataclasses.replace(synth.SHAPES[shape_name], n_layers=1, name=shape_name + "_l1")
     seed, T = 0, 2048
     om = from_synth.model_from_seed(sh, seed)
     base = from_synth.kv_synthetic(sh, seed, T + 64, T)
     cols = sample_cols(sh.vocab, seed)
-    out = {"shape": "llama70b", "n_layers": 1, "seed": seed, "prefix": T, "cols": cols, "runs": {}}
+    out = {"shape": shape_name, "n_layers": 1, "seed": seed, "prefix": T, "cols": cols, "runs": {}}
     for n in (1, 16):
         t0 = time.time()
         run = synth.linear_run(n, T)
         toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT, salt=n)
         lg = oracle.stage_forward(om, base.clone(), run, 0, 1, tokens=toks)["logits"]
         out["runs"][str(n)] = {"tokens": [int(t) for t in toks], "rows": [row_record(lg[i], cols) for i in range(n)]}
-        print("llama70b_layer n=%d done in %.0fs" % (n, time.time() - t0), flush=True)
+        print("%s_layer n=%d done in %.0fs" % (shape_name, n, time.time() - t0), flush=True)
     return out
 
 
+def llama70b_w8_layer():
+    return llama70b_layer("llama70b_w8")
+
+
+def llama70b_w4_layer():
+    return llama70b_layer("llama70b_w4")
+
+
 CASES = {"llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_w4_linear": llama7b_w4_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
-         "llama70b_layer": llama70b_layer}
+         "llama70b_layer": llama70b_layer, "llama70b_w8_layer": llama70b_w8_layer,
+         "llama70b_w4_layer": llama70b_w4_layer}
 
 if __name__ == "__main__":
     for name in (sys.argv[1:] or list(CASES)):

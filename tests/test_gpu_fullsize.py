@@ -318,13 +318,15 @@ def test_tinyllama_decode_steps_match_oracle():
         m.free()
 
 
-def test_llama70b_shaped_layer_matches_oracle():
+@pytest.mark.parametrize("shape_name", ["llama70b", "llama70b_w8", "llama70b_w4"])
+def test_llama70b_shaped_layer_matches_oracle(shape_name):
     """One decoder layer plus the LM head of the Llama-70B shape (d 8192, 64 query / 8 KV heads,
     FFN 28672) over 2048 prefix cells, batches of 1 and 16 tokens: the widest matrices, the most
-    column slices and the largest grouped-query fan-out the kernels meet."""
+    column slices and the largest grouped-query fan-out the kernels meet; with bf16, 8-bit and
+    4-bit weight matrices."""
     import dataclasses
-    g = _load("llama70b_layer")
-    sh = dataclasses.replace(synth.SHAPES["llama70b"], n_layers=g["n_layers"], name="llama70b_l1")
+    g = _load(shape_name + "_layer")
+    sh = dataclasses.replace(synth.SHAPES[shape_name], n_layers=g["n_layers"], name=shape_name + "_l1")
     m = gpu_loader.load_model(sh, g["seed"])
     T = g["prefix"]
     kv = pi.KVCache(m, T + 64)
