@@ -300,6 +300,16 @@ class Run:
         self.prefix_len = int(prefix_len)
         self.window_base = int(window_base)
 
+    @classmethod
+    def from_device(cls, n: int, tokens, positions, slots, mask, prefix_len: int, window_base: int, parent=None):
+        """A run whose arrays are already device tensors (int32 tokens/positions/slots/parent,
+        int64 mask words), e.g. slots and masks produced by the cell-metadata kernels; the first
+        n entries of each are used."""
+        r = cls.__new__(cls)
+        r.n, r.tokens, r.positions, r.slots, r.mask, r.parent = int(n), tokens, positions, slots, mask, parent
+        r.prefix_len, r.window_base = int(prefix_len), int(window_base)
+        return r
+
     def desc(self) -> PiRunDesc:
         return PiRunDesc(self.n, _ptr(self.tokens), _ptr(self.positions), _ptr(self.slots), _ptr(self.mask),
                          self.prefix_len, self.window_base)

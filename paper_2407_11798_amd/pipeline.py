@@ -176,10 +176,7 @@ class ContinuousSpeculation:
         for src_id, dst_mask in copies:
             self.meta.seq_cp(src_id, dst_mask)
         self.meta.build_mask(n_tot, P.positions, P.sees_seq, self.dense, self.dense, P.mask, P.out[3:4])
-        desc = pi.Run.__new__(pi.Run)
-        desc.n, desc.tokens, desc.positions = n_tot, P.tokens, P.positions
-        desc.slots, desc.mask, desc.parent = P.slots, P.mask, None
-        desc.prefix_len, desc.window_base = self.dense, self.dense
+        desc = pi.Run.from_device(n_tot, P.tokens, P.positions, P.slots, P.mask, self.dense, self.dense)
         groups = [k for k, r in enumerate(runs) for _ in range(r.n)]
         # (a non-speculative run is never cancelled -- its entries are what later runs build on --
         # because the bookkeeping never stores into its word)
