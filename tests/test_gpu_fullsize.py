@@ -291,6 +291,55 @@ def test_llama7b_runs_described_by_cell_metadata(llama7b):
     assert pos[:T + a].tolist() == list(range(T + a)) and not (pos[T + a:] >= 0).any()
 
 
+def test_llama7b_continuous_speculation_equals_plain_decoding(llama7b):
+    """At full size there is no oracle sequence to compare with, but the method's own claim
+    (Section "Model Accuracy") holds at any size: whatever the draft quality and however the
+    runs are queued, cancelled and packed into passes, the tokens are those of decoding one
+    token per forward.  Compared up to the first step whose top-2 logit gap is too small for
+    the batch size not to matter."""
+    from paper_2407_11798_amd.pipeline import ContinuousSpeculation
+    sh, m = llama7b
+    T, n_gen = 512, 24
+    kv = pi.KVCache(m, T + 64 + 64)
+    first = int(synth.tokens_host(sh, 0, 1, synth.T_MISC, salt=77)[0])
+    gpu_loader.prefill_kv_synthetic(kv, sh, 0, T)
+    lg = torch.empty((1, sh.vocab), device="cuda")
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    res = torch.zeros(2, dtype=torch.int32, device="cuda")
+    G, safe, t = [], n_gen, first
+    for i in range(n_gen):
+        run = gpu_loader.make_run(synth.linear_run(1, T + i), np.array([t], dtype=np.int32))
+        pi.stage_forward(m, kv, run, 0, sh.n_layers, logits_out=lg)
+        pi.verify_greedy(run.tokens, None, 1, lg, sh.vocab, t, acc, res)
+        pi.kv_rollback(kv, run.slots, 1, acc, res)
+        torch.cuda.synchronize()
+        top = torch.topk(lg[0], 2).values
+        if float(top[0] - top[1]) < 1e-3 * float(lg[0].abs().max()) and safe == n_gen:
+            safe = i
+        t = int(res[1].item())
+        G.append(t)
+    assert safe >= 12
+    for alpha, depth, rpp in ((0.7, 3, 1), (0.7, 2, 4)):
+        gpu_loader.prefill_kv_synthetic(kv, sh, 0, T)
+        u = synth.uniform_int_host(2 * (n_gen + 64), 5, synth.stream_id(synth.T_MISC, 10 * rpp), 1 << 20)
+
+        def draft(pos, u=u):
+            i = pos - (T + 1)
+            g = G[i] if i < len(G) else 0
+            return (g if u[2 * i] < alpha * (1 << 20) else (g + 3) % sh.vocab), float(u[2 * i + 1]) / (1 << 20)
+
+        cs = ContinuousSpeculation(m, kv, T, first, draft, depth=depth, micro_batch=4, base_cutoff=0.0, recovery=0.05,
+                                   decay=0.05, runs_per_pass=rpp)
+        out = cs.generate(n_gen)
+        st = dict(cs.stats)
+        cs.close()
+        assert out[:safe] == G[:safe], (alpha, depth, rpp)
+        assert st["tokens_accepted_from_drafts"] > 0 and st["discarded"] > 0
+        if rpp == 1:
+            assert st["cancelled"] > 0 and st["layers_skipped"] > 0      # at this size the signal arrives in time
+    kv.free()
+
+
 def test_tinyllama_decode_steps_match_oracle():
     """TinyLlama-shaped draft model (grouped-query attention, 4 KV heads x 64): single-token decode
     steps at short and long prefixes, the generator side's workload."""
