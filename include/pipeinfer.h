@@ -7,7 +7,7 @@
  *
  * Conventions
  *  - Every function returns an int32_t status: PI_OK (0), PI_CANCELLED (1, not an error)
- *    or a negative PI_E_* code.  No exceptions, no global state besides handles.
+ *    or a negative PI_E_* code.  No exceptions.
  *  - "device" pointers are caller-owned GPU memory (e.g. torch tensors); "host" pointers
  *    are ordinary CPU memory.  The library never frees or keeps a caller pointer beyond
  *    the call, except the asynchronous work enqueued on the given stream, which reads and
@@ -18,6 +18,14 @@
  *  - pi_model and pi_kv own their device memory until the matching *_free.  A pi_model
  *    carries one set of activation scratch buffers: at most one forward per model may be
  *    in flight at a time (issue them on one stream, or serialise streams with events).
+ *  - A forward is one persistent kernel whose workgroups synchronise with each other, so all
+ *    of them must be resident at once: the library orders every forward on a device behind
+ *    the previous forward on that device, whatever model and stream they belong to (an event
+ *    wait enqueued on the caller's stream; no host blocking).  Forwards of two models on two
+ *    streams therefore run one after the other, never side by side.  Other long kernels of
+ *    the caller that hold compute units for a long time delay a forward but cannot stop it.
+ *  - Process-wide state besides the handles: that per-device launch order, and one small
+ *    per-device scratch buffer that the verification calls share (see pi_verify_greedy).
  *  - Tokens per weight pass: 1 .. PI_MAX_BATCH (of one run, or of up to PI_MAX_GROUPS runs
  *    sharing the pass).  All sizes are validated on the host before any
  *    launch; a shape the kernels do not support returns PI_E_SHAPE, never a launch.
@@ -179,8 +187,10 @@ typedef struct {
  *              the first layer of the call and at every layer boundary; once a non-zero
  *              value is seen no further layer starts, outputs stay untouched and the run
  *              reports PI_CANCELLED.  It may only go 0 -> 1 during a run.
- *   run_status: device-visible int32[2], written by the device: [0] = PI_OK, PI_CANCELLED
- *              or PI_E_SLOT_LIVE, [1] = layers_done = index of the first layer NOT
+ *   run_status: device-visible int32[2], written by the device: [0] = PI_OK, PI_CANCELLED,
+ *              PI_E_SLOT_LIVE (a slot below kv_len or outside the window: nothing was
+ *              evaluated) or PI_E_ARG (a position outside [0, max_pos): likewise),
+ *              [1] = layers_done = index of the first layer NOT
  *              evaluated (== layer_end on success).  K/V of layers < layers_done were
  *              written to the run's slots; clean them with pi_kv_rollback.  [0] = PI_E_HIP
  *              means a bounded wait inside the kernel ran out (workgroups wait for each
@@ -229,7 +239,10 @@ int32_t pi_stage_forward_multi(pi_model* m, pi_kv* kv, const pi_run_desc* run, c
  * stop at the first node without a matching child.
  * Outputs (device): accepted_nodes[n] (first accepted_count entries valid, rest -1),
  * result[2] = {accepted_count, bonus_token} where bonus_token is the target's own next
- * token after the accepted path.  vocab <= 2^24.  Asynchronous. */
+ * token after the accepted path.  vocab <= 2^24.  Asynchronous.
+ * All verification calls on a device share one scratch buffer (row maxima and a counter,
+ * allocated on the first call on that device): issue them on one stream or order them with
+ * events; two verifications running at the same time on one device race. */
 int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
                          int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
                          int32_t* result, void* stream);
@@ -254,7 +267,12 @@ int32_t pi_verify_greedy_chained(const int32_t* draft, const int32_t* parent, in
  * layers, to canonical cells kv_len .. kv_len+a-1 in path order, every other cell in
  * slots[] is zero-filled (free again), and kv_len += a.  accepted_nodes/result are the
  * device outputs of pi_verify_greedy; pass result == NULL to discard the whole run
- * (cancelled run: a = 0).  Asynchronous; kv_len is updated on the device. */
+ * (cancelled run: a = 0).  Asynchronous; kv_len is updated on the device.
+ * slots[] and the result are device data that may come from a forward the device refused
+ * (PI_E_SLOT_LIVE, PI_E_ARG): only cells in [kv_len, n_cells) are read as a source or zero-filled
+ * -- a slot below kv_len (a live canonical cell) or outside the cache is skipped -- and the path
+ * is cut before the first accepted entry that is not a token of the run with such a cell, and at
+ * n_cells.  Rolling back a refused run therefore leaves the cache exactly as it was. */
 int32_t pi_kv_rollback(pi_kv* kv, const int32_t* slots, int32_t n, const int32_t* accepted_nodes,
                        const int32_t* result, void* stream);
 
@@ -400,7 +418,9 @@ const char* pi_strerror(int32_t status);
  * for at least `s_k` column slices in that projection phase; 0 restores the built-in choice, and
  * the library still rounds up to a split the tile count, grid and LDS allow.  phase 5: s_k != 0
  * makes later runs record the barrier timestamps pi_debug_read_trace returns (off by default:
- * reading the clock at every barrier costs time). */
+ * reading the clock at every barrier costs time).  phase 6: s_k = KiB of LDS the staged
+ * activations of a projection phase should stay under (16 .. 150; 0 restores the built-in 96):
+ * a larger figure means fewer column slices and more staging per workgroup. */
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],

@@ -168,6 +168,7 @@ class Model:
 
     def __init__(self, shape, max_pos: int = 4096):
         self.shape = shape
+        self.max_pos = max_pos
         wf = getattr(shape, "weight_format", "native")
         fp8 = wf in ("fp8", "fp4")
         cfg = PiModelConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,

@@ -42,6 +42,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
+  size_t lds_budget = kProjLdsBudget;  // what a projection phase's split aims to stay under (tuning hook)
   size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
   int wdtype = PI_DTYPE_BF16;  // format of the weight matrices (cfg.dtype, or 8-bit)
   int kt32() const { return weight_tile_cols(wdtype) / 32; }  // 32-column tiles per weight tile
@@ -102,7 +103,7 @@ hipError_t dev_alloc(pi_model* m, T** p, size_t bytes, bool zero) {
 // the grid, lets the phase's LDS needs for n tokens fit the budget and -- where the matrix has
 // fewer row blocks than the grid has workgroups -- gives every workgroup a row block, as long as
 // a slice keeps at least 16 tiles per row block.  0 = impossible.
-int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t budget = kProjLdsBudget) {
+int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t budget) {
   const int ov = m->sk_override[phase];
   int fits = 0;
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
@@ -132,7 +133,7 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
   p->lds = 0;
   p->part_tiles = 1;
   for (int ph = 0; ph < 5; ++ph) {
-    const int sk = choose_sk(m, ph, *mats[ph], n);
+    const int sk = choose_sk(m, ph, *mats[ph], n, m->lds_budget);
     if (sk == 0) return false;
     p->sk[ph] = sk;
     const int nt = mats[ph]->KT / sk;
@@ -156,14 +157,50 @@ size_t flag_index(const pi_model* m, int kind, int layer) {
   return (size_t)kind * m->cfg.n_layers + (is_layer_kind(kind) ? layer : 0);
 }
 
+// Per-device process-wide state (kMaxDevices devices at most; a device beyond that is refused).
+constexpr int kMaxDevices = 16;
 struct VerifyScratch {
   float* best_val = nullptr;
   int32_t* best_idx = nullptr;
   int* cnt = nullptr;
+  hipError_t err = hipSuccess;
+  bool ready = false;
 };
-VerifyScratch g_verify;
-std::once_flag g_verify_once;
-hipError_t g_verify_err = hipSuccess;
+VerifyScratch g_verify[kMaxDevices];
+std::mutex g_verify_mutex;
+
+// The stage kernel's workgroups wait for each other, so two stage kernels must never share the
+// device: each launch waits (on its own stream) for the event recorded behind the previous one.
+struct LaunchOrder {
+  hipEvent_t ev = nullptr;
+  hipStream_t last_stream = nullptr;
+  bool any = false;
+};
+LaunchOrder g_order[kMaxDevices];
+std::mutex g_order_mutex;
+
+hipError_t launch_stage_in_order(const StageArgs& a, int wdtype, int ring, int grid, size_t lds, hipStream_t s) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_order_mutex);
+  LaunchOrder& o = g_order[dev];
+  if (!o.ev) {
+    e = hipEventCreateWithFlags(&o.ev, hipEventDisableTiming);
+    if (e != hipSuccess) return e;
+  }
+  if (o.any && o.last_stream != s) {
+    e = hipStreamWaitEvent(s, o.ev, 0);
+    if (e != hipSuccess) return e;
+  }
+  e = launch_stage(a, wdtype, ring, grid, lds, s);
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(o.ev, s);
+  o.last_stream = s;
+  o.any = true;
+  return e;
+}
 
 }  // namespace
 
@@ -414,12 +451,17 @@ int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
 }
 
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
-  if (!m || phase < 0 || phase > 5 || s_k < 0) return PI_E_ARG;
+  if (!m || phase < 0 || phase > 6 || s_k < 0) return PI_E_ARG;
   if (phase == 5) {
     m->trace_on = s_k != 0;
     return PI_OK;
   }
-  m->sk_override[phase] = s_k;
+  if (phase == 6) {
+    if (s_k != 0 && (s_k < 16 || (size_t)s_k * 1024 > kProjLdsLimit)) return PI_E_ARG;
+    m->lds_budget = s_k ? (size_t)s_k * 1024 : kProjLdsBudget;
+  } else {
+    m->sk_override[phase] = s_k;
+  }
   // The buffer of cross-slice tiles was sized for the plans in force so far; grow it for this one.
   size_t tiles = 1;
   for (int n = 1; n <= PI_MAX_BATCH; ++n) {
@@ -432,7 +474,8 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
     if (e == hipSuccess) e = dev_alloc(m, &grown, 3 * tiles * 1024, false);
     if (e == hipSuccess) e = hipMemset(grown, 0xFF, 3 * tiles * 1024);
     if (e != hipSuccess) {
-      m->sk_override[phase] = 0;
+      if (phase == 6) m->lds_budget = kProjLdsBudget;
+      else m->sk_override[phase] = 0;
       return hip_status(e);
     }
     m->part = grown;  // the old buffer stays with the model until it is freed
@@ -671,6 +714,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.final_gain = m->final_gain;
   a.embed = m->embed;
   a.rope = m->rope;
+  a.max_pos = c.max_pos;
   a.dtype = c.dtype;
   a.d = c.d_model;
   a.n_q_heads = c.n_q_heads;
@@ -728,7 +772,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.trace_cap = m->trace_cap;
   a.wgtrace = m->wgtrace_layer >= 0 ? m->wgtrace : nullptr;
   a.wgtrace_layer = m->wgtrace_layer;
-  return hip_status(launch_stage(a, m->wdtype, ring, m->grid, sp.lds, (hipStream_t)stream));
+  return hip_status(launch_stage_in_order(a, m->wdtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
 
 }  // namespace
@@ -741,18 +785,26 @@ int32_t pi_verify_greedy_chained(const int32_t* draft, const int32_t* parent, in
   if (!draft || !logits || !accepted_nodes || !result) return PI_E_ARG;
   if (n < 1 || n > PI_MAX_BATCH || vocab < 1 || vocab > (1 << 24)) return PI_E_SHAPE;
   if (prev_result && (prev_n < 1 || prev_n > PI_MAX_BATCH)) return PI_E_SHAPE;
-  std::call_once(g_verify_once, [] {
-    hipError_t e = hipMalloc((void**)&g_verify.best_val, PI_MAX_BATCH * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc((void**)&g_verify.best_idx, PI_MAX_BATCH * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc((void**)&g_verify.cnt, sizeof(int));
-    if (e == hipSuccess) e = hipMemset(g_verify.cnt, 0, sizeof(int));
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-    g_verify_err = e;
-  });
-  if (g_verify_err != hipSuccess) return hip_status(g_verify_err);
+  int dev = 0;
+  hipError_t de = hipGetDevice(&dev);
+  if (de != hipSuccess) return hip_status(de);
+  if (dev < 0 || dev >= kMaxDevices) return PI_E_SHAPE;
+  VerifyScratch& vs = g_verify[dev];
+  {
+    std::lock_guard<std::mutex> lock(g_verify_mutex);
+    if (!vs.ready) {
+      hipError_t e = hipMalloc((void**)&vs.best_val, PI_MAX_BATCH * sizeof(float));
+      if (e == hipSuccess) e = hipMalloc((void**)&vs.best_idx, PI_MAX_BATCH * sizeof(int32_t));
+      if (e == hipSuccess) e = hipMalloc((void**)&vs.cnt, sizeof(int));
+      if (e == hipSuccess) e = hipMemset(vs.cnt, 0, sizeof(int));
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+      vs.err = e;
+      vs.ready = true;
+    }
+  }
+  if (vs.err != hipSuccess) return hip_status(vs.err);
   return hip_status(launch_verify(draft, parent, n, logits, vocab, root_expected, prev_result, prev_n, run_status,
-                                  accepted_nodes, result, g_verify.best_val, g_verify.best_idx, g_verify.cnt,
-                                  (hipStream_t)stream));
+                                  accepted_nodes, result, vs.best_val, vs.best_idx, vs.cnt, (hipStream_t)stream));
 }
 
 int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,

@@ -99,6 +99,12 @@ __global__ void __launch_bounds__(256) verify_kernel(const int32_t* draft, const
 // accepted path's pieces, zero every slot of the run, then write the path to cells
 // kv_len .. kv_len+a-1.  All of a thread's reads precede its writes and threads touch
 // disjoint columns, so overlapping source and destination cells are safe.
+// The slots and the verification result are device data the host never saw, and this kernel may
+// be queued right behind a forward that refused them: only cells of [kv_len, n_cells) are ever
+// read as a source or zero-filled (a slot outside is skipped: it is a live canonical cell, or no
+// cell at all), the accepted count is cut at the first entry that does not name a token of the run
+// whose slot is such a cell, and at what still fits below n_cells.  Every thread takes these
+// decisions from the same words, so all agree.
 __global__ void __launch_bounds__(256) rollback_kernel(char* kbuf, char* vbuf, int elem_size,
                                                        int n_layers, int n_kv_heads, int n_cells,
                                                        int head_dim, const int32_t* slots, int n,
@@ -106,8 +112,21 @@ __global__ void __launch_bounds__(256) rollback_kernel(char* kbuf, char* vbuf, i
                                                        int32_t* kv_len, int* cnt) {
   const int pieces = head_dim * elem_size / 16;
   const size_t total = (size_t)n_layers * n_kv_heads * pieces * 2;
-  const int a = result ? result[0] : 0;
   const int len = *kv_len;
+  int a = result ? result[0] : 0;
+  a = a < 0 ? 0 : (a > n ? n : a);
+  if (a > n_cells - len) a = n_cells - len > 0 ? n_cells - len : 0;
+  int src[PI_MAX_BATCH];
+#pragma unroll
+  for (int j = 0; j < PI_MAX_BATCH; ++j) {
+    src[j] = -1;
+    if (j < a) {
+      const int node = accepted[j];
+      const int s = node >= 0 && node < n ? slots[node] : -1;
+      if (s >= len && s < n_cells) src[j] = s;
+      else a = j;  // the path ends before the first entry that cannot be committed
+    }
+  }
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < total) {
     const int which = (int)(idx & 1);
@@ -120,8 +139,11 @@ __global__ void __launch_bounds__(256) rollback_kernel(char* kbuf, char* vbuf, i
     uint4 keep[PI_MAX_BATCH];
 #pragma unroll
     for (int j = 0; j < PI_MAX_BATCH; ++j)
-      if (j < a) keep[j] = *(const uint4*)(base + (size_t)slots[accepted[j]] * cell_stride);
-    for (int i = 0; i < n; ++i) *(uint4*)(base + (size_t)slots[i] * cell_stride) = make_uint4(0, 0, 0, 0);
+      if (j < a) keep[j] = *(const uint4*)(base + (size_t)src[j] * cell_stride);
+    for (int i = 0; i < n; ++i) {
+      const int s = slots[i];
+      if (s >= len && s < n_cells) *(uint4*)(base + (size_t)s * cell_stride) = make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
     for (int j = 0; j < PI_MAX_BATCH; ++j)
       if (j < a) *(uint4*)(base + (size_t)(len + j) * cell_stride) = keep[j];

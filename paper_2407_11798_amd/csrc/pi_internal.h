@@ -94,6 +94,7 @@ struct StageArgs {
   const float* final_gain;
   const void* embed;
   const float2* rope;  // [max_pos][hd/2] (cos, sin)
+  int max_pos;
   int dtype, d, n_q_heads, n_kv_heads, head_dim, ffn, vocab, n_layers;
   float eps;
   float wscale;  // 8-bit weights: the model's power-of-two scale (1 otherwise)

@@ -1429,21 +1429,26 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   bc.dead_groups = 0;
   const int L = A.n_layers;
 
-  // run latch (first wave of workgroup 0): validate the slots (lane i: token i), probe every run's
-  // cancel word once (lane g: run g)
+  // run latch (first wave of workgroup 0): validate the slots and positions (lane i: token i), probe
+  // every run's cancel word once (lane g: run g)
   const unsigned all_tokens = (1u << A.n) - 1u;
   if (blockIdx.x == 0 && threadIdx.x < 64) {
     int status = PI_OK;
     unsigned dead = 0;
     const int len = *A.kv_len;
-    bool bad = false;
+    bool bad = false, bad_pos = false;
     if (lane < A.n) {
       const int s = A.slots[lane];
       bad = s < len || s < A.window_base || s >= A.window_base + PI_WINDOW || s >= A.n_cells;
+      // the rotary table has max_pos rows: a position outside it would be read out of bounds
+      const int p = A.positions[lane];
+      bad_pos = p < 0 || p >= A.max_pos;
     }
-    const bool refused = __builtin_amdgcn_ballot_w64(bad) != 0;
+    const bool refused_slot = __builtin_amdgcn_ballot_w64(bad) != 0;
+    const bool refused = refused_slot || __builtin_amdgcn_ballot_w64(bad_pos) != 0;
+    const int refusal = refused_slot ? PI_E_SLOT_LIVE : PI_E_ARG;
     if (refused) {
-      status = PI_E_SLOT_LIVE;
+      status = refusal;
       dead = all_tokens;
     }
     // a run that an earlier stage of the same pass reported cancelled stays cancelled, and its
@@ -1459,7 +1464,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       if ((hits >> g) & 1ull) dead |= A.group_mask[g];
     if (!refused && dead == all_tokens) status = PI_CANCELLED;
     if (A.group_status && lane < A.n_groups && !before) {
-      __hip_atomic_store(A.group_status + 2 * lane, refused ? PI_E_SLOT_LIVE : (hit ? PI_CANCELLED : PI_OK), __ATOMIC_RELAXED,
+      __hip_atomic_store(A.group_status + 2 * lane, refused ? refusal : (hit ? PI_CANCELLED : PI_OK), __ATOMIC_RELAXED,
                          __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(A.group_status + 2 * lane + 1, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

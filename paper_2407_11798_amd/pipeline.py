@@ -147,6 +147,9 @@ class ContinuousSpeculation:
         if self.dense + pi.PI_WINDOW > self.kv.n_cells:
             raise RuntimeError("KV cache too small: the window [%d, %d) does not fit %d cells"
                                % (self.dense, self.dense + pi.PI_WINDOW, self.kv.n_cells))
+        last_pos = max(r.start + r.n - 1 for r in runs)
+        if last_pos >= self.model.max_pos:
+            raise RuntimeError("position %d reaches the model's rotary table (max_pos %d)" % (last_pos, self.model.max_pos))
         P = self.free.pop()
         P.out.zero_()     # a run whose status word already says "cancelled" stays cancelled: start every pass clean
         n_tot = sum(r.n for r in runs)

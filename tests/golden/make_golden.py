@@ -2,10 +2,11 @@
 """Writes the stored expected values under tests/golden/ by running the CPU oracle only.
 
 Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_w8_linear, llama7b_w4_linear, llama7b_runs,
-tinyllama_decode, llama70b_layer, llama70b_w8_layer, llama70b_w4_layer)
+tinyllama_decode, llama70b_layer, llama70b_w8_layer, llama70b_w4_layer, llama7b_full, llama70b_full)
 Every value comes from oracle/ on the seeded synthetic inputs of synth/; nothing here touches
-the HIP library.  The files are small JSON: per logits row the argmax, the top-2 gap, the row's
-max |logit| and the logits at a fixed sample of columns.
+the HIP library.  The JSON files are small: per logits row the argmax, the top-2 gap, the row's
+max |logit| and the logits at a fixed sample of columns.  The *_full cases store whole logits
+rows (every column, float32) in an .npz next to a JSON with the per-row records.
 """
 import json
 import os
@@ -177,7 +178,91 @@ def llama70b_w4_layer():
     return llama70b_layer("llama70b_w4")
 
 
-CASES = {"llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_w4_linear": llama7b_w4_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
+def _stack_layer_by_layer(sh, seed, T, batches, keep_hidden_after=(), keep_cells_of=()):
+    """The whole stack for several batch sizes in ONE pass over the layers: a layer's weights
+    are generated once, every batch goes through that layer as a stage of its own ([l, l+1),
+    hidden state handed on), then the weights are dropped -- a 140 GB model never exists in
+    memory.  Splitting a run into stages does not change the oracle's result (pinned in
+    tests/test_oracle_pins.py), so this is stage_forward over [0, L) for each batch."""
+    store = {}
+
+    def weights(name, layer):
+        key = (name, layer)
+        if key not in store:
+            t = synth.weight_host(sh, seed, from_synth._NAME_TO_KIND[name], layer, 0.0)
+            if t.dtype == np.uint8:
+                t = (from_synth.dequantise_fp4 if sh.weight_format == "fp4" else from_synth.dequantise_fp8)(t, sh.weight_scale_exp2)
+            store[key] = t
+        return store[key]
+
+    om = oracle.OracleModel(sh, weights)
+    state = {}
+    for n in batches:
+        kv = oracle.OracleKV(sh, T + 64)
+        kv.kv_len = T
+        state[n] = {"kv": kv, "run": synth.linear_run(n, T), "toks": synth.tokens_host(sh, seed, n, synth.T_DRAFT, salt=n),
+                    "hidden": None, "hidden_after": {}, "cells": {}}
+    out_logits = {}
+    for l in range(sh.n_layers):
+        t0 = time.time()
+        k, v = synth.kv_prefill_host(sh, seed, l, T)
+        for n in batches:
+            st = state[n]
+            st["kv"].set_cells(l, 0, k, v)
+            r = oracle.stage_forward(om, st["kv"], st["run"], l, l + 1, tokens=st["toks"], hidden_in=st["hidden"])
+            if l + 1 == sh.n_layers:
+                out_logits[n] = r["logits"]
+            else:
+                st["hidden"] = r["hidden"]
+                if l + 1 in keep_hidden_after:
+                    st["hidden_after"][l + 1] = r["hidden"].astype(np.float32)
+            if l in keep_cells_of:
+                slots = st["run"]["slots"]
+                st["cells"][l] = (st["kv"].K[l, slots].astype(np.float32), st["kv"].V[l, slots].astype(np.float32))
+            # the layer's prefix cells are not needed again: keep the cache small
+            st["kv"].K[l] = 0.0
+            st["kv"].V[l] = 0.0
+        for key in [k_ for k_ in store if k_[1] == l and k_[0] not in ("embed", "final_norm", "lm_head")]:
+            del store[key]
+        print("%s layer %d done in %.0fs" % (sh.name, l, time.time() - t0), flush=True)
+    return state, out_logits
+
+
+def _full_case(shape_name, T, batches, keep_hidden_after=(), keep_cells_of=()):
+    sh = synth.SHAPES[shape_name]
+    seed = 0
+    state, logits = _stack_layer_by_layer(sh, seed, T, batches, keep_hidden_after, keep_cells_of)
+    meta = {"shape": sh.name, "seed": seed, "prefix": T, "runs": {}}
+    arrays = {}
+    for n in batches:
+        lg = logits[n]
+        meta["runs"][str(n)] = {"tokens": [int(t) for t in state[n]["toks"]],
+                                "rows": [{"argmax": int(np.argmax(lg[i])), "gap": oracle.top2_gap(lg[i]),
+                                          "maxabs": float(np.max(np.abs(lg[i])))} for i in range(n)]}
+        arrays["logits_n%d" % n] = lg.astype(np.float32)
+        for l1, h in state[n]["hidden_after"].items():
+            arrays["hidden_n%d_after%d" % (n, l1)] = h
+        for l, (kc, vc) in state[n]["cells"].items():
+            arrays["k_n%d_layer%d" % (n, l)] = kc
+            arrays["v_n%d_layer%d" % (n, l)] = vc
+    np.savez(os.path.join(HERE, shape_name + "_full.npz"), **arrays)
+    return meta
+
+
+def llama7b_full():
+    """Llama-7B shape, 512 prefix cells, linear runs of 1 and 8 tokens: every logits column."""
+    return _full_case("llama7b", 512, (1, 8), keep_cells_of=(0, 31))
+
+
+def llama70b_full():
+    """Llama-70B shape at full depth (80 layers), 2048 prefix cells, linear runs of 1 and 16
+    tokens: every logits column, the hidden state after 20 layers (one pipeline stage's share)
+    and the run's own K/V cells in three layers."""
+    return _full_case("llama70b", 2048, (1, 16), keep_hidden_after=(20,), keep_cells_of=(0, 19, 79))
+
+
+CASES = {"llama7b_full": llama7b_full, "llama70b_full": llama70b_full,
+         "llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_w4_linear": llama7b_w4_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
          "llama70b_layer": llama70b_layer, "llama70b_w8_layer": llama70b_w8_layer,
          "llama70b_w4_layer": llama70b_w4_layer}
 

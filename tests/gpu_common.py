@@ -40,3 +40,26 @@ def max_rel_rowwise(gpu, ref):
     ref = np.asarray(ref, dtype=np.float64)
     err = np.max(np.abs(np.asarray(gpu, dtype=np.float64) - ref), axis=-1)
     return float(np.max(err / np.max(np.abs(ref), axis=-1)))
+
+
+class TieBudget:
+    """Counts the comparisons that the top-2 gap rule exempts.  An argmax (and what is accepted
+    through it) is only compared with the oracle's where the oracle's two largest logits of every
+    row involved are at least 1e-3 apart; a test may use that exemption `limit` times and fails on
+    the next one, so a gap that is wrong (or a tolerance that quietly swallows the comparisons)
+    cannot go unnoticed."""
+    GAP = 1e-3
+
+    def __init__(self, limit):
+        self.limit = limit
+        self.used = 0
+        self.checks = 0
+
+    def decisive(self, gaps) -> bool:
+        self.checks += 1
+        if all(g >= self.GAP for g in gaps):
+            return True
+        self.used += 1
+        assert self.used <= self.limit, "top-2 gap exemption used %d times in %d checks (limit %d)" % (
+            self.used, self.checks, self.limit)
+        return False

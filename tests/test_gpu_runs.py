@@ -11,7 +11,7 @@ import oracle
 from oracle import from_synth
 from synth import gpu_loader
 import paper_2407_11798_amd as pi
-from gpu_common import forward, verify, max_rel_rowwise
+from gpu_common import forward, verify, max_rel_rowwise, TieBudget
 
 pytestmark = pytest.mark.gpu
 
@@ -37,6 +37,7 @@ def test_token_trees_match_oracle_and_verify(shape_name):
     """Random trees (branching <= 3, depth <= 4) at several sizes incl. the largest batch; runs
     are placed at different offsets inside the 64-cell window."""
     sh, om, okv, gm, gkv = _setup(shape_name, 40, 112)
+    ties = TieBudget(1)
     for trial, (n, offset) in enumerate([(1, 0), (4, 0), (4, 12), (7, 3), (16, 0), (16, 48), (13, 17)]):
         parent = synth.random_tree(1, trial, n)
         toks = synth.sibling_distinct_tokens(sh, 1, trial, parent)
@@ -48,7 +49,7 @@ def test_token_trees_match_oracle_and_verify(shape_name):
         root_expected = int(toks[0])
         a, acc, bonus = oracle.verify_greedy(toks, parent, ref.astype(np.float32), root_expected)
         gacc, gres = verify(grun, toks, lg, sh.vocab, root_expected)
-        if all(oracle.top2_gap(ref[i]) >= 1e-3 for i in acc):
+        if ties.decisive([oracle.top2_gap(ref[i]) for i in acc]):
             assert gres.cpu().tolist() == [a, bonus]
         pi.kv_rollback(gkv, grun.slots, n)               # discard: keep the prefix for the next trial
         assert len(gkv) == 40

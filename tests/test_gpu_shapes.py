@@ -11,7 +11,7 @@ import oracle
 from oracle import from_synth
 from synth import gpu_loader
 import paper_2407_11798_amd as pi
-from gpu_common import forward, verify, max_rel_rowwise
+from gpu_common import forward, verify, max_rel_rowwise, TieBudget
 
 pytestmark = pytest.mark.gpu
 
@@ -45,6 +45,7 @@ def test_ragged_shapes_match_oracle(name):
     seed, n_cells = 3, 160
     om = from_synth.model_from_seed(sh, seed, 0.1)
     gm = gpu_loader.load_model(sh, seed, 0.1)
+    ties = TieBudget(1)
     for T in (0, 31, 33, 96):
         okv = from_synth.kv_synthetic(sh, seed, n_cells, T)
         gkv = pi.KVCache(gm, n_cells)
@@ -62,7 +63,7 @@ def test_ragged_shapes_match_oracle(name):
             root_expected = int(toks[0])
             a, acc, bonus = oracle.verify_greedy(toks, parent, ref.astype(np.float32), root_expected)
             gacc, gres = verify(grun, toks, lg, sh.vocab, root_expected)
-            if all(oracle.top2_gap(ref[i]) >= 1e-3 for i in acc):
+            if ties.decisive([oracle.top2_gap(ref[i]) for i in acc]):
                 assert gres.cpu().tolist() == [a, bonus]
             pi.kv_rollback(gkv, grun.slots, n)
             assert len(gkv) == T

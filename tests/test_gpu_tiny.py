@@ -8,7 +8,7 @@ import oracle
 from oracle import from_synth
 from synth import gpu_loader
 import paper_2407_11798_amd as pi
-from gpu_common import forward, verify, max_rel_rowwise
+from gpu_common import forward, verify, max_rel_rowwise, TieBudget
 
 pytestmark = pytest.mark.gpu
 
@@ -93,14 +93,18 @@ def test_planted_draft_verify_and_rollback(shape_name, gain_sigma):
     assert a_ref == 2
     acc, res = verify(grun, d, lg, sh.vocab, root_expected)
     gaps = [oracle.top2_gap(ref[i]) for i in range(4)]
-    if min(gaps[:2]) >= 1e-3:
-        assert res.cpu().tolist() == [a_ref, bonus_ref]
-        assert acc.cpu().tolist()[:a_ref] == acc_ref and acc.cpu().tolist()[a_ref:] == [-1, -1]
+    # the planted rows are decisive in every configuration here (smallest gap 5e-3): no exemption
+    assert TieBudget(0).decisive(gaps[:2])
+    assert res.cpu().tolist() == [a_ref, bonus_ref]
+    assert acc.cpu().tolist()[:a_ref] == acc_ref and acc.cpu().tolist()[a_ref:] == [-1, -1]
     pi.kv_rollback(gkv, grun.slots, 4, acc, res)
     oracle.kv_rollback(okv, run["slots"], acc_ref)
     assert len(gkv) == okv.kv_len == 66
     for l in range(sh.n_layers):
         k, v = gkv.get_cells(l, 64, 64)
         assert not k[2:].any() and not v[2:].any()          # rejected cells are free again
-        assert np.max(np.abs(k[:2] - okv.K[l, 64:66])) < 5e-2
+        # the committed cells: arithmetic error only (fp32 cache) or one rounding step (bf16 cache)
+        tol = 5e-5 if sh.dtype == "f32" else 2.0 ** -7 * max(np.abs(okv.K[l, 64:66]).max(), np.abs(okv.V[l, 64:66]).max())
+        assert np.max(np.abs(k[:2] - okv.K[l, 64:66])) <= tol
+        assert np.max(np.abs(v[:2] - okv.V[l, 64:66])) <= tol
     gm.free()
