@@ -419,7 +419,7 @@ const char* pi_strerror(int32_t status);
  * the library still rounds up to a split the tile count, grid and LDS allow.  phase 5: s_k != 0
  * makes later runs record the barrier timestamps pi_debug_read_trace returns (off by default:
  * reading the clock at every barrier costs time).  phase 6: s_k = KiB of LDS the staged
- * activations of a projection phase should stay under (16 .. 150; 0 restores the built-in 96):
+ * activations of every projection phase should stay under (16 .. 150; 0 restores the built-in choice):
  * a larger figure means fewer column slices and more staging per workgroup. */
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host

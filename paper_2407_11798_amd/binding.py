@@ -13,7 +13,8 @@ from ctypes import c_int32, c_int64, c_void_p, c_float, POINTER, byref
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpipeinfer_hip.so")
+# the library built in-tree, unless PIPEINFER_LIB names another build of it
+LIB_PATH = os.environ.get("PIPEINFER_LIB") or os.path.join(_HERE, "libpipeinfer_hip.so")
 
 PI_OK, PI_CANCELLED = 0, 1
 PI_E_ARG, PI_E_SHAPE, PI_E_OOM, PI_E_SLOT_LIVE, PI_E_HIP, PI_E_STATE = -1, -2, -3, -4, -5, -6

@@ -12,7 +12,7 @@ using namespace pi;
 
 namespace {
 
-constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS a projection phase should take (more slices beat a fuller LDS)
+constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS the QKV phase should take (there a second slice beats a fuller LDS)
 constexpr size_t kProjLdsLimit = 150 * 1024;  // ... and may take where no split fits the budget (160 KiB; a little is static)
 constexpr unsigned long long kBarrierTimeoutTicks = 200000000ull;  // 2 s of the 100 MHz clock
 
@@ -42,7 +42,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
-  size_t lds_budget = kProjLdsBudget;  // what a projection phase's split aims to stay under (tuning hook)
+  size_t lds_budget = 0;  // tuning hook: what every projection phase's split aims to stay under (0: built-in per phase)
   size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
   int wdtype = PI_DTYPE_BF16;  // format of the weight matrices (cfg.dtype, or 8-bit)
   int kt32() const { return weight_tile_cols(wdtype) / 32; }  // 32-column tiles per weight tile
@@ -99,23 +99,44 @@ hipError_t dev_alloc(pi_model* m, T** p, size_t bytes, bool zero) {
   return e;
 }
 
-// Column slices for one projection: the smallest power of two that divides the tile count and
-// the grid, lets the phase's LDS needs for n tokens fit the budget and -- where the matrix has
-// fewer row blocks than the grid has workgroups -- gives every workgroup a row block, as long as
-// a slice keeps at least 16 tiles per row block.  0 = impossible.
+// Column slices for one projection phase (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head).  A split must
+// be a power of two that divides the tile count and the grid, keep the phase's LDS needs for n
+// tokens within reach and leave a slice at least 16 tiles per row block (fewer would starve the
+// ring).  Among those, measured on the 7B and 70B shapes:
+//  * the fewest slices whose staged activations fit the budget are best for the wide matrices
+//    (QKV, gate/up, LM head), which have several row blocks per workgroup anyway;
+//  * the output and down projections have about one row block per workgroup: unsliced, the
+//    workgroup's eight waves share that one row block and one wave reduces and finishes it
+//    alone at the very end of the phase.  Sliced so that a workgroup holds eight row blocks, every
+//    wave owns one and the eight finish side by side; that is worth more than the partial tiles
+//    that then cross slices through memory (3-5 us per 7B layer) -- for the down projection
+//    always, for the output projection from four tokens on;
+//  * a matrix with fewer row blocks than the grid has workgroups is sliced until every
+//    workgroup has a row block.
+// 0 = impossible.
 int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t budget) {
   const int ov = m->sk_override[phase];
+  const auto usable = [&](int sk, size_t cap) {
+    if (sk < 1 || sk > m->grid || sk > w.KT || w.KT % sk || m->grid % sk) return false;
+    const int gs = m->grid / sk;
+    return stage_proj_lds_bytes(n, m->kt32() * (w.KT / sk), (w.NRB + gs - 1) / gs) <= cap;
+  };
   int fits = 0;
   for (int sk = 1; sk <= m->grid && sk <= w.KT; sk *= 2) {
-    if (w.KT % sk || m->grid % sk) continue;
-    const int gs = m->grid / sk;
-    if (stage_proj_lds_bytes(n, m->kt32() * (w.KT / sk), (w.NRB + gs - 1) / gs) > budget) continue;
+    if (!usable(sk, budget)) continue;
     if (ov > sk) continue;  // an override asks for at least this many slices
     if (fits && w.KT / sk < 16) break;  // more slices would starve the ring
     fits = sk;
     if ((long)w.NRB * sk >= m->grid) break;
   }
   if (!fits && budget < kProjLdsLimit) return choose_sk(m, phase, w, n, kProjLdsLimit);
+  if (fits && !ov && (phase == 3 || (phase == 1 && n >= 4))) {
+    // one row block per wave: the largest split with at most eight row blocks per workgroup
+    int star = fits;
+    for (int sk = fits * 2; sk <= m->grid && (long)w.NRB * sk <= 8L * m->grid && w.KT / sk >= 16; sk *= 2)
+      if (usable(sk, budget)) star = sk;
+    fits = star;
+  }
   return fits;
 }
 
@@ -133,7 +154,10 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
   p->lds = 0;
   p->part_tiles = 1;
   for (int ph = 0; ph < 5; ++ph) {
-    const int sk = choose_sk(m, ph, *mats[ph], n, m->lds_budget);
+    // the QKV projection does better with a second slice than with more than 96 KiB of staged
+    // activations; the others take what LDS there is
+    const size_t budget = m->lds_budget ? m->lds_budget : (ph == 0 ? kProjLdsBudget : kProjLdsLimit);
+    const int sk = choose_sk(m, ph, *mats[ph], n, budget);
     if (sk == 0) return false;
     p->sk[ph] = sk;
     const int nt = mats[ph]->KT / sk;
@@ -458,7 +482,7 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
   }
   if (phase == 6) {
     if (s_k != 0 && (s_k < 16 || (size_t)s_k * 1024 > kProjLdsLimit)) return PI_E_ARG;
-    m->lds_budget = s_k ? (size_t)s_k * 1024 : kProjLdsBudget;
+    m->lds_budget = (size_t)s_k * 1024;
   } else {
     m->sk_override[phase] = s_k;
   }
@@ -474,7 +498,7 @@ int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
     if (e == hipSuccess) e = dev_alloc(m, &grown, 3 * tiles * 1024, false);
     if (e == hipSuccess) e = hipMemset(grown, 0xFF, 3 * tiles * 1024);
     if (e != hipSuccess) {
-      if (phase == 6) m->lds_budget = kProjLdsBudget;
+      if (phase == 6) m->lds_budget = 0;
       else m->sk_override[phase] = 0;
       return hip_status(e);
     }

@@ -139,7 +139,7 @@ def test_rollback_commits_path_and_frees_the_rest(shape_name):
         (np.array([20, 21, 22, 23]), [0, 1, 2]),           # linear chain, slots already in place
         (np.array([30, 25, 41, 33, 28]), [1, 3, 4]),       # scattered slots, path in the middle
         (np.array([40, 41, 42]), []),                      # nothing accepted (cancelled run)
-        (np.array([27, 26, 25, 24]), [3, 2, 0]),           # sources overlap destinations, reversed
+        (np.array([29, 28, 27, 26]), [3, 2, 0]),           # sources overlap destinations, reversed (kv_len is 26 by now)
     ]
     for slots, path in cases:
         n = len(slots)
