@@ -247,6 +247,19 @@ int32_t pi_verify_greedy(const int32_t* draft, const int32_t* parent, int32_t n,
                          int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
                          int32_t* result, void* stream);
 
+/* pi_verify_greedy for callers that cannot allocate: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, but the scratch
+ * (row maxima and the counter of finished rows, 132 bytes) lives in a 256-byte array that is part
+ * of the library's device code instead of memory allocated on first use: the call allocates
+ * nothing and frees nothing, on the device or through any library.  The limit is that of the
+ * other verification calls: n <= PI_MAX_BATCH rows (PI_E_SHAPE beyond; vocab <= 2^24).  Every
+ * call on a GPU uses that GPU's one array and two calls that overlap in time on one GPU race:
+ * issue them on one stream or order them with events.  (The first call on a device looks up the
+ * array's address; that is a query, not an allocation.)  Asynchronous. */
+int32_t pi_verify_greedy_noalloc(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                                 int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
+                                 int32_t* result, void* stream);
+
 /* The same for a run that builds on another run's speculation (Section "Continuous
  * Speculation": trees build on the previous trees, so a rejected speculation takes its
  * descendants with it), decided on the device so that runs can be queued back to back:

@@ -30,7 +30,7 @@ PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
-    "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_verify_greedy_chained", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
+    "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_verify_greedy_noalloc", "pi_verify_greedy_chained", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
     "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
     "pi_kvmeta_alloc", "pi_kvmeta_free", "pi_kvmeta_seq_acquire", "pi_kvmeta_seq_release", "pi_kvmeta_fill",
     "pi_kvmeta_place", "pi_kvmeta_seq_cp", "pi_kvmeta_seq_rm", "pi_kvmeta_accept", "pi_kvmeta_build_mask",
@@ -95,6 +95,8 @@ def lib():
                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_verify_greedy.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
                                        c_void_p, c_void_p]
+        L.pi_verify_greedy_noalloc.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+                                               c_void_p, c_void_p]
         L.pi_verify_greedy_chained.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_int32, c_int32, c_void_p, c_int32,
                                                c_void_p, c_void_p, c_void_p, c_void_p]
         L.pi_kv_rollback.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p]
@@ -355,6 +357,14 @@ def verify_greedy(draft, parent, n: int, logits, vocab: int, root_expected: int,
     st = lib().pi_verify_greedy(_ptr(draft), _ptr(parent), n, _ptr(logits), vocab, root_expected,
                                 _ptr(accepted_nodes), _ptr(result), _stream_handle(stream))
     return _check(st, "pi_verify_greedy")
+
+
+def verify_greedy_noalloc(draft, parent, n: int, logits, vocab: int, root_expected: int, accepted_nodes, result,
+                          stream=None) -> int:
+    """pi_verify_greedy for callers that cannot allocate (its scratch is a device array of the library)."""
+    st = lib().pi_verify_greedy_noalloc(_ptr(draft), _ptr(parent), n, _ptr(logits), vocab, root_expected,
+                                        _ptr(accepted_nodes), _ptr(result), _stream_handle(stream))
+    return _check(st, "pi_verify_greedy_noalloc")
 
 
 def verify_greedy_chained(draft, parent, n: int, logits, vocab: int, root_expected: int, prev_result, prev_n: int,

@@ -1,9 +1,20 @@
 // Kernels beside the stage kernel: greedy verification (argmax + tree walk), KV
 // commit/rollback, KV cell set/get.
+#include <mutex>
+
 #include "pi_internal.h"
 
 namespace pi {
 namespace {
+
+// Scratch of the verification entry point that allocates nothing: per logits row the largest value
+// and its index, and the counter by which the last block to finish is found.  One copy per GPU
+// the library runs on, held until the process ends.
+constexpr int kScratchBytes = 256;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static_assert(PI_MAX_BATCH * (sizeof(float) + sizeof(int32_t)) + sizeof(int) <= kScratchBytes, "scratch too small");
+
+__global__ void clear_counter_kernel(int* cnt) { *cnt = 0; }
 
 // ---- greedy verification -------------------------------------------------------------------
 // One block per logits row finds argmax (lowest id on ties); the last block to finish walks
@@ -245,3 +256,50 @@ hipError_t launch_kv_get(const void* k, const void* v, int kv_dtype, int n_kv_he
 }
 
 }  // namespace pi
+
+// The scratch array's address on each device, looked up once per device with that device current.
+// (In host code the array's name is only a handle for this lookup, never a device address.)
+namespace {
+constexpr int kMaxDevices = 16;
+struct ScratchAddr {
+  unsigned char* ptr = nullptr;
+  hipError_t err = hipSuccess;
+  bool looked_up = false;
+};
+ScratchAddr g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+}  // namespace
+
+extern "C" int32_t pi_verify_greedy_noalloc(const int32_t* draft, const int32_t* parent, int32_t n, const float* logits,
+                                            int32_t vocab, int32_t root_expected, int32_t* accepted_nodes,
+                                            int32_t* result, void* stream) {
+  using namespace pi;
+  if (!draft || !logits || !accepted_nodes || !result) return PI_E_ARG;
+  if (n < 1 || n > PI_MAX_BATCH || vocab < 1 || vocab > (1 << 24)) return PI_E_SHAPE;  // more rows than the scratch array holds
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return PI_E_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return PI_E_SHAPE;
+  ScratchAddr& sa = g_scratch[dev];
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!sa.looked_up) {
+      void* p = nullptr;
+      sa.err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      sa.ptr = (unsigned char*)p;
+      sa.looked_up = true;
+    }
+  }
+  if (sa.err != hipSuccess || !sa.ptr) return PI_E_HIP;
+  float* best_val = (float*)sa.ptr;
+  int32_t* best_idx = (int32_t*)(sa.ptr + PI_MAX_BATCH * sizeof(float));
+  int* cnt = (int*)(sa.ptr + PI_MAX_BATCH * (sizeof(float) + sizeof(int32_t)));
+  // the array keeps what the last call left: the counter must start at zero (a fill kernel, not a
+  // memset node, so that the call can be captured into a graph)
+  clear_counter_kernel<<<dim3(1), dim3(1), 0, (hipStream_t)stream>>>(cnt);
+  e = hipGetLastError();
+  if (e != hipSuccess) return PI_E_HIP;
+  e = launch_verify(draft, parent, n, logits, vocab, root_expected, nullptr, 0, nullptr, accepted_nodes, result, best_val,
+                    best_idx, cnt, (hipStream_t)stream);
+  return e == hipSuccess ? PI_OK : PI_E_HIP;
+}
