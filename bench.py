@@ -71,6 +71,132 @@ def cpu_baseline(shape, prefix_len, n, seed):
                                                                          shape.n_layers, full)}
 
 
+def time_forward(pi, torch, model, kv, run, n, layer_begin, layer_end, steps, warmup, shape):
+    """Mean HIP-event time (ms) of one pi_stage_forward over [layer_begin, layer_end); the run's cells are
+    discarded after every forward (outside the timed region)."""
+    last = layer_end == shape.n_layers
+    logits = torch.empty((n, shape.vocab), device="cuda") if last else None
+    hidden = torch.empty((n, shape.d_model), device="cuda") if not last else None
+    hin = torch.zeros((n, shape.d_model), device="cuda") if layer_begin > 0 else None
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for k in range(warmup + steps):
+        e = evs[k - warmup] if k >= warmup else None
+        if e:
+            e[0].record()
+        pi.stage_forward(model, kv, run, layer_begin, layer_end, hidden_in=hin, hidden_out=hidden, logits_out=logits,
+                         run_status=status)
+        if e:
+            e[1].record()
+        pi.kv_rollback(kv, run.slots, n)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, layer_end], status
+    return sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+
+
+def shape_leg(pi, torch, synth, gpu_loader, shape_name, prefixes, batches, seed, steps, warmup, slice_layers=0):
+    """Forward-only timing of another model shape: per (prefix, n) the forward time, the algorithmic
+    bytes and the fraction of the HBM peak; optionally also the first `slice_layers` layers alone
+    (one pipeline stage's share)."""
+    shape = synth.SHAPES[shape_name]
+    need = shape.n_layers * shape.layer_params * shape.bytes_per_weight * 1.08 + 4e9
+    free, _total = torch.cuda.mem_get_info()
+    if free < need:
+        return {"skipped": "needs %.0f GB of device memory, %.0f GB free" % (need / 1e9, free / 1e9)}
+    model = gpu_loader.load_model(shape, seed)
+    layer_bytes, lm_bytes = model.weight_bytes()
+    leg = {"shape": shape.name, "layers": shape.n_layers, "weights": shape.dtype, "runs": []}
+    try:
+        for T in prefixes:
+            kv = pi.KVCache(model, ((T + 64 + 15) // 16) * 16)
+            gpu_loader.prefill_kv_synthetic(kv, shape, seed, T)
+            for n in batches:
+                run = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(shape, seed, n, synth.T_DRAFT, salt=n))
+                ms = time_forward(pi, torch, model, kv, run, n, 0, shape.n_layers, steps, warmup, shape)
+                ab = algorithmic_bytes(shape, layer_bytes, lm_bytes, T, n)
+                rec = {"prefix": T, "n": n, "forward_ms": ms, "verified_tokens_per_s_forward_only": n / (ms * 1e-3),
+                       "per_layer_us": ms * 1e3 / (shape.n_layers + lm_bytes / layer_bytes),
+                       "algorithmic_GB": ab / 1e9, "achieved_GBps": ab / 1e9 / (ms * 1e-3),
+                       "frac_of_peak": ab / 1e9 / (ms * 1e-3) / HBM_PEAK_GBS}
+                if slice_layers:
+                    sms = time_forward(pi, torch, model, kv, run, n, 0, slice_layers, steps, warmup, shape)
+                    es = shape.bytes_per_weight
+                    sb = (slice_layers * layer_bytes + n * shape.d_model * es
+                          + slice_layers * (T + n) * 2 * shape.n_kv_heads * shape.head_dim * es)
+                    rec["slice"] = {"layers": slice_layers, "forward_ms": sms, "algorithmic_GB": sb / 1e9,
+                                    "achieved_GBps": sb / 1e9 / (sms * 1e-3), "frac_of_peak": sb / 1e9 / (sms * 1e-3) / HBM_PEAK_GBS}
+                leg["runs"].append(rec)
+            kv.free()
+    finally:
+        model.free()
+    return leg
+
+
+def cancellation_on_device_clock(pi, torch, np, model, kv, run, n, shape, layer_end, layers):
+    """Early Inference Cancellation timed on the device's own clock: a workgroup in the middle of
+    the grid raises the run's cancel word when it enters the gate/up phase of a chosen layer and
+    stamps the 100 MHz clock; workgroup 0 stamps every barrier it passes.  The run must stop at the
+    boundary that ends that layer (one layer at most after the signal)."""
+    cap = 5 * shape.n_layers + 8
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    last = layer_end == shape.n_layers
+    logits = torch.empty((n, shape.vocab), device="cuda") if last else None
+    hidden = torch.empty((n, shape.d_model), device="cuda") if not last else None
+    model.set_plan(5, 1)
+    trials = []
+    try:
+        for layer in layers:
+            flag.zero_()
+            model.raise_cancel(layer, 3)
+            pi.stage_forward(model, kv, run, 0, layer_end, hidden_out=hidden, logits_out=logits, cancel_flag=flag,
+                             run_status=status)
+            pi.kv_rollback(kv, run.slots, n)
+            torch.cuda.synchronize()
+            st = status.cpu().tolist()
+            tr = model.read_trace(cap).astype(np.int64)
+            rec = {"raised_in_layer": layer, "status": st[0], "layers_done": st[1]}
+            if st[0] == 1 and st[1] >= 1:
+                t_store, t_stop = int(tr[cap - 1]), int(tr[3 + 2 * (st[1] - 1)])   # boundary that ended layer layers_done - 1
+                t_layer0 = int(tr[3 + 2 * (st[1] - 2)]) if st[1] >= 2 else int(tr[1])
+                rec.update({"signal_to_stop_us": (t_stop - t_store) / 100.0, "layer_us": (t_stop - t_layer0) / 100.0,
+                            "layers_started_after_signal": st[1] - (layer + 1)})
+            trials.append(rec)
+    finally:
+        model.raise_cancel(-1, 3)
+        model.set_plan(5, 0)
+    ok = [t for t in trials if "signal_to_stop_us" in t]
+    return {"trials": len(trials), "stopped": len(ok),
+            "layers_started_after_signal_max": max((t["layers_started_after_signal"] for t in ok), default=None),
+            "signal_to_stop_us_mean": float(np.mean([t["signal_to_stop_us"] for t in ok])) if ok else None,
+            "signal_to_stop_us_max": float(np.max([t["signal_to_stop_us"] for t in ok])) if ok else None,
+            "signal_to_stop_layers_max": float(np.max([t["signal_to_stop_us"] / t["layer_us"] for t in ok])) if ok else None,
+            "signal": "cancel word stored by workgroup grid/2 on entering gate/up of the layer; clock: device, 100 MHz",
+            "per_trial": trials}
+
+
+def phase_timeline(pi, torch, np, model, kv, run, n, shape, layer):
+    """Per-workgroup timestamps of every phase of one layer (pi_debug_wgtrace), as min / mean / max
+    over the workgroups in microseconds from the first workgroup's entry into the phase."""
+    logits = torch.empty((n, shape.vocab), device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    rows = {}
+    for k, name in enumerate(["qkv", "attention", "o", "gate_up", "down"]):
+        model.wgtrace(layer * 8 + k)
+        for _ in range(3):
+            pi.stage_forward(model, kv, run, 0, shape.n_layers, logits_out=logits, run_status=status)
+            pi.kv_rollback(kv, run.slots, n)
+        torch.cuda.synchronize()
+        t = model.wgtrace(layer * 8 + k, read=True).astype(np.int64)
+        t = (t - t[:, 0].min()) / 100.0
+        f = lambda j: [round(float(t[:, j].min()), 1), round(float(t[:, j].mean()), 1), round(float(t[:, j].max()), 1)]
+        rows[name] = {"entered": f(0), "work_done": f(2)}
+        if k in (2, 4):
+            rows[name]["barrier_passed"] = f(5)
+    model.wgtrace(-1)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -87,6 +213,11 @@ def main():
     ap.add_argument("--no-continuous", action="store_true", help="skip the continuous-speculation generation loop")
     ap.add_argument("--no-c4", action="store_true", help="skip the eight-runs-half-cancelled workload")
     ap.add_argument("--no-w8", action="store_true", help="skip the same workload with 8-bit weight matrices")
+    ap.add_argument("--no-other-shapes", action="store_true",
+                    help="skip the 70B-shaped (full depth and 20-layer slice) and TinyLlama-shaped decode legs")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the bare streaming probe (hbm_ceiling_GBps)")
+    ap.add_argument("--phase-timeline", type=int, default=-1,
+                    help="print per-phase workgroup timestamps of this layer for every batch size and exit")
     ap.add_argument("--slice-layers", type=int, default=0,
                     help="also time a pipeline stage's share: the first this-many layers as one stage call")
     ap.add_argument("--calibrate-copy", type=int, default=0,
@@ -121,6 +252,15 @@ def main():
     kv = pi.KVCache(model, n_cells)
     gpu_loader.prefill_kv_synthetic(kv, shape, args.seed, T)
     layer_bytes, lm_bytes = model.weight_bytes()
+
+    if args.phase_timeline >= 0:
+        tl = {}
+        for n in batches:
+            run = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(shape, args.seed, n, synth.T_DRAFT, salt=n))
+            tl[str(n)] = phase_timeline(pi, torch, np, model, kv, run, n, shape, args.phase_timeline)
+        print(json.dumps({"phase_timeline_us": tl, "shape": shape.name, "prefix": T, "layer": args.phase_timeline,
+                          "columns": "min / mean / max over the 256 workgroups, from the first workgroup's entry into the phase"}))
+        return
 
     per_batch = {}
     for n in batches:
@@ -221,11 +361,16 @@ def main():
         pi.kv_rollback(kv, run.slots, n)
     torch.cuda.synchronize()
     layer_us = hb["per_layer_us"]
-    cancel = {"trials": 16, "cancelled": len(lat),
+    cancel = {"trials": 0 if args.no_cancel else 16, "cancelled": len(lat),
               "latency_us_mean": float(np.mean(lat)) if lat else None,
               "latency_us_max": float(np.max(lat)) if lat else None,
               "latency_layers_max": float(np.max(lat)) / layer_us if lat else None,
-              "layers_done": stopped_at}
+              "layers_done": stopped_at,
+              "clock": "host (flag written -> status seen through mapped memory: includes PCIe visibility and host polling)"}
+    if not args.no_cancel:
+        cancel["device_clock"] = cancellation_on_device_clock(
+            pi, torch, np, model, kv, run, n, shape, shape.n_layers,
+            sorted(set(int(x) for x in np.linspace(0, shape.n_layers - 2, 8))))
 
     # Several runs per weight pass: eight 4-token speculation trees under the shared prefix (the
     # shape of the paper's continuous speculation: many small runs in flight), evaluated as eight
@@ -509,6 +654,23 @@ def main():
             kv8.free()
             m8.free()
 
+    # The other model shapes of the workload list, forward only: the 70B-shaped target (80 layers,
+    # 2048 prefix cells, batches of 1 / 4 / 8 / 16, and its first 20 layers alone: one pipeline
+    # stage's share) and single-token decode steps of the TinyLlama-shaped draft model.
+    other = None
+    if not args.no_other_shapes and shape.name == "llama7b":
+        kv.free()
+        model.free()
+        model = kv = None
+        few = max(3, min(10, args.steps // 5))
+        other = {"tinyllama_decode": shape_leg(pi, torch, synth, gpu_loader, "tinyllama", (128, 512, 2048), (1,),
+                                               args.seed, max(few, 20), 5),
+                 "llama70b": shape_leg(pi, torch, synth, gpu_loader, "llama70b", (2048,), (1, 4, 8, 16), args.seed, few, 2,
+                                       slice_layers=20)}
+    ceiling = None
+    if not args.no_ceiling:
+        ceiling = pi.binding.stream_probe(2 << 30, 5)
+
     out = {
         "metric": "verified tokens/sec per spec batch (1/4/8 tok) + achieved HBM GB/s vs peak",
         "value": hb["verified_tokens_per_s"], "unit": "verified tokens/s (n=%s)" % head,
@@ -527,6 +689,8 @@ def main():
         "kv_metadata": kvmeta,
         "continuous_speculation": contin,
         "quantised_weights": w8,
+        "other_shapes": other,
+        "hbm_ceiling_GBps": ceiling,
         "roofline": {"bound": "hbm", "achieved": hb["achieved_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": hb["frac_of_peak"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get((shape.name, T, int(head))),

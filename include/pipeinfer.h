@@ -443,6 +443,19 @@ int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64
  * barrier of the last run: [0] run latch, [1] stage input ready, then two per layer (after the
  * output projection; layer boundary).  count <= 5 * n_layers + 8.  Blocking. */
 int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count);
+/* Measurement aid for the latency of Early Inference Cancellation on the device clock: while
+ * barrier tracing is on (pi_debug_set_plan phase 5), later forwards raise the cancel word of their
+ * first run THEMSELVES -- a workgroup in the middle of the grid stores 1 into it when it enters
+ * phase `phase` (0 QKV, 2 O, 3 gate/up, 4 down) of layer `layer`, then stamps the 100 MHz clock
+ * into entry 5 * n_layers + 7 of the trace -- so the store comes from another compute unit than the
+ * one that probes the word, at a known moment of a known layer.  The run must then stop at the
+ * boundary that ends this layer: layers_done == layer + 1.  layer < 0 switches it off. */
+int32_t pi_debug_raise_cancel(pi_model* m, int32_t layer, int32_t phase);
+/* What a launch of the forward's shape (one workgroup of 8 waves per compute unit, rings of eight
+ * 128-bit non-temporal loads per lane) reads per second when it does nothing else: allocates
+ * `bytes` (>= 64 MiB) of device memory, streams it reps + 1 times and returns the best rate in
+ * GB/s.  Blocking; frees what it allocated. */
+int32_t pi_debug_stream_probe(int64_t bytes, int32_t reps, double* gbps);
 /* Debug hook: per-workgroup timestamps of one phase.  `key` = layer * 8 + phase (0 QKV, 1
  * attention, 2 O, 3 gate/up, 4 down) selects the phase later runs record (-1: none).  With
  * dst_host non-null, first copies the last recording to the host: grid x 8 values of the 100 MHz

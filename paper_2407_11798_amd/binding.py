@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import c_int32, c_int64, c_void_p, c_float, POINTER, byref
+from ctypes import c_int32, c_int64, c_void_p, c_float, c_double, POINTER, byref
 
 import numpy as np
 
@@ -31,7 +31,7 @@ EXPORTS = [
     "pi_model_load", "pi_model_set_tensor", "pi_model_free", "pi_model_weight_bytes", "pi_kv_alloc",
     "pi_kv_free", "pi_kv_set_cells", "pi_kv_get_cells", "pi_kv_set_len", "pi_kv_len", "pi_kv_raw",
     "pi_stage_forward", "pi_stage_forward_multi", "pi_verify_greedy", "pi_verify_greedy_noalloc", "pi_verify_greedy_chained", "pi_kv_rollback", "pi_strerror", "pi_debug_set_plan",
-    "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace",
+    "pi_debug_read_scratch", "pi_debug_read_trace", "pi_debug_wgtrace", "pi_debug_raise_cancel", "pi_debug_stream_probe",
     "pi_kvmeta_alloc", "pi_kvmeta_free", "pi_kvmeta_seq_acquire", "pi_kvmeta_seq_release", "pi_kvmeta_fill",
     "pi_kvmeta_place", "pi_kvmeta_seq_cp", "pi_kvmeta_seq_rm", "pi_kvmeta_accept", "pi_kvmeta_build_mask",
     "pi_kvmeta_compact", "pi_kvmeta_read",
@@ -103,6 +103,8 @@ def lib():
         L.pi_strerror.argtypes = [c_int32]
         L.pi_strerror.restype = ctypes.c_char_p
         L.pi_debug_set_plan.argtypes = [c_void_p, c_int32, c_int32]
+        L.pi_debug_raise_cancel.argtypes = [c_void_p, c_int32, c_int32]
+        L.pi_debug_stream_probe.argtypes = [c_int64, c_int32, POINTER(c_double)]
         L.pi_debug_read_trace.argtypes = [c_void_p, c_void_p, c_int32]
         L.pi_debug_read_scratch.argtypes = [c_void_p, c_int32, c_void_p, c_int64]
         c_uint32 = ctypes.c_uint32
@@ -120,7 +122,6 @@ def lib():
                                            c_void_p, c_void_p]
         L.pi_kvmeta_compact.argtypes = [c_void_p, c_void_p, c_int32, c_void_p, c_void_p]
         L.pi_kvmeta_read.argtypes = [c_void_p, c_void_p, c_void_p]
-        c_double = ctypes.c_double
         L.pi_mapped_device_pointer.argtypes = [c_void_p, POINTER(c_void_p)]
         L.pi_sched_create.argtypes = [c_double, c_double, c_double, POINTER(c_void_p)]
         L.pi_sched_free.argtypes = [c_void_p]
@@ -208,6 +209,16 @@ class Model:
 
     def set_plan(self, phase, s_k=0):
         _check(lib().pi_debug_set_plan(self.handle, phase, s_k), "pi_debug_set_plan")
+
+    def raise_cancel(self, layer: int, phase: int = 3):
+        _check(lib().pi_debug_raise_cancel(self.handle, layer, phase), "pi_debug_raise_cancel")
+
+    def wgtrace(self, key: int, read: bool = False, grid: int = 256):
+        """Select the phase (layer * 8 + kind) later runs record; with read=True first return the last
+        recording as [grid][8] clock values."""
+        buf = np.zeros(grid * 8, dtype=np.uint64) if read else None
+        _check(lib().pi_debug_wgtrace(self.handle, key, c_void_p(buf.ctypes.data) if read else None), "pi_debug_wgtrace")
+        return None if buf is None else buf.reshape(grid, 8)
 
     def read_trace(self, count: int):
         out = np.zeros(count, dtype=np.uint64)
@@ -379,6 +390,13 @@ def kv_rollback(kv: KVCache, slots, n: int, accepted_nodes=None, result=None, st
     st = lib().pi_kv_rollback(kv.handle, _ptr(slots), n, _ptr(accepted_nodes), _ptr(result),
                               _stream_handle(stream))
     return _check(st, "pi_kv_rollback")
+
+
+def stream_probe(nbytes: int = 2 << 30, reps: int = 5) -> float:
+    """GB/s a bare streaming read of the forward's launch shape reaches (pi_debug_stream_probe)."""
+    g = c_double()
+    _check(lib().pi_debug_stream_probe(nbytes, reps, byref(g)), "pi_debug_stream_probe")
+    return g.value
 
 
 def seq_bits(seqs) -> int:

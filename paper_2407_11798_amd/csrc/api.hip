@@ -36,6 +36,7 @@ struct pi_model {
   bool trace_on = false;
   unsigned long long* wgtrace = nullptr;
   int wgtrace_layer = -1;
+  int raise_key = -1;  // debug: phase (layer * 8 + kind) at which the kernel raises the run's cancel word itself
   int grid = 0;  // workgroups of the stage kernel = compute units
   unsigned epoch = 0;  // grid barriers reserved by earlier launches
   size_t configured_lds[17] = {0};  // per ring size: dynamic LDS the kernel was configured for
@@ -467,6 +468,18 @@ int32_t pi_debug_wgtrace(pi_model* m, int32_t layer, uint64_t* dst_host) {
   return hip_status(e);
 }
 
+int32_t pi_debug_raise_cancel(pi_model* m, int32_t layer, int32_t phase) {
+  if (!m || phase < 0 || phase > 4 || phase == 1) return PI_E_ARG;
+  if (layer >= m->cfg.n_layers) return PI_E_ARG;
+  m->raise_key = layer < 0 ? -1 : layer * 8 + phase;
+  return PI_OK;
+}
+
+int32_t pi_debug_stream_probe(int64_t bytes, int32_t reps, double* gbps) {
+  if (bytes < (1 << 26) || reps < 1 || reps > 1000 || !gbps) return PI_E_ARG;
+  return hip_status(stream_probe((size_t)bytes, reps, gbps));
+}
+
 int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
   if (!m || !dst_host || count < 0 || count > m->trace_cap) return PI_E_ARG;
   hipError_t e = hipDeviceSynchronize();
@@ -796,6 +809,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.trace_cap = m->trace_cap;
   a.wgtrace = m->wgtrace_layer >= 0 ? m->wgtrace : nullptr;
   a.wgtrace_layer = m->wgtrace_layer;
+  a.raise_key = m->trace_on ? m->raise_key : -1;
   return hip_status(launch_stage_in_order(a, m->wdtype, ring, m->grid, sp.lds, (hipStream_t)stream));
 }
 

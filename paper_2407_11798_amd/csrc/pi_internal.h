@@ -137,6 +137,9 @@ struct StageArgs {
   int trace_cap;
   unsigned long long* wgtrace;  // optional debug: [grid][8] timestamps of workgroup events in one layer
   int wgtrace_layer;
+  // optional debug: a workgroup in the middle of the grid raises the first run's cancel word itself when
+  // it enters phase `raise_key` (layer * 8 + phase kind) and stamps the clock into trace[trace_cap - 1]
+  int raise_key;
   // rarely read (workgroup 0, at layer boundaries), so kept behind everything the phases use
   int32_t* group_status;             // [n_groups][2] {status, layers_done} per run, or null
   int n_groups;                      // runs sharing the micro-batch
@@ -161,6 +164,7 @@ size_t stage_proj_lds_bytes(int n, int nt, int r_max);  // nt in 32-column tiles
 int stage_ring_size(int wdtype, int min_nt);
 hipError_t stage_configure(int wdtype, int ring, size_t max_lds, int* max_blocks_per_cu);
 hipError_t launch_stage(const StageArgs& a, int wdtype, int ring, int grid, size_t lds, hipStream_t s);
+hipError_t stream_probe(size_t bytes, int reps, double* gbps);
 hipError_t launch_verify(const int32_t* draft, const int32_t* parent, int n, const float* logits,
                          int vocab, int root_expected, const int32_t* prev_result, int prev_n,
                          const int32_t* run_status, int32_t* accepted, int32_t* result,

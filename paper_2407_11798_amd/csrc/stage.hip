@@ -1567,6 +1567,13 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     }
     e.N = M.N;
     wg_mark(A, l * 8 + k, 0);
+    if (__builtin_expect(A.raise_key == l * 8 + k, 0) && A.cancel_flags && A.trace && blockIdx.x == gridDim.x / 2 &&
+        threadIdx.x == 0) {
+      // measurement aid: the cancellation signal raised from another compute unit, on the device clock
+      __hip_atomic_store((int32_t*)A.cancel_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      wave_drain();
+      A.trace[A.trace_cap - 1] = wall_clock64();
+    }
     proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
                        has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
                        /*poll_x=*/k == 2 || k == 4, /*kind=*/k);
@@ -1638,6 +1645,66 @@ hipError_t stage_configure(int dtype, int ring, size_t max_lds, int* max_blocks_
   hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
   if (e != hipSuccess) return e;
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(max_blocks_per_cu, fn, kStageThreads, max_lds);
+}
+
+// ---- read-bandwidth probe --------------------------------------------------------------------
+// What this chip delivers to a launch of the stage kernel's shape that does nothing but stream: one
+// workgroup of 8 waves per compute unit, each wave reading its own contiguous range of 1 KiB tiles
+// with a ring of eight 128-bit non-temporal loads per lane and folding them into a checksum.
+namespace {
+__global__ void __launch_bounds__(kStageThreads, 1) stream_probe_kernel(const u32x4* __restrict__ w, long tiles_per_wave,
+                                                                      unsigned* sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const u32x4* p = w + ((size_t)(blockIdx.x * kWaves + wave) * tiles_per_wave) * 64 + lane;
+  u32x4 acc = {0, 0, 0, 0};
+  for (long i = 0; i < tiles_per_wave; i += 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + (size_t)(i + j) * 64);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= v[j];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[0] = 1;  // keeps the loads alive
+}
+}  // namespace
+
+hipError_t stream_probe(size_t bytes, int reps, double* gbps) {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return e;
+  const int grid = prop.multiProcessorCount;
+  const size_t per_wave = bytes / ((size_t)grid * kWaves) / 8192 * 8;  // tiles per wave, a multiple of the ring
+  if (per_wave == 0) return hipErrorInvalidValue;
+  const size_t used = per_wave * 1024 * grid * kWaves;
+  void* buf = nullptr;
+  unsigned* sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  e = hipMalloc(&buf, used);
+  if (e == hipSuccess) e = hipMalloc((void**)&sink, 64);
+  if (e == hipSuccess) e = hipMemset(buf, 1, used);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  float best_ms = 0.0f;
+  for (int r = 0; e == hipSuccess && r < reps + 1; ++r) {  // the first launch warms up
+    e = hipEventRecord(e0, nullptr);
+    if (e == hipSuccess) {
+      stream_probe_kernel<<<dim3((unsigned)grid), dim3(kStageThreads), 0, nullptr>>>((const u32x4*)buf, (long)per_wave, sink);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (r > 0 && (best_ms == 0.0f || ms < best_ms)) best_ms = ms;
+  }
+  if (e == hipSuccess && gbps) *gbps = (double)used / 1e9 / ((double)best_ms * 1e-3);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (sink) (void)hipFree(sink);
+  if (buf) (void)hipFree(buf);
+  return e;
 }
 
 hipError_t launch_stage(const StageArgs& a, int dtype, int ring, int grid, size_t lds, hipStream_t s) {

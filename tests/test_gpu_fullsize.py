@@ -504,9 +504,62 @@ def test_llama70b_full_depth_matches_oracle():
             pi.kv_rollback(kv, run.slots, n)
         torch.cuda.synchronize()
         assert len(kv) == T
+        # Early Inference Cancellation on a 20-layer stage of this shape: the signal is raised from
+        # another compute unit in the middle of a layer and the stage stops at that layer's end
+        _cancel_raised_on_the_device(m, kv, sh, T, 8, 20, (0, 7, 18))
     finally:
         kv.free()
         m.free()
+
+
+def _cancel_raised_on_the_device(m, kv, sh, T, n, layer_end, layers):
+    """A workgroup in the middle of the grid stores the run's cancel word when it enters the gate/up
+    phase of `layer` (pi_debug_raise_cancel): the run must stop at the boundary that ends this very
+    layer -- no further layer starts after the signal -- and the stop must come within one layer's
+    time of the store on the device's own clock."""
+    cap = 5 * sh.n_layers + 8
+    toks = synth.tokens_host(sh, 0, n, synth.T_DRAFT, salt=n)
+    run = gpu_loader.make_run(synth.linear_run(n, T), toks)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    last = layer_end == sh.n_layers
+    logits = torch.full((n, sh.vocab), 7.0, device="cuda") if last else None
+    hidden = torch.full((n, sh.d_model), 7.0, device="cuda") if not last else None
+    snapshot_len = len(kv)
+    m.set_plan(5, 1)
+    try:
+        for layer in layers:
+            flag.zero_()
+            m.raise_cancel(layer, 3)
+            pi.stage_forward(m, kv, run, 0, layer_end, hidden_out=hidden, logits_out=logits, cancel_flag=flag,
+                             run_status=status)
+            pi.kv_rollback(kv, run.slots, n)
+            torch.cuda.synchronize()
+            assert status.cpu().tolist() == [pi.PI_CANCELLED, layer + 1], (layer, status.cpu().tolist())
+            out = logits if last else hidden
+            assert float(out.min()) == 7.0 and float(out.max()) == 7.0          # outputs untouched
+            tr = m.read_trace(cap).astype(np.int64)
+            t_store, t_stop = int(tr[cap - 1]), int(tr[3 + 2 * layer])
+            t_prev = int(tr[3 + 2 * (layer - 1)]) if layer > 0 else int(tr[1])
+            assert t_prev < t_store < t_stop                                     # raised inside the layer it stopped
+            assert t_stop - t_store <= t_stop - t_prev                           # within one layer's time
+            print("cancel raised in layer %d: stop %.1f us after the signal (the layer took %.1f us)"
+                  % (layer, (t_stop - t_store) / 100.0, (t_stop - t_prev) / 100.0), flush=True)
+    finally:
+        m.raise_cancel(-1, 3)
+        m.set_plan(5, 0)
+    assert len(kv) == snapshot_len
+
+
+def test_llama7b_cancel_raised_on_the_device_stops_at_the_end_of_the_layer(llama7b):
+    sh, m = llama7b
+    T = 512
+    kv = pi.KVCache(m, T + 64)
+    gpu_loader.prefill_kv_synthetic(kv, sh, 0, T)
+    snapshot = kv.raw().copy()
+    _cancel_raised_on_the_device(m, kv, sh, T, 8, sh.n_layers, (0, 1, 13, 30))
+    assert np.array_equal(kv.raw(), snapshot)                                    # as if the runs had never started
+    kv.free()
 
 
 def test_llama70b_shaped_stage_slice_properties():
