@@ -176,24 +176,24 @@ def cancellation_on_device_clock(pi, torch, np, model, kv, run, n, shape, layer_
 
 
 def phase_timeline(pi, torch, np, model, kv, run, n, shape, layer):
-    """Per-workgroup timestamps of every phase of one layer (pi_debug_wgtrace), as min / mean / max
-    over the workgroups in microseconds from the first workgroup's entry into the phase."""
+    """Per-workgroup timestamps of the five phases of one layer (pi_debug_wgtrace), all from one
+    forward, as min / mean / max over the workgroups in microseconds from the moment the first
+    workgroup entered the layer's QKV phase."""
     logits = torch.empty((n, shape.vocab), device="cuda")
     status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    model.wgtrace(layer)
+    for _ in range(3):
+        pi.stage_forward(model, kv, run, 0, shape.n_layers, logits_out=logits, run_status=status)
+        pi.kv_rollback(kv, run.slots, n)
+    torch.cuda.synchronize()
+    t = model.wgtrace(-1, read=True).astype(np.int64)
+    t = (t - t[:, 0, 0].min()) / 100.0
     rows = {}
     for k, name in enumerate(["qkv", "attention", "o", "gate_up", "down"]):
-        model.wgtrace(layer * 8 + k)
-        for _ in range(3):
-            pi.stage_forward(model, kv, run, 0, shape.n_layers, logits_out=logits, run_status=status)
-            pi.kv_rollback(kv, run.slots, n)
-        torch.cuda.synchronize()
-        t = model.wgtrace(layer * 8 + k, read=True).astype(np.int64)
-        t = (t - t[:, 0].min()) / 100.0
-        f = lambda j: [round(float(t[:, j].min()), 1), round(float(t[:, j].mean()), 1), round(float(t[:, j].max()), 1)]
+        f = lambda j: [round(float(t[:, k, j].min()), 1), round(float(t[:, k, j].mean()), 1), round(float(t[:, k, j].max()), 1)]
         rows[name] = {"entered": f(0), "work_done": f(2)}
         if k in (2, 4):
             rows[name]["barrier_passed"] = f(5)
-    model.wgtrace(-1)
     return rows
 
 

@@ -456,12 +456,13 @@ int32_t pi_debug_raise_cancel(pi_model* m, int32_t layer, int32_t phase);
  * `bytes` (>= 64 MiB) of device memory, streams it reps + 1 times and returns the best rate in
  * GB/s.  Blocking; frees what it allocated. */
 int32_t pi_debug_stream_probe(int64_t bytes, int32_t reps, double* gbps);
-/* Debug hook: per-workgroup timestamps of one phase.  `key` = layer * 8 + phase (0 QKV, 1
- * attention, 2 O, 3 gate/up, 4 down) selects the phase later runs record (-1: none).  With
- * dst_host non-null, first copies the last recording to the host: grid x 8 values of the 100 MHz
- * clock per workgroup: [0] phase start, [1] inputs staged, [2] wave 0 done streaming, [3] before
- * the barrier, [4] workgroup arrived at the barrier, [5] barrier passed.  Blocking. */
-int32_t pi_debug_wgtrace(pi_model* m, int32_t key, uint64_t* dst_host);
+/* Debug hook: per-workgroup timestamps of the five phases of one layer.  `layer` selects the layer
+ * later runs record (-1: none).  With dst_host non-null, first copies the last recording to the
+ * host: grid x 5 x 8 values of the 100 MHz clock, per workgroup and phase (0 QKV, 1 attention, 2 O,
+ * 3 gate/up, 4 down): [0] phase entered, [2] the phase's work done (stores settled), [3] before
+ * the barrier, [4] workgroup arrived at the barrier, [5] barrier passed (phases 2 and 4 end in a
+ * barrier; the others hand over through the data).  Blocking. */
+int32_t pi_debug_wgtrace(pi_model* m, int32_t layer, uint64_t* dst_host);
 
 #ifdef __cplusplus
 }

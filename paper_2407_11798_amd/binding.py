@@ -213,12 +213,12 @@ class Model:
     def raise_cancel(self, layer: int, phase: int = 3):
         _check(lib().pi_debug_raise_cancel(self.handle, layer, phase), "pi_debug_raise_cancel")
 
-    def wgtrace(self, key: int, read: bool = False, grid: int = 256):
-        """Select the phase (layer * 8 + kind) later runs record; with read=True first return the last
-        recording as [grid][8] clock values."""
-        buf = np.zeros(grid * 8, dtype=np.uint64) if read else None
-        _check(lib().pi_debug_wgtrace(self.handle, key, c_void_p(buf.ctypes.data) if read else None), "pi_debug_wgtrace")
-        return None if buf is None else buf.reshape(grid, 8)
+    def wgtrace(self, layer: int, read: bool = False, grid: int = 256):
+        """Select the layer whose phases later runs record (-1: none); with read=True first return the
+        last recording as [grid][5 phases][8] clock values."""
+        buf = np.zeros(grid * 40, dtype=np.uint64) if read else None
+        _check(lib().pi_debug_wgtrace(self.handle, layer, c_void_p(buf.ctypes.data) if read else None), "pi_debug_wgtrace")
+        return None if buf is None else buf.reshape(grid, 5, 8)
 
     def read_trace(self, count: int):
         out = np.zeros(count, dtype=np.uint64)

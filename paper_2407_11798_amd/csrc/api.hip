@@ -322,7 +322,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (e == hipSuccess) e = dev_alloc(m, &m->sync, sizeof(StageSync), true);
   m->trace_cap = 5 * c.n_layers + 8;
   if (e == hipSuccess) e = dev_alloc(m, &m->trace, (size_t)m->trace_cap * sizeof(unsigned long long), true);
-  if (e == hipSuccess) e = dev_alloc(m, &m->wgtrace, (size_t)1024 * 8 * sizeof(unsigned long long), true);
+  if (e == hipSuccess) e = dev_alloc(m, &m->wgtrace, (size_t)kMaxGrid * 40 * sizeof(unsigned long long), true);
   if (e == hipSuccess) {
     std::vector<LayerDev> ld(c.n_layers);
     auto md = [](const PackedMat& p) {
@@ -464,7 +464,7 @@ int32_t pi_debug_wgtrace(pi_model* m, int32_t layer, uint64_t* dst_host) {
   m->wgtrace_layer = layer;
   if (!dst_host) return PI_OK;
   hipError_t e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = hipMemcpy(dst_host, m->wgtrace, (size_t)m->grid * 8 * sizeof(uint64_t), hipMemcpyDeviceToHost);
+  if (e == hipSuccess) e = hipMemcpy(dst_host, m->wgtrace, (size_t)m->grid * 40 * sizeof(uint64_t), hipMemcpyDeviceToHost);
   return hip_status(e);
 }
 

@@ -135,7 +135,7 @@ struct StageArgs {
   unsigned epoch_base;               // barriers used by earlier launches on this model
   unsigned long long* trace;  // optional: 100 MHz timestamps, one per barrier passed by workgroup 0
   int trace_cap;
-  unsigned long long* wgtrace;  // optional debug: [grid][8] timestamps of workgroup events in one layer
+  unsigned long long* wgtrace;  // optional debug: [grid][5 phases][8] timestamps of workgroup events in one layer
   int wgtrace_layer;
   // optional debug: a workgroup in the middle of the grid raises the first run's cancel word itself when
   // it enters phase `raise_key` (layer * 8 + phase kind) and stamps the clock into trace[trace_cap - 1]

@@ -35,13 +35,8 @@
 #pragma STDC FP_CONTRACT OFF
 #endif
 
-#ifdef __HIP_DEVICE_COMPILE__
 #define SYNTH_FMA(a, b, c) __builtin_fma((a), (b), (c))
 #define SYNTH_SQRT(a) __builtin_sqrt((a))
-#else
-#define SYNTH_FMA(a, b, c) __builtin_fma((a), (b), (c))
-#define SYNTH_SQRT(a) __builtin_sqrt((a))
-#endif
 
 SYNTH_FN uint64_t synth_mix(uint64_t x) {
   x += 0x9E3779B97F4A7C15ull;
