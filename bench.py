@@ -620,7 +620,7 @@ def main():
     w8 = None
     if not args.no_w8 and shape.weight_format == "native":
         w8 = {}
-        for suffix in ("_w8", "_w4"):
+        for suffix in ("_w8", "_w4", "_w4b"):
             if shape.name + suffix not in synth.SHAPES:
                 continue
             sh8 = synth.SHAPES[shape.name + suffix]
@@ -628,7 +628,8 @@ def main():
             kv8 = pi.KVCache(m8, n_cells)
             gpu_loader.prefill_kv_synthetic(kv8, sh8, args.seed, T)
             lb8, lm8 = m8.weight_bytes()
-            leg = {"weights": "%s x 2^%d" % ({"fp8": "fp8-e4m3", "fp4": "fp4-e2m1"}[sh8.weight_format], sh8.weight_scale_exp2),
+            leg = {"weights": "fp4-e2m1, one power-of-two scale per 32 columns of a row" if sh8.weight_format == "fp4b" else
+                   "%s x 2^%d" % ({"fp8": "fp8-e4m3", "fp4": "fp4-e2m1"}[sh8.weight_format], sh8.weight_scale_exp2),
                    "per_batch": {}}
             for n in batches:
                 run8 = gpu_loader.make_run(synth.linear_run(n, T), synth.tokens_host(sh8, args.seed, n, synth.T_DRAFT, salt=n))

@@ -60,6 +60,9 @@ extern "C" {
 #define PI_DTYPE_FP4_E2M1 3 /* weight matrices only: 4-bit floats, sign, 2 exponent bits (bias 1), 1 mantissa
                              * bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives (the OCP FP4 E2M1 format);
                              * two weights per byte, the lower-numbered column in the low nibble */
+#define PI_DTYPE_FP4_E2M1_B32 4 /* weight matrices only: FP4 E2M1 nibbles as above with one power-of-two scale
+                                * per 32 consecutive columns of a row, stored as a byte: weight = e2m1(nibble) *
+                                * 2^(scale byte - 127), scale byte in 1 .. 254 (4.25 bits per weight) */
 #define PI_LOC_HOST 0
 #define PI_LOC_DEVICE 1
 
@@ -100,7 +103,11 @@ typedef struct pi_kv pi_kv;
  * inside the projection kernels: weight = e4m3(byte) * 2^weight_scale_exp2 (one power-of-two
  * scale for the whole model; -32 <= weight_scale_exp2 <= 32).  With weight_dtype
  * PI_DTYPE_FP4_E2M1 they are stored and streamed at half a byte per weight: weight =
- * e2m1(nibble) * 2^weight_scale_exp2.  Everything else (activations, embedding rows, KV cache,
+ * e2m1(nibble) * 2^weight_scale_exp2.  With weight_dtype PI_DTYPE_FP4_E2M1_B32 every block of 32
+ * consecutive columns of a matrix row has a scale of its own (weight = e2m1(nibble) * 2^(scale
+ * byte - 127); weight_scale_exp2 must be 0): the block formats of the paper's model files, in a
+ * layout of our own; the scale bytes travel beside the tiles and are streamed with them.
+ * Everything else (activations, embedding rows, KV cache,
  * accumulation) is as in a bf16 model.  weight_dtype 0 with dtype PI_DTYPE_BF16 is read as
  * "same as dtype". */
 typedef struct {
@@ -108,7 +115,8 @@ typedef struct {
   float rms_eps, rope_base;
   int32_t dtype;   /* PI_DTYPE_F32 | PI_DTYPE_BF16 */
   int32_t max_pos; /* positions must be < max_pos */
-  int32_t weight_dtype;      /* 0 or == dtype: matrices in `dtype`; PI_DTYPE_FP8_E4M3 / PI_DTYPE_FP4_E2M1 (bf16 models only) */
+  int32_t weight_dtype;      /* 0 or == dtype: matrices in `dtype`; PI_DTYPE_FP8_E4M3 / PI_DTYPE_FP4_E2M1 /
+                              * PI_DTYPE_FP4_E2M1_B32 (bf16 models only) */
   int32_t weight_scale_exp2; /* used with the 8-bit and 4-bit formats */
 } pi_model_config;
 
@@ -122,8 +130,10 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out);
  * (PI_DTYPE_F32: float; PI_DTYPE_BF16: 16-bit bf16 patterns) at `src_loc` (host or device).
  * Matrices must come in the model's dtype or in fp32 (rounded to bf16, nearest-even, for
  * a bf16 model); the matrices of a model with 8-bit or 4-bit weights must come in that format
- * (PI_DTYPE_FP8_E4M3: [out][in] bytes; PI_DTYPE_FP4_E2M1: [out][in/2] bytes; the library does
- * not quantise; the embedding table still comes in bf16 or fp32);
+ * (PI_DTYPE_FP8_E4M3: [out][in] bytes; PI_DTYPE_FP4_E2M1: [out][in/2] bytes;
+ * PI_DTYPE_FP4_E2M1_B32: [out][in/2] code bytes followed at once by [out][ceil(in/32)] scale
+ * bytes in the same buffer; the library does not quantise; the embedding table still comes in
+ * bf16 or fp32);
  * gains must be fp32.  `layer` is ignored for the three global tensors.
  * The tensor is repacked into the internal layout; `src` may be reused after return.
  * Blocking. */

@@ -52,6 +52,28 @@ def dequantise_fp4(packed: np.ndarray, scale_exp2: int) -> np.ndarray:
     return (out * 2.0 ** scale_exp2).astype(np.float32)
 
 
+def dequantise_fp4_blocks(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """Block-scaled 4-bit weights as the model defines them: codes[r][j] holds columns 2j (low
+    nibble) and 2j+1 (high nibble) of row r as FP4 E2M1 codes; scales[r][b] belongs to columns
+    32b .. 32b+31 of row r; weight = e2m1(code) * 2^(scale - 127)."""
+    rows, half = codes.shape
+    out = np.empty((rows, 2 * half), dtype=np.float64)
+    out[:, 0::2] = E2M1[codes & 0xF]
+    out[:, 1::2] = E2M1[codes >> 4]
+    per_col = np.repeat(scales.astype(np.int64), 32, axis=1)[:, :2 * half]
+    return (out * np.exp2((per_col - 127).astype(np.float64))).astype(np.float32)
+
+
+def dequantise(shape, kind: int, t: np.ndarray) -> np.ndarray:
+    """A stored tensor of `shape` as the values the model defines (quantised matrices decoded)."""
+    if t.dtype != np.uint8:
+        return t
+    if shape.weight_format == "fp4b":
+        rows, cols = synth.tensor_shape(shape, kind)
+        return dequantise_fp4_blocks(*synth.split_fp4b(t, rows, cols))
+    return (dequantise_fp4 if shape.weight_format == "fp4" else dequantise_fp8)(t, shape.weight_scale_exp2)
+
+
 def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
                     cache: bool = True) -> OracleModel:
     """Weights are regenerated from the seed when asked for; `cache` keeps them (small models)."""
@@ -61,9 +83,7 @@ def model_from_seed(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0,
         key = (name, layer)
         if key in store:
             return store[key]
-        t = synth.weight_host(shape, seed, _NAME_TO_KIND[name], layer, gain_sigma)
-        if t.dtype == np.uint8:
-            t = (dequantise_fp4 if shape.weight_format == "fp4" else dequantise_fp8)(t, shape.weight_scale_exp2)
+        t = dequantise(shape, _NAME_TO_KIND[name], synth.weight_host(shape, seed, _NAME_TO_KIND[name], layer, gain_sigma))
         if cache:
             store[key] = t
         return t

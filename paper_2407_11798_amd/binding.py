@@ -22,7 +22,7 @@ PI_E_FULL, PI_E_BUSY = -7, -8
 PI_MAX_BATCH, PI_WINDOW = 16, 64
 PI_MAX_SEQ, PI_SEQ_CANONICAL, PI_POS_MAX = 32, 0, 0x7FFFFFFF
 PI_RUN_SUPERFLUOUS, PI_RUN_INVALIDATED = 1, 2
-PI_DTYPE_F32, PI_DTYPE_BF16, PI_DTYPE_FP8_E4M3, PI_DTYPE_FP4_E2M1 = 0, 1, 2, 3
+PI_DTYPE_F32, PI_DTYPE_BF16, PI_DTYPE_FP8_E4M3, PI_DTYPE_FP4_E2M1, PI_DTYPE_FP4_E2M1_B32 = 0, 1, 2, 3, 4
 PI_LOC_HOST, PI_LOC_DEVICE = 0, 1
 (PI_T_EMBED, PI_T_ATTN_NORM, PI_T_WQ, PI_T_WK, PI_T_WV, PI_T_WO, PI_T_FFN_NORM, PI_T_WG, PI_T_WU,
  PI_T_WD, PI_T_FINAL_NORM, PI_T_LM_HEAD) = range(12)
@@ -174,11 +174,11 @@ class Model:
         self.shape = shape
         self.max_pos = max_pos
         wf = getattr(shape, "weight_format", "native")
-        fp8 = wf in ("fp8", "fp4")
+        fp8 = wf in ("fp8", "fp4")   # formats with one power-of-two scale per model
         cfg = PiModelConfig(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads,
                             shape.head_dim, shape.ffn, shape.vocab, shape.rms_eps, shape.rope_base,
                             _dtype_code(shape.dtype), max_pos,
-                            {"fp8": PI_DTYPE_FP8_E4M3, "fp4": PI_DTYPE_FP4_E2M1}.get(wf, _dtype_code(shape.dtype)),
+                            {"fp8": PI_DTYPE_FP8_E4M3, "fp4": PI_DTYPE_FP4_E2M1, "fp4b": PI_DTYPE_FP4_E2M1_B32}.get(wf, _dtype_code(shape.dtype)),
                             getattr(shape, "weight_scale_exp2", 0) if fp8 else 0)
         h = c_void_p()
         _check(lib().pi_model_load(byref(cfg), byref(h)), "pi_model_load")

@@ -84,8 +84,9 @@ PackedMat make_packed(int N, int K, int dtype) {
   p.KT = (K + weight_tile_cols(dtype) - 1) / weight_tile_cols(dtype);
   // 4-bit tiles are 128 columns wide: rounded up to a multiple of eight tiles (zero weights), so that the
   // tile count still splits into power-of-two column slices and a short contraction still fills a ring
-  if (dtype == kWeightFP4) p.KT = (p.KT + 7) / 8 * 8;
+  if (weight_is_fp4(dtype)) p.KT = (p.KT + 7) / 8 * 8;
   p.bytes = (size_t)p.NRB * p.KT * weight_tile_bytes(dtype);
+  if (dtype == kWeightFP4B) p.scale_bytes = (size_t)p.NRB * p.KT * 64;
   return p;
 }
 
@@ -258,7 +259,9 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (c.d_model % 32 || (c.n_q_heads * c.head_dim) % 32 || c.ffn % 16 || c.vocab % 16) return PI_E_SHAPE;
   if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 8) return PI_E_SHAPE;
   if (c.dtype != PI_DTYPE_F32 && c.dtype != PI_DTYPE_BF16) return PI_E_SHAPE;
-  const bool w8 = c.weight_dtype == PI_DTYPE_FP8_E4M3 || c.weight_dtype == PI_DTYPE_FP4_E2M1;
+  const bool w8 = c.weight_dtype == PI_DTYPE_FP8_E4M3 || c.weight_dtype == PI_DTYPE_FP4_E2M1 ||
+                  c.weight_dtype == PI_DTYPE_FP4_E2M1_B32;
+  if (c.weight_dtype == PI_DTYPE_FP4_E2M1_B32 && c.weight_scale_exp2 != 0) return PI_E_SHAPE;  // the blocks carry the scales
   if (w8 ? (c.dtype != PI_DTYPE_BF16 || c.weight_scale_exp2 < -32 || c.weight_scale_exp2 > 32)
          : (c.weight_dtype != c.dtype && !(c.weight_dtype == 0 && c.dtype == PI_DTYPE_BF16)))
     return PI_E_SHAPE;
@@ -285,12 +288,14 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     L.down = make_packed(d, c.ffn, wd);
     for (PackedMat* p : {&L.qkv, &L.o, &L.gateup, &L.down}) {
       if (e == hipSuccess) e = dev_alloc(m, (char**)&p->data, p->bytes, true);
+      if (e == hipSuccess && p->scale_bytes) e = dev_alloc(m, (char**)&p->scales, p->scale_bytes, true);
     }
     if (e == hipSuccess) e = dev_alloc(m, &L.attn_gain, d * sizeof(float), true);
     if (e == hipSuccess) e = dev_alloc(m, &L.ffn_gain, d * sizeof(float), true);
   }
   m->lm_head = make_packed(c.vocab, d, wd);
   if (e == hipSuccess) e = dev_alloc(m, (char**)&m->lm_head.data, m->lm_head.bytes, true);
+  if (e == hipSuccess && m->lm_head.scale_bytes) e = dev_alloc(m, (char**)&m->lm_head.scales, m->lm_head.scale_bytes, true);
   if (e == hipSuccess) e = dev_alloc(m, (char**)&m->embed, (size_t)c.vocab * d * es, true);
   if (e == hipSuccess) e = dev_alloc(m, &m->final_gain, d * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2), false);
@@ -328,6 +333,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
     auto md = [](const PackedMat& p) {
       MatDev r;
       r.w = (const char*)p.data;
+      r.s = (const char*)p.scales;
       r.N = p.N;
       r.K = p.K;
       r.NRB = p.NRB;
@@ -377,8 +383,10 @@ int32_t pi_model_free(pi_model* m) {
 int32_t pi_model_weight_bytes(const pi_model* m, int64_t* layer_bytes, int64_t* lm_head_bytes) {
   if (!m) return PI_E_ARG;
   const LayerWeights& L = m->layers[0];
-  if (layer_bytes) *layer_bytes = (int64_t)(L.qkv.bytes + L.o.bytes + L.gateup.bytes + L.down.bytes);
-  if (lm_head_bytes) *lm_head_bytes = (int64_t)m->lm_head.bytes;
+  if (layer_bytes)
+    *layer_bytes = (int64_t)(L.qkv.bytes + L.o.bytes + L.gateup.bytes + L.down.bytes + L.qkv.scale_bytes + L.o.scale_bytes +
+                             L.gateup.scale_bytes + L.down.scale_bytes);
+  if (lm_head_bytes) *lm_head_bytes = (int64_t)(m->lm_head.bytes + m->lm_head.scale_bytes);
   return PI_OK;
 }
 
@@ -386,7 +394,7 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
                             int32_t src_loc) {
   if (!m || !src) return PI_E_ARG;
   if (kind < PI_T_EMBED || kind > PI_T_LM_HEAD) return PI_E_ARG;
-  if (src_dtype < PI_DTYPE_F32 || src_dtype > PI_DTYPE_FP4_E2M1) return PI_E_ARG;
+  if (src_dtype < PI_DTYPE_F32 || src_dtype > PI_DTYPE_FP4_E2M1_B32) return PI_E_ARG;
   if (src_loc != PI_LOC_HOST && src_loc != PI_LOC_DEVICE) return PI_E_ARG;
   if (is_layer_kind(kind) && (layer < 0 || layer >= m->cfg.n_layers)) return PI_E_ARG;
   const pi_model_config& c = m->cfg;
@@ -396,8 +404,9 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
   if (!is_gain && src_dtype == PI_DTYPE_BF16 && c.dtype == PI_DTYPE_F32) return PI_E_ARG;
   // quantised weights: the streamed matrices come in the model's weight format and nothing else does
   const bool is_matrix = !is_gain && kind != PI_T_EMBED;
-  const bool quantised_src = src_dtype == PI_DTYPE_FP8_E4M3 || src_dtype == PI_DTYPE_FP4_E2M1;
-  const bool quantised_dst = is_matrix && (m->wdtype == kWeightFP8 || m->wdtype == kWeightFP4);
+  const bool quantised_src = src_dtype == PI_DTYPE_FP8_E4M3 || src_dtype == PI_DTYPE_FP4_E2M1 ||
+                             src_dtype == PI_DTYPE_FP4_E2M1_B32;
+  const bool quantised_dst = is_matrix && (m->wdtype == kWeightFP8 || weight_is_fp4(m->wdtype));
   if (quantised_src != quantised_dst || (quantised_src && src_dtype != m->wdtype)) return PI_E_ARG;
   const int wd = m->wdtype;
   int rows = 1, cols = d;
@@ -410,8 +419,9 @@ int32_t pi_model_set_tensor(pi_model* m, int32_t kind, int32_t layer, const void
     case PI_T_WD: rows = d; cols = c.ffn; break;
     default: break;
   }
-  if (src_dtype == PI_DTYPE_FP4_E2M1 && cols % 2) return PI_E_SHAPE;
-  const size_t src_bytes = src_dtype == PI_DTYPE_FP4_E2M1 ? (size_t)rows * cols / 2
+  if (weight_is_fp4(src_dtype) && cols % 2) return PI_E_SHAPE;
+  const size_t src_bytes = src_dtype == PI_DTYPE_FP4_E2M1_B32 ? (size_t)rows * cols / 2 + (size_t)rows * ((cols + 31) / 32)
+                           : src_dtype == PI_DTYPE_FP4_E2M1 ? (size_t)rows * cols / 2
                            : (size_t)rows * cols * (src_dtype == PI_DTYPE_FP8_E4M3 ? 1 : src_dtype == PI_DTYPE_BF16 ? 2 : 4);
   const void* dsrc = src;
   void* staging = nullptr;
@@ -762,6 +772,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.n_layers = L;
   a.eps = c.rms_eps;
   a.wscale = m->wdtype == kWeightFP8 || m->wdtype == kWeightFP4 ? std::ldexp(1.0f, c.weight_scale_exp2) : 1.0f;
+  a.lm_head.s = (const char*)m->lm_head.scales;
   a.n = n;
   a.tokens = run->tokens;
   a.positions = run->positions;

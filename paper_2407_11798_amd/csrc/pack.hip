@@ -83,6 +83,25 @@ __global__ void __launch_bounds__(256) repack_fp4_kernel(const uint8_t* src, int
   }
 }
 
+// Scale plane of a block-scaled 4-bit matrix: one thread per (source row, 128-column tile) writes the
+// four scale bytes of the row's 32-column blocks in that tile (2^0 where the row has no such block).
+__global__ void __launch_bounds__(256) repack_fp4_scales_kernel(const uint8_t* scales, int rows, int cols, char* dst, int KT,
+                                                                int row_mul, int row_add) {
+  const int bpr = (cols + 31) / 32;
+  const size_t total = (size_t)rows * KT;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i / KT), t = (int)(i % KT);
+    const int pr = r * row_mul + row_add;
+    const int rb = pr / kRowBlock, lr = pr % kRowBlock;
+    uint32_t w = 0u;
+    for (int h = 0; h < 4; ++h) {
+      const int b = 4 * t + h;
+      w |= (uint32_t)(b < bpr ? scales[(size_t)r * bpr + b] : 127u) << (8 * h);
+    }
+    *(uint32_t*)(dst + (((size_t)rb * KT + t) * 16 + lr) * 4) = w;
+  }
+}
+
 __global__ void __launch_bounds__(256) convert_kernel(const void* src, int src_dtype, void* dst,
                                                       int dst_dtype, size_t count) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
@@ -115,7 +134,19 @@ hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, Pac
                                                                     dst.KT, row_mul, row_add);
     return hipGetLastError();
   }
-  if (dst_dtype == kWeightFP4) {
+  if (dst_dtype == kWeightFP4B) {  // the scale bytes follow the code bytes in the source buffer
+    const uint8_t* sc = (const uint8_t*)src + (size_t)rows * cols / 2;
+    const size_t totals = (size_t)rows * dst.KT;
+    size_t blockss = (totals + 255) / 256;
+    if (blockss > 16384) blockss = 16384;
+    if (blockss) {
+      repack_fp4_scales_kernel<<<dim3((unsigned)blockss), dim3(256), 0, s>>>(sc, rows, cols, (char*)dst.scales, dst.KT,
+                                                                             row_mul, row_add);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+  }
+  if (weight_is_fp4(dst_dtype)) {
     const size_t total4 = (size_t)rows * dst.KT * 16;
     size_t blocks4 = (total4 + 255) / 256;
     if (blocks4 > 16384) blocks4 = 16384;

@@ -28,9 +28,14 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 //   fp4 tile  (1 KiB): 16 rows x 128 columns, two weights per byte; lane l holds, in bytes 4h..4h+3
 //                      (h = 0..3), W[16rb + (l&15)][128t + 32h + 8(l>>4) + 0..7], lower column in the
 //                      low nibble: four consecutive bf16-shaped tiles in one 16-byte piece.
+//   block-scaled fp4:  the same tiles, and beside them a plane of scale bytes, 64 per tile in tile
+//                      order: byte (16 rows x 4) [r][h] is the scale of row 16rb + r, columns
+//                      128t + 32h .. + 31 (127 = 2^0 where the matrix has no such columns).
 // Rows >= N and columns >= K are zero.  KT counts tiles of the matrix's own width.
 struct PackedMat {
   void* data = nullptr;
+  void* scales = nullptr;  // block-scaled formats only
+  size_t scale_bytes = 0;
   int N = 0, K = 0;    // logical
   int NRB = 0, KT = 0; // row blocks, k tiles
   size_t bytes = 0;
@@ -39,8 +44,9 @@ struct PackedMat {
 // Weight format of a model as the kernels see it: the activation side of PI_DTYPE_FP8_E4M3 is
 // that of a bf16 model; only the matrices differ.
 constexpr int kWeightF32 = PI_DTYPE_F32, kWeightBF16 = PI_DTYPE_BF16, kWeightFP8 = PI_DTYPE_FP8_E4M3,
-              kWeightFP4 = PI_DTYPE_FP4_E2M1;
-__host__ __device__ constexpr int weight_tile_cols(int wd) { return wd == kWeightFP4 ? 128 : wd == kWeightFP8 ? 64 : 32; }
+              kWeightFP4 = PI_DTYPE_FP4_E2M1, kWeightFP4B = PI_DTYPE_FP4_E2M1_B32;
+__host__ __device__ constexpr bool weight_is_fp4(int wd) { return wd == kWeightFP4 || wd == kWeightFP4B; }
+__host__ __device__ constexpr int weight_tile_cols(int wd) { return weight_is_fp4(wd) ? 128 : wd == kWeightFP8 ? 64 : 32; }
 __host__ __device__ constexpr int weight_tile_bytes(int wd) { return wd == kWeightF32 ? 2048 : 1024; }
 
 struct LayerWeights {
@@ -75,6 +81,7 @@ struct StageSync {
 
 struct MatDev {
   const char* w;
+  const char* s;  // scale plane of a block-scaled matrix, else null
   int N, K, NRB, KT;
 };
 

@@ -194,6 +194,8 @@ __device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc,
 struct WaveStream {
   const char* w;   // the whole matrix, read through a raw buffer of `bytes` bytes
   uint32_t bytes;
+  const char* ws;  // block-scaled weights: the plane of scale bytes (64 per tile, in tile order), else null
+  uint32_t sbytes;
   int KT, nt, t0, NRB;
   int rb0, R;         // this workgroup's row blocks [rb0, rb0 + R)
   int f0, f1, share;  // this wave's flat range of the workgroup's R * nt tiles; tiles per wave
@@ -218,6 +220,7 @@ __device__ __forceinline__ T* uni_ptr(T* p) {
 __device__ __forceinline__ MatDev uni_mat(const MatDev& m) {
   MatDev r;
   r.w = uni_ptr(m.w);
+  r.s = uni_ptr(m.s);
   r.N = uni(m.N);
   r.K = uni(m.K);
   r.NRB = uni(m.NRB);
@@ -246,6 +249,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 __device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
   S.w = uni_ptr(S.w);
   S.bytes = (uint32_t)uni((int)S.bytes);
+  S.ws = uni_ptr(S.ws);
+  S.sbytes = (uint32_t)uni((int)S.sbytes);
   S.KT = uni(S.KT); S.nt = uni(S.nt); S.t0 = uni(S.t0); S.NRB = uni(S.NRB);
   S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
   S.slice = uni(S.slice); S.wave = uni(S.wave); S.rb0 = uni(S.rb0); S.R = uni(S.R);
@@ -258,6 +263,8 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   constexpr int kTileBytes = weight_tile_bytes(DT);
   S.w = M.w;
   S.bytes = (uint32_t)M.NRB * (uint32_t)M.KT * kTileBytes;
+  S.ws = M.s;
+  S.sbytes = (uint32_t)M.NRB * (uint32_t)M.KT * 64u;
   S.KT = M.KT;
   S.NRB = M.NRB;
   S.nt = uni(M.KT / S_k);
@@ -286,6 +293,7 @@ struct Ring {
   static constexpr int kTileBytes = weight_tile_bytes(DT);
   static constexpr int kRegs = DT == kWeightF32 ? 2 * UR : UR;
   u32x4 r[kRegs];
+  uint32_t s[DT == kWeightFP4B ? UR : 1];  // block-scaled weights: the lane's row's four scale bytes of the tile
 };
 
 // What one pass over the ring does, worked out in scalar registers before the pass, so that every
@@ -314,7 +322,12 @@ __device__ __forceinline__ void ring_issue(Ring<DT, UR>& R, const WaveStream& S,
   const int soff = (int)((J < P.el ? P.lbaseA : P.lbaseB) + (uint32_t)(J * TB)) & mask;
   const int voff = (lane16 & mask) | (0x7ffffff0 & ~mask);
   const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(S.w, S.bytes);
-  if constexpr (DT != kWeightF32) {
+  if constexpr (DT == kWeightFP4B) {
+    // the tile, then the dword of its scale plane that belongs to this lane's row (tile offset / 16 + 4 row)
+    R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
+    const int svoff = (((lane16 >> 4) & 15) * 4 & mask) | (0x7ffffff0 & ~mask);
+    R.s[J] = __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(S.ws, S.sbytes), svoff, (int)((uint32_t)soff >> 4), 2);
+  } else if constexpr (DT != kWeightF32) {
     R.r[J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
   } else {
     R.r[2 * J] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 2);
@@ -767,16 +780,20 @@ __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeStat
         C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
         C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
       }
-    } else if constexpr (DT == kWeightFP4) {
-      // sixteen bytes -> four bf16 operands (one per 32 columns), one byte = two weights
+    } else if constexpr (weight_is_fp4(DT)) {
+      // sixteen bytes -> four bf16 operands (one per 32 columns), one byte = two weights; with
+      // block scales each of the four has the scale of its own 32 columns of the lane's row,
+      // 2^(byte - 127), which is the float whose exponent field is that byte
       const u32x4 w = R.r[J];
 #pragma unroll
       for (int h = 0; h < 4; ++h) {
+        float sc = PLn.wscale;
+        if constexpr (DT == kWeightFP4B) sc = __uint_as_float(((R.s[J] >> (8 * h)) & 0xffu) << 23);
         u32x4 o;
-        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 0));
-        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 1));
-        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 2));
-        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], PLn.wscale, 3));
+        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 0));
+        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 1));
+        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 2));
+        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 3));
         const bf16x8 av = __builtin_bit_cast(bf16x8, o);
         C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
         C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
@@ -1622,6 +1639,7 @@ size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
 
 namespace {
 const void* stage_fn(int dtype, int ring) {
+  if (dtype == kWeightFP4B) return ring == 8 ? (const void*)stage_kernel<kWeightFP4B, 8> : (const void*)stage_kernel<kWeightFP4B, 4>;
   if (dtype == kWeightFP4) return ring == 8 ? (const void*)stage_kernel<kWeightFP4, 8> : (const void*)stage_kernel<kWeightFP4, 4>;
   if (dtype == kWeightFP8) return ring == 8 ? (const void*)stage_kernel<kWeightFP8, 8> : (const void*)stage_kernel<kWeightFP8, 4>;
   if (dtype == PI_DTYPE_BF16) return ring == 8 ? (const void*)stage_kernel<PI_DTYPE_BF16, 8> : (const void*)stage_kernel<PI_DTYPE_BF16, 4>;

@@ -15,6 +15,14 @@ This module only sequences calls: every decision about runs comes from the nativ
 bookkeeping (pi_sched_*), every array is produced by the library's kernels, and nothing is
 computed on the host beyond appending tokens to a list.  The draft model is an argument: any
 callable position -> (token, confidence).
+
+Token trees (Sections "Speculative Inference / Verification", "Continuous Speculation": trees
+build on previous trees): with an `alternative` callable a speculative run is a small tree -- its
+chain of draft tokens plus one leaf holding the draft model's second choice for one of the
+chain's positions, a sibling of the chain token there.  The leaf hangs at least two positions
+above the chain's end, so the chain is the only path of full depth: the next run builds on the
+chain's last token and counts exactly when the whole chain was accepted.  Each of the tree's two
+branches has a sequence partition of its own; a node belongs to the branches that pass through it.
 """
 from __future__ import annotations
 
@@ -34,6 +42,7 @@ class _Pass:
         dev, nb = "cuda", pi.PI_MAX_BATCH
         self.tokens = torch.zeros(nb, dtype=torch.int32, device=dev)
         self.positions = torch.zeros(nb, dtype=torch.int32, device=dev)
+        self.parent = torch.zeros(nb, dtype=torch.int32, device=dev)     # parent node of each token inside its run
         self.cell_seq = torch.zeros(nb, dtype=torch.int32, device=dev)   # sequences each new entry belongs to
         self.sees_seq = torch.zeros(nb, dtype=torch.int32, device=dev)   # sequences each token reads
         self.slots = torch.zeros(nb, dtype=torch.int32, device=dev)
@@ -46,19 +55,34 @@ class _Pass:
         self.cancel = torch.zeros(_MAX_RUNS, dtype=torch.int32, pin_memory=True)
         self.cancel_dev = pi.mapped_device_pointer(self.cancel)
         self.event = torch.cuda.Event()
-        self.h_in = torch.zeros((4, nb), dtype=torch.int32, pin_memory=True)  # tokens, positions, cell_seq, sees_seq
+        self.h_in = torch.zeros((5, nb), dtype=torch.int32, pin_memory=True)  # tokens, positions, cell_seq, sees_seq, parent
         self.runs = []
 
 
 class _Run:
-    def __init__(self, speculative, tokens, start, seq):
-        self.speculative, self.tokens, self.start, self.seq = speculative, [int(t) for t in tokens], start, seq
-        self.n = len(tokens)
+    """tokens[0 .. m-1] is the chain (positions start .. start+m-1); an optional last token is the
+    alternative for position start + alt_at, a sibling of the chain token there."""
+
+    def __init__(self, speculative, tokens, start, seq, alt=None, alt_at=-1):
+        self.speculative, self.start, self.seq = speculative, start, seq
+        self.m = len(tokens)
+        self.tokens = [int(t) for t in tokens] + ([int(alt)] if alt is not None else [])
+        self.n = len(self.tokens)
+        self.parent = list(range(-1, self.m - 1)) + ([alt_at - 1] if alt is not None else [])
+        self.positions = list(range(start, start + self.m)) + ([start + alt_at] if alt is not None else [])
+        self.alt_at = alt_at if alt is not None else -1
+        self.seq_alt = 0      # the alternative leaf's partition (a bit), 0 if the run is a chain
         self.id = -1
         self.cancelled = False
         self.pass_ = None
         self.k = 0            # index in its pass
         self.first = 0        # index of its first token in the pass
+
+    def node_seqs(self):
+        """Per token the set of partitions it belongs to: the chain's partition, plus the
+        alternative's for the chain tokens above the fork; the alternative leaf has its own only."""
+        out = [self.seq | (self.seq_alt if i < self.alt_at else 0) for i in range(self.m)]
+        return out + ([self.seq_alt] if self.alt_at >= 0 else [])
 
 
 def _i32(v):
@@ -74,9 +98,11 @@ class ContinuousSpeculation:
 
     def __init__(self, model, kv, prefix_len: int, first_token: int, draft, depth: int = 3, micro_batch: int = 4,
                  base_cutoff: float = 0.3, recovery: float = 0.05, decay: float = 0.05, n_seq: int = 32,
-                 runs_per_pass: int = 1):
+                 runs_per_pass: int = 1, alternative=None):
+        """alternative(pos) -> token or None: the draft model's second choice for position pos; when
+        given, runs become trees (chain + one alternative leaf) where there is room."""
         assert 1 <= micro_batch <= 4 and depth >= 1 and 1 <= runs_per_pass <= _MAX_RUNS
-        self.model, self.kv, self.draft = model, kv, draft
+        self.model, self.kv, self.draft, self.alternative = model, kv, draft, alternative
         self.depth, self.mb, self.rpp = depth, micro_batch, runs_per_pass
         self.L = model.shape.n_layers
         self.vocab = model.shape.vocab
@@ -96,7 +122,7 @@ class ContinuousSpeculation:
         self._cutoff_stop = False
         self.stats = {"passes": 0, "runs": 0, "non_speculative": 0, "speculative": 0, "discarded": 0, "cancelled": 0,
                       "layers_skipped": 0, "tokens_speculated": 0, "tokens_accepted_from_drafts": 0, "compactions": 0,
-                      "cutoff_stops": 0}
+                      "cutoff_stops": 0, "tree_runs": 0, "alternatives_accepted": 0}
 
     # ---- issuing ---------------------------------------------------------------------------
     def _runs_in_flight(self):
@@ -109,7 +135,7 @@ class ContinuousSpeculation:
         out = []
         for r in self._runs_in_flight() + extra:
             if not r.cancelled:
-                for k, t in enumerate(r.tokens):
+                for k, t in enumerate(r.tokens[:r.m]):       # the chain: what later runs build on
                     if A <= r.start + k < start:
                         out.append(t)
         return out
@@ -125,7 +151,7 @@ class ContinuousSpeculation:
             runs.append(_Run(False, [self.accepted[-1]], len(self.accepted) - 1, self.all_seq))
             n_tok, last = 1, runs[0]
         while len(runs) < self.rpp and n_tok + 1 <= pi.PI_MAX_BATCH and self.issued_cells + n_tok + 1 <= pi.PI_WINDOW:
-            start = last.start + last.n
+            start = last.start + last.m
             batch = []
             room = min(self.mb, pi.PI_MAX_BATCH - n_tok, pi.PI_WINDOW - self.issued_cells - n_tok)
             while len(batch) < room:
@@ -138,9 +164,17 @@ class ContinuousSpeculation:
                 self.stats["cutoff_stops"] += 1 if room > 0 else 0
                 break
             self.sched.on_speculated()
-            last = _Run(True, batch, start, 0)
+            alt, alt_at = None, -1
+            spare = min(pi.PI_MAX_BATCH - n_tok, pi.PI_WINDOW - self.issued_cells - n_tok) - len(batch)
+            if self.alternative is not None and spare >= 1:
+                for j in range(len(batch) - 1):      # at least two positions above the chain's end
+                    a = self.alternative(start + j)
+                    if a is not None and int(a) != batch[j]:
+                        alt, alt_at = int(a), j
+                        break
+            last = _Run(True, batch, start, 0, alt, alt_at)
             runs.append(last)
-            n_tok += len(batch)
+            n_tok += last.n
         return runs
 
     def _issue(self, runs):
@@ -162,18 +196,26 @@ class ContinuousSpeculation:
                 sid = self.meta.acquire()
                 assert sid is not None, "out of sequence partitions"
                 r.seq = 1 << sid
+                if r.alt_at >= 0:
+                    sid2 = self.meta.acquire()
+                    assert sid2 is not None, "out of sequence partitions"
+                    r.seq_alt = 1 << sid2
+                    self.stats["tree_runs"] += 1
                 if prev is not None and prev.speculative:
-                    copies.append((prev.seq.bit_length() - 1, r.seq))   # early sharing: build on the run before
+                    # early sharing: every branch of this run builds on the chain of the run before
+                    copies.append((prev.seq.bit_length() - 1, r.seq | r.seq_alt))
+            seqs = np.asarray([_i32(q) for q in r.node_seqs()], dtype=np.int32)
             P.h_in[0, first:first + r.n] = torch.as_tensor(np.asarray(r.tokens, dtype=np.int32))
-            P.h_in[1, first:first + r.n] = torch.arange(r.start, r.start + r.n, dtype=torch.int32)
-            P.h_in[2, first:first + r.n] = _i32(r.seq)
+            P.h_in[1, first:first + r.n] = torch.as_tensor(np.asarray(r.positions, dtype=np.int32))
+            P.h_in[2, first:first + r.n] = torch.as_tensor(seqs)
             # a non-speculative run's entry belongs to every sequence at once (it is known to be right),
             # but the run itself reads the canonical sequence only: never another run's speculation
-            P.h_in[3, first:first + r.n] = _i32(r.seq) if r.speculative else 1
+            P.h_in[3, first:first + r.n] = torch.as_tensor(seqs) if r.speculative else 1
+            P.h_in[4, first:first + r.n] = torch.as_tensor(np.asarray(r.parent, dtype=np.int32))
             P.cancel[k] = 0
             first += r.n
             prev = r
-        for dst, src in ((P.tokens, 0), (P.positions, 1), (P.cell_seq, 2), (P.sees_seq, 3)):
+        for dst, src in ((P.tokens, 0), (P.positions, 1), (P.cell_seq, 2), (P.sees_seq, 3), (P.parent, 4)):
             dst.copy_(P.h_in[src], non_blocking=True)
         self.meta.place(n_tot, P.positions, P.cell_seq, self.dense, P.slots, P.out[2:3])
         for src_id, dst_mask in copies:
@@ -191,12 +233,14 @@ class ContinuousSpeculation:
             a, b = r.first, r.first + r.n
             res = P.out[_RES + 2 * k:_RES + 2 * k + 2]
             gst = P.out[_GS + 2 * k:_GS + 2 * k + 2]
+            par = P.parent[a:b] if r.alt_at >= 0 else None     # a chain needs no parent array
             if prev is None:
-                pi.verify_greedy_chained(P.tokens[a:b], None, r.n, P.logits[a:b], self.vocab, r.tokens[0], None, 0, gst,
+                pi.verify_greedy_chained(P.tokens[a:b], par, r.n, P.logits[a:b], self.vocab, r.tokens[0], None, 0, gst,
                                          P.out[_PATH + a:_PATH + b], res)
             else:
+                # the run before counts as accepted whole when its chain was: the chain is its only path of that length
                 pres = prev.pass_.out[_RES + 2 * prev.k:_RES + 2 * prev.k + 2]
-                pi.verify_greedy_chained(P.tokens[a:b], None, r.n, P.logits[a:b], self.vocab, 0, pres, prev.n, gst,
+                pi.verify_greedy_chained(P.tokens[a:b], par, r.n, P.logits[a:b], self.vocab, 0, pres, prev.m, gst,
                                          P.out[_PATH + a:_PATH + b], res)
             if r.speculative:
                 self.meta.accept(r.n, P.positions[a:b], P.cell_seq[a:b], P.out[_PATH + a:_PATH + b], res)
@@ -206,8 +250,7 @@ class ContinuousSpeculation:
         done = []
         for k, r in enumerate(runs):
             assumed = self._assumed(r.start, done)
-            r.id = self.sched.begin_run(r.speculative, assumed, r.start - len(assumed), r.tokens, list(range(-1, r.n - 1)),
-                                        list(range(r.start, r.start + r.n)),
+            r.id = self.sched.begin_run(r.speculative, assumed, r.start - len(assumed), r.tokens, r.parent, r.positions,
                                         cancel_word_ptr=P.cancel.data_ptr() + 4 * k)
             done.append(r)
             self.stats["runs"] += 1
@@ -242,17 +285,22 @@ class ContinuousSpeculation:
             if counted:
                 # positions start .. start+a-1 hold the run's accepted tokens (the first of them is
                 # the accepted end already), position start+a the target's own token
-                new = r.tokens[1:a] + [bonus]
-                assert len(self.accepted) == r.start + 1 and self.accepted[r.start] == r.tokens[0]
+                path = [int(v) for v in out[_PATH + r.first:_PATH + r.first + a]]
+                new = [r.tokens[i] for i in path[1:]] + [bonus]
+                assert len(self.accepted) == r.start + 1 and self.accepted[r.start] == r.tokens[path[0]]
                 self.accepted += new
                 if r.speculative:
                     self.stats["tokens_accepted_from_drafts"] += a
+                    if r.alt_at >= 0 and path[-1] == r.n - 1:
+                        self.stats["alternatives_accepted"] += 1
                 hit = {rid for rid, _, _ in self.sched.accept_tokens(new, run_completed=True)}
                 for q in P.runs + self._runs_in_flight():
                     if q.id in hit:
                         q.cancelled = True
             if r.speculative:
                 self.meta.release(r.seq.bit_length() - 1)
+                if r.seq_alt:
+                    self.meta.release(r.seq_alt.bit_length() - 1)
         # the chain can be continued only while its last run is in flight and still stands (a
         # rejected token takes every run built on it along, so the last run tells)
         if self.tail is not None and (self.tail.pass_ is P or self.tail.cancelled):
@@ -277,7 +325,7 @@ class ContinuousSpeculation:
             if self.fifo and self.fifo[0].event.query():
                 self._process_head()                       # logits are waiting: sample and verify
                 continue
-            if not self.fifo and self.issued_cells + 1 + self.mb > pi.PI_WINDOW:
+            if not self.fifo and self.issued_cells + 2 + self.mb > pi.PI_WINDOW:
                 self._compact()
                 continue
             if len(self.fifo) < self.depth and self.free and self.issued_cells + 1 <= pi.PI_WINDOW:

@@ -40,8 +40,9 @@ class ModelShape:
     rope_base: float = 10000.0
     dtype: str = "bf16"  # storage type of weights and KV cache: "f32" or "bf16"
     # "fp8" / "fp4": the weight matrices (not the embedding table) are FP8 E4M3 bytes / FP4 E2M1
-    # nibbles (two per byte) and the weight is code value * 2^weight_scale_exp2; everything else
-    # follows `dtype`
+    # nibbles (two per byte) and the weight is code value * 2^weight_scale_exp2; "fp4b": FP4 E2M1
+    # nibbles with one power-of-two scale per 32 columns of a row (weight = code value *
+    # 2^(scale byte - 127)); everything else follows `dtype`
     weight_format: str = "native"
     weight_scale_exp2: int = 0
 
@@ -59,7 +60,7 @@ class ModelShape:
 
     @property
     def bytes_per_matrix_weight(self) -> int:
-        return {"fp8": 1, "fp4": 0.5}.get(self.weight_format, self.bytes_per_weight)
+        return {"fp8": 1, "fp4": 0.5, "fp4b": 0.53125}.get(self.weight_format, self.bytes_per_weight)
 
 
 SHAPES = {
@@ -83,6 +84,11 @@ SHAPES = {
                              weight_scale_exp2=-6),
     "llama70b_w4": ModelShape("llama70b_w4", 80, 8192, 64, 8, 128, 28672, 32000, weight_format="fp4",
                               weight_scale_exp2=-6),
+    # 4-bit weight matrices with one power-of-two scale per 32 columns of a row (4.25 bits per weight)
+    "tiny_w4b": ModelShape("tiny_w4b", 2, 256, 4, 4, 64, 688, 1024, weight_format="fp4b"),
+    "tiny_gqa_w4b": ModelShape("tiny_gqa_w4b", 3, 256, 8, 2, 32, 352, 512, weight_format="fp4b"),
+    "llama7b_w4b": ModelShape("llama7b_w4b", 32, 4096, 32, 32, 128, 11008, 32000, weight_format="fp4b"),
+    "llama70b_w4b": ModelShape("llama70b_w4b", 80, 8192, 64, 8, 128, 28672, 32000, weight_format="fp4b"),
 }
 
 # Tensor kinds (also the upper part of the generator stream id).
@@ -150,6 +156,8 @@ def host_lib():
                                                 ctypes.c_void_p]
         _host.synth_debug_e4m3_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
         _host.synth_debug_e2m1_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64]
+        _host.synth_fill_normal_fp4b_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                                      ctypes.c_uint64, ctypes.c_uint64, ctypes.c_double]
     return _host
 
 
@@ -166,6 +174,8 @@ def hip_lib():
         _hip.synth_fill_uniform_int_device.argtypes = [ctypes.c_void_p, ctypes.c_int64,
                                                        ctypes.c_uint64, ctypes.c_uint64,
                                                        ctypes.c_uint32, ctypes.c_void_p]
+        _hip.synth_fill_normal_fp4b_device.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                                       ctypes.c_uint64, ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p]
     return _hip
 
 
@@ -185,6 +195,30 @@ def normal_host(n: int, seed: int, sid: int, sigma: float, dtype: str) -> np.nda
     if rc != 0:
         raise RuntimeError("synth_fill_normal_host failed")
     return out
+
+
+def fp4b_sizes(rows: int, cols: int):
+    """Bytes of codes and of scales of a block-scaled 4-bit matrix [rows][cols]."""
+    return rows * cols // 2, rows * ((cols + 31) // 32)
+
+
+def normal_fp4b_host(rows: int, cols: int, seed: int, sid: int, sigma: float) -> np.ndarray:
+    """A block-scaled 4-bit matrix ~ N(0, sigma^2) as ONE uint8 array: codes[rows][cols / 2] (two FP4
+    E2M1 nibbles per byte, even column low) followed by scales[rows][ceil(cols / 32)] (weight = code
+    value * 2^(scale - 127), one scale per 32 columns of a row, chosen so that the block's largest
+    magnitude lands in [4, 8) before rounding)."""
+    nc, ns = fp4b_sizes(rows, cols)
+    out = np.empty(nc + ns, dtype=np.uint8)
+    rc = host_lib().synth_fill_normal_fp4b_host(out.ctypes.data, out.ctypes.data + nc, rows, cols, seed, sid, float(sigma))
+    if rc != 0:
+        raise RuntimeError("synth_fill_normal_fp4b_host failed")
+    return out
+
+
+def split_fp4b(buf: np.ndarray, rows: int, cols: int):
+    """(codes[rows][cols / 2], scales[rows][ceil(cols / 32)]) views of a block-scaled 4-bit matrix."""
+    nc, ns = fp4b_sizes(rows, cols)
+    return buf[:nc].reshape(rows, cols // 2), buf[nc:nc + ns].reshape(rows, (cols + 31) // 32)
 
 
 def uniform_int_host(n: int, seed: int, sid: int, rng: int) -> np.ndarray:
@@ -241,6 +275,8 @@ def weight_host(shape: ModelShape, seed: int, kind: int, layer: int = 0,
     if shape.weight_format == "fp8" and kind != T_EMBED:
         return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2,
                            "fp8").reshape(dims)
+    if shape.weight_format == "fp4b" and kind != T_EMBED:
+        return normal_fp4b_host(dims[0], dims[1], seed, stream_id(kind, layer), WEIGHT_SIGMA)
     if shape.weight_format == "fp4" and kind != T_EMBED:
         return normal_host(n, seed, stream_id(kind, layer), WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2,
                            "fp4").reshape(dims[0], dims[1] // 2)

@@ -36,10 +36,20 @@ def load_model(shape: synth.ModelShape, seed: int, gain_sigma: float = 0.0, max_
             t = synth.weight_host(shape, seed, kind, layer, gain_sigma)
             code = None
             if t.dtype == np.uint8:
-                code = pi.PI_DTYPE_FP4_E2M1 if shape.weight_format == "fp4" else pi.PI_DTYPE_FP8_E4M3
+                code = {"fp4": pi.PI_DTYPE_FP4_E2M1, "fp4b": pi.PI_DTYPE_FP4_E2M1_B32}.get(shape.weight_format, pi.PI_DTYPE_FP8_E4M3)
             m.set_tensor(_KIND_TO_PI[kind], layer, t, src_dtype=code)
             return
         rows, cols = synth.tensor_shape(shape, kind)
+        if shape.weight_format == "fp4b" and kind != synth.T_EMBED:
+            nc, ns = synth.fp4b_sizes(rows, cols)
+            t = torch.empty(nc + ns, dtype=torch.uint8, device="cuda")    # codes, then scales: the layout the ABI takes
+            rc = synth.hip_lib().synth_fill_normal_fp4b_device(t.data_ptr(), t.data_ptr() + nc, rows, cols, seed,
+                                                               synth.stream_id(kind, layer), float(synth.WEIGHT_SIGMA),
+                                                               torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+            torch.cuda.current_stream().synchronize()
+            m.set_tensor(_KIND_TO_PI[kind], layer, t, src_dtype=pi.PI_DTYPE_FP4_E2M1_B32)
+            return
         if shape.weight_format in ("fp8", "fp4") and kind != synth.T_EMBED:
             t = device_normal(rows * cols, seed, synth.stream_id(kind, layer),
                               synth.WEIGHT_SIGMA * 2.0 ** -shape.weight_scale_exp2, shape.weight_format)

@@ -16,7 +16,8 @@
  *   u1 = ((h1 >> 11) + 1) * 2^-53  in (0,1],  u2 = (h2 >> 11) * 2^-53 in [0,1)
  *   r = sqrt(-2 ln u1);  z = r cos(2 pi u2) for even i,  r sin(2 pi u2) for odd i
  * (Box-Muller).  value = (float)(sigma * z), optionally rounded to bf16 (RNE) or to an FP8 E4M3
- * byte or an FP4 E2M1 nibble (both RNE, saturating; two nibbles per byte, even element low).
+ * byte or an FP4 E2M1 nibble (both RNE, saturating; two nibbles per byte, even element low), or to
+ * block-scaled FP4: nibbles of value / 2^e with one exponent e per 32 elements of a row.
  */
 #ifndef PI_SYNTH_CORE_H
 #define PI_SYNTH_CORE_H
@@ -174,6 +175,40 @@ SYNTH_FN uint8_t synth_f32_to_e2m1(float f) {
   const float a = c.f;
   const int code = (a > 0.25f) + (a >= 0.75f) + (a > 1.25f) + (a >= 1.75f) + (a > 2.5f) + (a >= 3.5f) + (a > 5.0f);
   return (uint8_t)(sign | (uint8_t)code);
+}
+
+/* One block of a block-scaled 4-bit row: `count` (even, <= 32) consecutive elements starting at the
+ * even element `first` of stream `key` share a power-of-two scale 2^e, stored as the byte e + 127.
+ * e = floor(log2(largest magnitude)) - 2, so the largest element lands in [4, 8) before rounding
+ * (magnitudes above 6 saturate at 6); a block of zeros gets e = 0.  Each element is then rounded
+ * to an FP4 E2M1 nibble of value / 2^e.  codes: count / 2 bytes, even element in the low nibble.
+ * Integer exponent arithmetic and exact power-of-two scaling only: host and device agree. */
+SYNTH_FN uint8_t synth_fp4_block(uint64_t key, uint64_t first, int count, double sigma, uint8_t* codes) {
+  float v[32];
+  uint32_t amax_bits = 0;
+  for (int p = 0; p < count / 2; ++p) {
+    double z0, z1;
+    synth_normal_pair(key, first / 2 + (uint64_t)p, &z0, &z1);
+    v[2 * p] = (float)(sigma * z0);
+    v[2 * p + 1] = (float)(sigma * z1);
+  }
+  for (int j = 0; j < count; ++j) {
+    union { float f; uint32_t u; } c;
+    c.f = v[j];
+    const uint32_t a = c.u & 0x7fffffffu;
+    if (a > amax_bits) amax_bits = a;   /* magnitudes of finite floats order like their bit patterns */
+  }
+  int e = 0;
+  if (amax_bits >= 0x00800000u) {       /* a normal number: its exponent field is floor(log2) + 127 */
+    e = (int)(amax_bits >> 23) - 127 - 2;
+    if (e < -120) e = -120;
+    if (e > 120) e = 120;
+  }
+  union { float f; uint32_t u; } inv;
+  inv.u = (uint32_t)(127 - e) << 23;    /* 2^-e */
+  for (int p = 0; p < count / 2; ++p)
+    codes[p] = (uint8_t)(synth_f32_to_e2m1(v[2 * p] * inv.f) | (synth_f32_to_e2m1(v[2 * p + 1] * inv.f) << 4));
+  return (uint8_t)(e + 127);
 }
 
 /* Uniform integer in [0, range) for element i. */

@@ -45,6 +45,21 @@ __global__ void __launch_bounds__(256) fill_normal_kernel(void* dst, int64_t n, 
   }
 }
 
+// one thread per 32-column block of a block-scaled 4-bit matrix
+__global__ void __launch_bounds__(256) fill_fp4b_kernel(uint8_t* codes, uint8_t* scales, int64_t rows, int64_t cols,
+                                                        uint64_t key, double sigma) {
+  const int64_t bpr = (cols + 31) / 32;
+  for (int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; b < rows * bpr; b += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = b / bpr, j = b % bpr;
+    const int count = (int)(cols - 32 * j < 32 ? cols - 32 * j : 32);
+    uint8_t c[16];
+    const uint8_t sc = synth_fp4_block(key, (uint64_t)(r * cols + 32 * j), count, sigma, c);
+    uint8_t* d = codes + (r * cols + 32 * j) / 2;
+    for (int p = 0; p < count / 2; ++p) d[p] = c[p];
+    scales[b] = sc;
+  }
+}
+
 __global__ void __launch_bounds__(256) fill_uniform_int_kernel(int32_t* dst, int64_t n,
                                                                uint64_t key, uint32_t range) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
@@ -72,6 +87,19 @@ extern "C" int synth_fill_normal_device(void* dst, int64_t n, uint64_t seed, uin
     fill_normal_kernel<2><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
   else
     fill_normal_kernel<3><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(dst, n, key, sigma);
+  return hipGetLastError() == hipSuccess ? 0 : -2;
+}
+
+// codes[rows][cols / 2] and scales[rows][ceil(cols / 32)] on the device. Asynchronous on `stream`.
+extern "C" int synth_fill_normal_fp4b_device(uint8_t* codes, uint8_t* scales, int64_t rows, int64_t cols, uint64_t seed,
+                                             uint64_t stream_id, double sigma, void* stream) {
+  if (!codes || !scales || rows < 0 || cols < 0 || (cols & 1)) return -1;
+  const int64_t blocks_total = rows * ((cols + 31) / 32);
+  if (blocks_total == 0) return 0;
+  int64_t blocks = (blocks_total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  fill_fp4b_kernel<<<dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream>>>(codes, scales, rows, cols,
+                                                                                   synth_key(seed, stream_id), sigma);
   return hipGetLastError() == hipSuccess ? 0 : -2;
 }
 

@@ -32,6 +32,22 @@ int synth_fill_normal_host(void* dst, int64_t n, uint64_t seed, uint64_t stream_
   return 0;
 }
 
+/* Block-scaled 4-bit matrix [rows][cols] (cols even): codes[rows][cols / 2] and
+ * scales[rows][ceil(cols / 32)]; a row's last block may be shorter than 32. */
+int synth_fill_normal_fp4b_host(uint8_t* codes, uint8_t* scales, int64_t rows, int64_t cols, uint64_t seed,
+                                uint64_t stream_id, double sigma) {
+  if (!codes || !scales || rows < 0 || cols < 0 || (cols & 1)) return -1;
+  const uint64_t key = synth_key(seed, stream_id);
+  const int64_t bpr = (cols + 31) / 32;
+#pragma omp parallel for schedule(static)
+  for (int64_t b = 0; b < rows * bpr; ++b) {
+    const int64_t r = b / bpr, j = b % bpr;
+    const int count = (int)(cols - 32 * j < 32 ? cols - 32 * j : 32);
+    scales[b] = synth_fp4_block(key, (uint64_t)(r * cols + 32 * j), count, sigma, codes + (r * cols + 32 * j) / 2);
+  }
+  return 0;
+}
+
 int synth_fill_uniform_int_host(int32_t* dst, int64_t n, uint64_t seed, uint64_t stream_id,
                                 uint32_t range) {
   if (!dst || n < 0 || range == 0) return -1;

@@ -2,7 +2,8 @@
 """Writes the stored expected values under tests/golden/ by running the CPU oracle only.
 
 Usage: python tests/golden/make_golden.py [case ...]   (cases: llama7b_linear, llama7b_w8_linear, llama7b_w4_linear, llama7b_runs,
-tinyllama_decode, llama70b_layer, llama70b_w8_layer, llama70b_w4_layer, llama7b_full, llama70b_full)
+tinyllama_decode, llama70b_layer, llama70b_w8_layer, llama70b_w4_layer, llama7b_w4b_linear, llama70b_w4b_layer,
+llama7b_full, llama70b_full)
 Every value comes from oracle/ on the seeded synthetic inputs of synth/; nothing here touches
 the HIP library.  The JSON files are small: per logits row the argmax, the top-2 gap, the row's
 max |logit| and the logits at a fixed sample of columns.  The *_full cases store whole logits
@@ -76,6 +77,11 @@ def llama7b_w8_linear(shape_name="llama7b_w8"):
 
 def llama7b_w4_linear():
     return llama7b_w8_linear("llama7b_w4")
+
+
+def llama7b_w4b_linear():
+    """4-bit weight matrices with one power-of-two scale per 32 columns of a row."""
+    return llama7b_w8_linear("llama7b_w4b")
 
 
 def llama7b_runs():
@@ -178,6 +184,10 @@ def llama70b_w4_layer():
     return llama70b_layer("llama70b_w4")
 
 
+def llama70b_w4b_layer():
+    return llama70b_layer("llama70b_w4b")
+
+
 def _stack_layer_by_layer(sh, seed, T, batches, keep_hidden_after=(), keep_cells_of=()):
     """The whole stack for several batch sizes in ONE pass over the layers: a layer's weights
     are generated once, every batch goes through that layer as a stage of its own ([l, l+1),
@@ -189,10 +199,8 @@ def _stack_layer_by_layer(sh, seed, T, batches, keep_hidden_after=(), keep_cells
     def weights(name, layer):
         key = (name, layer)
         if key not in store:
-            t = synth.weight_host(sh, seed, from_synth._NAME_TO_KIND[name], layer, 0.0)
-            if t.dtype == np.uint8:
-                t = (from_synth.dequantise_fp4 if sh.weight_format == "fp4" else from_synth.dequantise_fp8)(t, sh.weight_scale_exp2)
-            store[key] = t
+            kind = from_synth._NAME_TO_KIND[name]
+            store[key] = from_synth.dequantise(sh, kind, synth.weight_host(sh, seed, kind, layer, 0.0))
         return store[key]
 
     om = oracle.OracleModel(sh, weights)
@@ -264,7 +272,8 @@ def llama70b_full():
 CASES = {"llama7b_full": llama7b_full, "llama70b_full": llama70b_full,
          "llama7b_linear": llama7b_linear, "llama7b_w8_linear": llama7b_w8_linear, "llama7b_w4_linear": llama7b_w4_linear, "llama7b_runs": llama7b_runs, "tinyllama_decode": tinyllama_decode,
          "llama70b_layer": llama70b_layer, "llama70b_w8_layer": llama70b_w8_layer,
-         "llama70b_w4_layer": llama70b_w4_layer}
+         "llama70b_w4_layer": llama70b_w4_layer, "llama7b_w4b_linear": llama7b_w4b_linear,
+         "llama70b_w4b_layer": llama70b_w4b_layer}
 
 if __name__ == "__main__":
     for name in (sys.argv[1:] or list(CASES)):

@@ -60,7 +60,8 @@ def test_null_and_shape_arguments_are_refused_without_touching_a_device():
     ok = dict(n_layers=1, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn=256, vocab=64, rms_eps=1e-5,
               rope_base=10000.0, max_pos=16)
     for bad in (dict(dtype=0, weight_dtype=2), dict(dtype=1, weight_dtype=2, weight_scale_exp2=40),
-                dict(dtype=1, weight_dtype=4), dict(dtype=0, weight_dtype=3), dict(dtype=0, weight_dtype=1)):
+                dict(dtype=1, weight_dtype=5), dict(dtype=0, weight_dtype=3), dict(dtype=0, weight_dtype=1),
+                dict(dtype=0, weight_dtype=4), dict(dtype=1, weight_dtype=4, weight_scale_exp2=-6)):   # block scales: bf16 model only, no model-wide scale
         cfg2 = pi.binding.PiModelConfig(**ok, **bad)
         assert lib.pi_model_load(ctypes.byref(cfg2), ctypes.byref(out)) == pi.binding.PI_E_SHAPE, bad
     assert lib.pi_stage_forward(None, None, None, 0, 1, None, None, None, None, None, None) == pi.binding.PI_E_ARG

@@ -127,7 +127,7 @@ def test_llama7b_every_logit_column_matches_oracle(llama7b):
     assert len(kv) == T
 
 
-@pytest.mark.parametrize("shape_name", ["llama7b_w8", "llama7b_w4"])
+@pytest.mark.parametrize("shape_name", ["llama7b_w8", "llama7b_w4", "llama7b_w4b"])
 def test_llama7b_with_quantised_weights_matches_oracle(shape_name):
     """The same shape with FP8 E4M3 (one byte per weight) or FP4 E2M1 (half a byte) weight
     matrices: sampled logits against the oracle evaluated on the dequantised weights."""
@@ -139,7 +139,11 @@ def test_llama7b_with_quantised_weights_matches_oracle(shape_name):
         assert layer_bytes == sh.layer_params and lm_bytes == sh.vocab * sh.d_model  # one byte per weight
     else:   # half a byte per weight; the down projection's 86 tiles of 128 columns are padded to 88
         pad = sh.d_model * (88 * 128 - sh.ffn) // 2
-        assert layer_bytes == sh.layer_params // 2 + pad and lm_bytes == sh.vocab * sh.d_model // 2
+        codes, lm_codes = sh.layer_params // 2 + pad, sh.vocab * sh.d_model // 2
+        if sh.weight_format == "fp4b":   # and one scale byte per 32 columns: a sixteenth on top
+            assert layer_bytes == codes + codes // 16 and lm_bytes == lm_codes + lm_codes // 16
+        else:
+            assert layer_bytes == codes and lm_bytes == lm_codes
     T = g["prefix"]
     kv = pi.KVCache(m, T + 64)
     gpu_loader.prefill_kv_synthetic(kv, sh, g["seed"], T)
@@ -424,7 +428,7 @@ def test_tinyllama_decode_steps_match_oracle():
         m.free()
 
 
-@pytest.mark.parametrize("shape_name", ["llama70b", "llama70b_w8", "llama70b_w4"])
+@pytest.mark.parametrize("shape_name", ["llama70b", "llama70b_w8", "llama70b_w4", "llama70b_w4b"])
 def test_llama70b_shaped_layer_matches_oracle(shape_name):
     """One decoder layer plus the LM head of the Llama-70B shape (d 8192, 64 query / 8 KV heads,
     FFN 28672) over 2048 prefix cells, batches of 1 and 16 tokens: the widest matrices, the most

@@ -45,7 +45,11 @@ def tiny_truth():
     gm.free()
 
 
-@pytest.mark.parametrize("alpha,depth,mb,cutoff,rpp", [
+def _settings(*rows):
+    return [r if len(r) == 6 else r + (None,) for r in rows]
+
+
+@pytest.mark.parametrize("alpha,depth,mb,cutoff,rpp,beta", _settings(
     (0.7, 3, 4, (0.3, 0.05, 0.05), 1),
     (0.3, 2, 2, (0.5, 0.1, 0.2), 1),
     (1.0, 4, 4, (0.0, 0.0, 0.0), 1),        # every draft right, never a cutoff stop
@@ -54,8 +58,11 @@ def tiny_truth():
     (0.7, 2, 4, (0.1, 0.03, 0.05), 4),      # several runs share a pass over the weights
     (0.9, 1, 3, (0.0, 0.0, 0.0), 6),        # one pass in flight, up to six runs and sixteen tokens in it
     (0.3, 3, 1, (0.2, 0.05, 0.05), 3),      # one-token micro-batches
-])
-def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutoff, rpp):
+    (0.5, 3, 4, (0.1, 0.03, 0.05), 1, 0.8), # token trees: a chain plus the draft's second choice as a sibling leaf
+    (0.6, 2, 3, (0.0, 0.0, 0.0), 4, 0.5),   # trees, several per weight pass
+    (0.0, 2, 4, (0.0, 0.0, 0.0), 1, 1.0),   # the chain is always wrong at once and the second choice always right
+))
+def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutoff, rpp, beta):
     sh, T, first, G, safe, gm = tiny_truth
     n_gen = min(safe, 64)
     gkv = pi.KVCache(gm, 176)
@@ -69,8 +76,21 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
         right = u[2 * i] < alpha * (1 << 20)
         return (g if right else (g + 1 + int(u[2 * i]) % 7) % sh.vocab), float(u[2 * i + 1]) / (1 << 20)
 
+    u2 = synth.uniform_int_host(len(G) + 64, 23, synth.stream_id(synth.T_MISC, 7), 1 << 20)
+
+    def alternative(pos):
+        """The draft's second choice: where its first choice is wrong it is the target's token with
+        probability beta; otherwise some other token (a sibling that will be rejected)."""
+        i = pos - (T + 1)
+        g = G[i] if i < len(G) else 0
+        first_right = u[2 * i] < alpha * (1 << 20)
+        if not first_right and u2[i] < beta * (1 << 20):
+            return g
+        return (g + 9 + int(u2[i]) % 5) % sh.vocab
+
     cs = ContinuousSpeculation(gm, gkv, T, first, draft, depth=depth, micro_batch=mb, base_cutoff=cutoff[0],
-                               recovery=cutoff[1], decay=cutoff[2], runs_per_pass=rpp)
+                               recovery=cutoff[1], decay=cutoff[2], runs_per_pass=rpp,
+                               alternative=alternative if beta is not None else None)
     out = cs.generate(n_gen)
     st = cs.stats
     assert out == G[:n_gen], "first difference at %d" % next(i for i in range(n_gen) if out[i] != G[i])
@@ -87,12 +107,16 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
         assert st["passes"] < st["runs"]
     if alpha == 1.0:
         assert st["cancelled"] == 0 and st["tokens_accepted_from_drafts"] >= n_gen - st["non_speculative"] - 4
-    if alpha == 0.0:
+    if alpha == 0.0 and beta is None:
         assert st["tokens_accepted_from_drafts"] == 0 and st["non_speculative"] >= n_gen
     if 0.0 < alpha < 1.0:
         assert st["tokens_accepted_from_drafts"] > 0
     if alpha < 1.0:
         assert st["discarded"] > 0                                    # runs built on a rejected token were thrown away
     assert st["compactions"] >= 1
+    if beta is None:
+        assert st["tree_runs"] == 0
+    else:
+        assert st["tree_runs"] > 0 and st["alternatives_accepted"] > 0   # second choices did stand in for wrong first ones
     cs.close()
     print("alpha %.1f depth %d mb %d runs/pass %d: %s" % (alpha, depth, mb, rpp, st))

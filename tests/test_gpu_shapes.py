@@ -30,6 +30,9 @@ ODD_SHAPES = {
                                      weight_scale_exp2=-6),
     "odd_w4_gqa8": synth.ModelShape("odd_w4_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="bf16", weight_format="fp4",
                                     weight_scale_exp2=-5),
+    # 4-bit weight matrices with a scale per 32 columns: rows that end in a half block (1040 = 32 * 32 + 16)
+    "odd_w4b_hd128": synth.ModelShape("odd_w4b_hd128", 1, 384, 3, 3, 128, 1040, 2000, dtype="bf16", weight_format="fp4b"),
+    "odd_w4b_gqa8": synth.ModelShape("odd_w4b_gqa8", 2, 512, 16, 2, 32, 1376, 1024, dtype="bf16", weight_format="fp4b"),
 }
 
 

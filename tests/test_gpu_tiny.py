@@ -26,6 +26,15 @@ def check_logits(gpu, ref, dtype):
 
 
 def test_device_fill_equals_host_fill():
+    # block-scaled 4-bit matrices: codes and scales, a ragged last block per row
+    rows, cols = 37, 688
+    nc, ns = synth.fp4b_sizes(rows, cols)
+    t = torch.empty(nc + ns, dtype=torch.uint8, device="cuda")
+    sid = synth.stream_id(synth.T_WG, 3)
+    assert synth.hip_lib().synth_fill_normal_fp4b_device(t.data_ptr(), t.data_ptr() + nc, rows, cols, 5, sid, 0.02,
+                                                         torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(t.cpu().numpy(), synth.normal_fp4b_host(rows, cols, 5, sid, 0.02))
     for dtype in ("f32", "bf16", "fp8", "fp4"):
         n = 1_000_003 if dtype != "fp4" else 1_000_004        # two 4-bit values per byte
         sid = synth.stream_id(synth.T_WD, 7)
@@ -63,7 +72,7 @@ def _true_prefill(sh, seed, gain_sigma, n_prefill, n_cells):
 
 @pytest.mark.parametrize("shape_name,gain_sigma", [("tiny", 0.0), ("tiny", 0.1), ("tiny_bf16", 0.1), ("tiny_gqa", 0.1),
                                                    ("tiny_w8", 0.1), ("tiny_gqa_w8", 0.1), ("tiny_w4", 0.1),
-                                                   ("tiny_gqa_w4", 0.1)])
+                                                   ("tiny_gqa_w4", 0.1), ("tiny_w4b", 0.1), ("tiny_gqa_w4b", 0.1)])
 def test_planted_draft_verify_and_rollback(shape_name, gain_sigma):
     """Tiny configuration: 64 prefilled positions, 4 draft tokens planted to agree with the
     oracle's argmax for the first 2; accepted count, bonus token and kv_len must match."""

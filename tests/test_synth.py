@@ -175,3 +175,59 @@ def test_e2m1_codes_rounding_and_packing():
     assert q.shape == (2000,) and np.array_equal(q & 0xF, codes[0::2]) and np.array_equal(q >> 4, codes[1::2])
     w = from_synth.dequantise_fp4(q.reshape(40, 50), -6)
     assert w.shape == (40, 100) and np.array_equal(w.reshape(-1).astype(np.float64), t[codes] / 64)
+
+
+# ---- 4-bit weights with one scale per 32 columns ---------------------------------------------------------
+
+def test_block_scaled_fp4_scale_rule_rounding_and_layout():
+    """Per block of 32 columns of a row: scale byte - 127 = floor(log2(largest magnitude)) - 2, so
+    the largest element lands in [4, 8) before rounding; every nibble is the nearest E2M1 code of
+    value / 2^e (checked against the plain rounding, itself pinned by brute force above); the
+    decoded weight is within half a step of the value, or saturated at 6 * 2^e."""
+    from oracle import from_synth
+    rows, cols = 24, 688                      # 21 whole blocks and one of 16 columns per row
+    sid = synth.stream_id(synth.T_WD, 1)
+    buf = synth.normal_fp4b_host(rows, cols, 7, sid, 0.02)
+    codes, scales = synth.split_fp4b(buf, rows, cols)
+    assert codes.shape == (rows, cols // 2) and scales.shape == (rows, 22) and buf.size == rows * (cols // 2 + 22)
+    f = synth.normal_host(rows * cols, 7, sid, 0.02, "f32").reshape(rows, cols).astype(np.float64)
+    w = from_synth.dequantise_fp4_blocks(codes, scales).astype(np.float64)
+    assert w.shape == (rows, cols)
+    for r in range(rows):
+        for b in range(22):
+            blk = f[r, 32 * b:32 * b + 32]
+            e = int(np.floor(np.log2(np.max(np.abs(blk))))) - 2
+            assert scales[r, b] == e + 127
+            assert 4.0 <= np.max(np.abs(blk)) / 2.0 ** e < 8.0
+            want = synth.f32_to_e2m1_host((blk / 2.0 ** e).astype(np.float32))
+            got = np.empty(len(blk), dtype=np.uint8)
+            got[0::2] = codes[r, 16 * b:16 * b + len(blk) // 2] & 0xF
+            got[1::2] = codes[r, 16 * b:16 * b + len(blk) // 2] >> 4
+            assert np.array_equal(got, want)
+            dec = w[r, 32 * b:32 * b + 32]
+            assert np.array_equal(dec, from_synth.E2M1[got] * 2.0 ** e)
+            # error: half the local step (0.25, 0.5 or 1 in units of 2^e), or saturation above 6
+            err = np.abs(dec - blk) / 2.0 ** e
+            a = np.abs(blk) / 2.0 ** e
+            bound = np.where(a <= 2.0, 0.25, np.where(a <= 4.0, 0.5, np.where(a <= 6.0, 1.0, a - 6.0)))
+            assert np.all(err <= bound + 1e-12)
+    # the quantiser keeps what a 4-bit format can: relative error of the whole matrix
+    assert np.linalg.norm(w - f) / np.linalg.norm(f) < 0.12
+    # known bytes -> known values (scale 125 = 2^-2, codes 0x7 = 6, 0x9 = -0.5; scale 130 = 2^3 in the next block)
+    c = np.zeros((1, 32), dtype=np.uint8)
+    c[0, 0] = 0x97
+    c[0, 16] = 0x21
+    s_ = np.array([[125, 130]], dtype=np.uint8)
+    d = from_synth.dequantise_fp4_blocks(c, s_)
+    assert d[0, :2].tolist() == [1.5, -0.125] and d[0, 32:34].tolist() == [4.0, 8.0] and not d[0, 2:32].any()
+
+
+def test_block_scaled_model_decodes_through_the_oracle_loader():
+    from oracle import from_synth
+    sh = synth.SHAPES["tiny_w4b"]
+    om = from_synth.model_from_seed(sh, 0)
+    wd = om.w("wd", 1)
+    assert wd.shape == (sh.d_model, sh.ffn)
+    f = synth.normal_host(sh.d_model * sh.ffn, 0, synth.stream_id(synth.T_WD, 1), 0.02, "f32").reshape(sh.d_model, sh.ffn)
+    assert np.linalg.norm(wd - f) / np.linalg.norm(f) < 0.12
+    assert om.w("embed").dtype == np.float64 and om.w("embed").shape == (sh.vocab, sh.d_model)
