@@ -227,6 +227,31 @@ __device__ __forceinline__ MatDev uni_mat(const MatDev& m) {
   r.KT = uni(m.KT);
   return r;
 }
+// The per-layer table does not change while a kernel runs and the layer index is the same in every
+// lane: read through the constant address space it comes by scalar loads, straight into scalar
+// registers and through the scalar cache, instead of a vector load whose ~1 us the wave would sit
+// out at the top of every phase.
+typedef const __attribute__((address_space(4))) LayerDev* LayerTab;
+__device__ __forceinline__ MatDev tab_mat(const __attribute__((address_space(4))) MatDev& m) {
+  MatDev r;
+  r.w = m.w;
+  r.s = m.s;
+  r.N = m.N;
+  r.K = m.K;
+  r.NRB = m.NRB;
+  r.KT = m.KT;
+  return r;
+}
+__device__ __forceinline__ LayerDev tab_layer(LayerTab t, int l) {
+  LayerDev r;
+  r.qkv = tab_mat(t[l].qkv);
+  r.o = tab_mat(t[l].o);
+  r.gateup = tab_mat(t[l].gateup);
+  r.down = tab_mat(t[l].down);
+  r.attn_gain = t[l].attn_gain;
+  r.ffn_gain = t[l].ffn_gain;
+  return r;
+}
 __device__ __forceinline__ LayerDev uni_layer(const LayerDev& l) {
   LayerDev r;
   r.qkv = uni_mat(l.qkv);
@@ -1512,7 +1537,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   bool dead = dead_tokens == all_tokens;  // nothing left to do
   if (ok && !dead) {
     embed_phase(A);
-    stream_init<DT>(S, uni_mat(A.layers[A.layer_begin].qkv), A.sk[0], wave);
+    stream_init<DT>(S, tab_mat(((LayerTab)A.layers)[A.layer_begin].qkv), A.sk[0], wave);
     ok = grid_barrier(A, bc, -1, false);
   }
   // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
@@ -1528,7 +1553,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
                                      bc.epoch + 1, bar_sh)))
         break;
       wg_mark(A, l * 8 + 1, 2);
-      stream_init<DT>(S, uni_mat(A.layers[l].o), A.sk[1], wave);
+      stream_init<DT>(S, tab_mat(((LayerTab)A.layers)[l].o), A.sk[1], wave);
       // No grid barrier here: the output projection asks for its weights at once and reads the
       // attention output until no piece of it is "empty" any more (the merging workgroups are
       // the last to finish this phase; everyone else's weight requests travel meanwhile).
@@ -1562,7 +1587,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       M = A.lm_head; sk = A.sk[4]; xin = A.x; gain = A.final_gain; scaled = true;
       e.epi = EPI_LOGITS; e.out = A.logits_out; has_next = false; nxt = M;
     } else {
-      const LayerDev W = uni_layer(A.layers[l]);
+      const LayerDev W = tab_layer((LayerTab)A.layers, l);
       if (k == 0) {  // RMSNorm + QKV projection + RoPE + KV write
         M = W.qkv; sk = A.sk[0]; xin = A.x; gain = W.attn_gain; scaled = true;
         e.epi = EPI_QKV; e.out = A.q; has_next = false; nxt = M;
@@ -1574,7 +1599,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       } else {  // down projection + residual; then the next layer's QKV or the LM head
         M = W.down; sk = A.sk[3]; xin = A.a; e.epi = EPI_RESID; e.out = A.x;
         if (l + 1 < A.layer_end) {
-          nxt = uni_mat(A.layers[l + 1].qkv); nsk = A.sk[0];
+          nxt = tab_mat(((LayerTab)A.layers)[l + 1].qkv); nsk = A.sk[0];
         } else if (A.layer_end == L) {
           nxt = A.lm_head; nsk = A.sk[4];
         } else {
