@@ -71,7 +71,9 @@ __device__ __forceinline__ void wave_drain() { asm volatile("s_waitcnt vmcnt(0) 
 // (vmcnt = 0; the export and LDS/scalar counters are left alone)
 __device__ __forceinline__ void wave_settle() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 __device__ __forceinline__ void wg_mark(const StageArgs& A, int l, int ev) {
-  if (A.wgtrace && l == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + ev] = wall_clock64();  // l: layer * 8 + phase kind
+  // l: layer * 8 + phase kind; one row of 8 stamps per workgroup and phase of the traced layer
+  if (A.wgtrace && (l >> 3) == A.wgtrace_layer && (l & 7) < 5 && threadIdx.x == 0)
+    A.wgtrace[(blockIdx.x * 5 + (l & 7)) * 8 + ev] = wall_clock64();
 }
 
 // Bounded waits read the clock only once a wait has lasted a while: a clock read is a scalar
@@ -112,7 +114,8 @@ struct BarrierCtx {
 // boundaries are never adjacent, so it reads the same set.)  sh[1] is that set.
 __device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
   __syncthreads();  // every wave of this workgroup has drained its stores
-  if (A.wgtrace && mark == A.wgtrace_layer && threadIdx.x == 0) A.wgtrace[blockIdx.x * 8 + 4] = wall_clock64();
+  if (A.wgtrace && mark >= 0 && (mark >> 3) == A.wgtrace_layer && (mark & 7) < 5 && threadIdx.x == 0)
+    A.wgtrace[(blockIdx.x * 5 + (mark & 7)) * 8 + 4] = wall_clock64();
   bc.epoch += 1;
   StageSync* sy = A.sync;
   if (threadIdx.x < 64) {
