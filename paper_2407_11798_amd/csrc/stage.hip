@@ -255,6 +255,12 @@ __device__ __forceinline__ LayerDev tab_layer(LayerTab t, int l) {
   r.ffn_gain = t[l].ffn_gain;
   return r;
 }
+// (The block-scaled kernel, which also carries the scale plane's descriptor through its streaming loop,
+// is the one variant that measures slower with the table in scalar registers: it keeps the vector load.)
+template <int DT>
+__device__ __forceinline__ MatDev table_mat(const StageArgs& A, int l, int which);
+template <int DT>
+__device__ __forceinline__ LayerDev table_layer(const StageArgs& A, int l);
 __device__ __forceinline__ LayerDev uni_layer(const LayerDev& l) {
   LayerDev r;
   r.qkv = uni_mat(l.qkv);
@@ -264,6 +270,17 @@ __device__ __forceinline__ LayerDev uni_layer(const LayerDev& l) {
   r.attn_gain = uni_ptr(l.attn_gain);
   r.ffn_gain = uni_ptr(l.ffn_gain);
   return r;
+}
+
+template <int DT>
+__device__ __forceinline__ MatDev table_mat(const StageArgs& A, int l, int which) {  // which: 0 QKV, 1 O
+  if constexpr (DT == kWeightFP4B) return uni_mat(which == 0 ? A.layers[l].qkv : A.layers[l].o);
+  else return tab_mat(which == 0 ? ((LayerTab)A.layers)[l].qkv : ((LayerTab)A.layers)[l].o);
+}
+template <int DT>
+__device__ __forceinline__ LayerDev table_layer(const StageArgs& A, int l) {
+  if constexpr (DT == kWeightFP4B) return uni_layer(A.layers[l]);
+  else return tab_layer((LayerTab)A.layers, l);
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
@@ -1540,7 +1557,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   bool dead = dead_tokens == all_tokens;  // nothing left to do
   if (ok && !dead) {
     embed_phase(A);
-    stream_init<DT>(S, tab_mat(((LayerTab)A.layers)[A.layer_begin].qkv), A.sk[0], wave);
+    stream_init<DT>(S, table_mat<DT>(A, A.layer_begin, 0), A.sk[0], wave);
     ok = grid_barrier(A, bc, -1, false);
   }
   // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
@@ -1556,7 +1573,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
                                      bc.epoch + 1, bar_sh)))
         break;
       wg_mark(A, l * 8 + 1, 2);
-      stream_init<DT>(S, tab_mat(((LayerTab)A.layers)[l].o), A.sk[1], wave);
+      stream_init<DT>(S, table_mat<DT>(A, l, 1), A.sk[1], wave);
       // No grid barrier here: the output projection asks for its weights at once and reads the
       // attention output until no piece of it is "empty" any more (the merging workgroups are
       // the last to finish this phase; everyone else's weight requests travel meanwhile).
@@ -1590,7 +1607,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       M = A.lm_head; sk = A.sk[4]; xin = A.x; gain = A.final_gain; scaled = true;
       e.epi = EPI_LOGITS; e.out = A.logits_out; has_next = false; nxt = M;
     } else {
-      const LayerDev W = tab_layer((LayerTab)A.layers, l);
+      const LayerDev W = table_layer<DT>(A, l);
       if (k == 0) {  // RMSNorm + QKV projection + RoPE + KV write
         M = W.qkv; sk = A.sk[0]; xin = A.x; gain = W.attn_gain; scaled = true;
         e.epi = EPI_QKV; e.out = A.q; has_next = false; nxt = M;
@@ -1602,7 +1619,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       } else {  // down projection + residual; then the next layer's QKV or the LM head
         M = W.down; sk = A.sk[3]; xin = A.a; e.epi = EPI_RESID; e.out = A.x;
         if (l + 1 < A.layer_end) {
-          nxt = tab_mat(((LayerTab)A.layers)[l + 1].qkv); nsk = A.sk[0];
+          nxt = table_mat<DT>(A, l + 1, 0); nsk = A.sk[0];
         } else if (A.layer_end == L) {
           nxt = A.lm_head; nsk = A.sk[4];
         } else {
