@@ -443,7 +443,10 @@ const char* pi_strerror(int32_t status);
  * makes later runs record the barrier timestamps pi_debug_read_trace returns (off by default:
  * reading the clock at every barrier costs time).  phase 6: s_k = KiB of LDS the staged
  * activations of every projection phase should stay under (16 .. 150; 0 restores the built-in choice):
- * a larger figure means fewer column slices and more staging per workgroup. */
+ * a larger figure means fewer column slices and more staging per workgroup.  phase 7: s_k = weight tiles
+ * (1 KiB each) a wave may ask for ahead of a phase, into LDS, while it waits for the phase to begin
+ * (0 restores the built-in choice, 1 = none, otherwise an even figure up to 64; always limited by the
+ * LDS the projection phases leave free). */
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],

@@ -1,4 +1,5 @@
 // The C ABI (include/pipeinfer.h): handles, host-side validation, the per-layer launch sequence.
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -13,6 +14,8 @@ using namespace pi;
 namespace {
 
 constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS the QKV phase should take (there a second slice beats a fuller LDS)
+constexpr size_t kLdsLimit = 159 * 1024;      // dynamic LDS of a workgroup (160 KiB per compute unit; a little is static)
+constexpr int kParkMax = 16;                  // tiles a wave may ask for ahead of a phase (1 KiB of LDS each)
 constexpr size_t kProjLdsLimit = 150 * 1024;  // ... and may take where no split fits the budget (160 KiB; a little is static)
 constexpr unsigned long long kBarrierTimeoutTicks = 200000000ull;  // 2 s of the 100 MHz clock
 
@@ -43,6 +46,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
+  int park_override = 0;  // tuning hook: 0 = built-in rule, 1 = no tiles ahead of a phase, else the cap per wave
   size_t lds_budget = 0;  // tuning hook: what every projection phase's split aims to stay under (0: built-in per phase)
   size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
   int wdtype = PI_DTYPE_BF16;  // format of the weight matrices (cfg.dtype, or 8-bit)
@@ -147,6 +151,7 @@ struct StagePlan {
   int min_nt;
   size_t lds;
   size_t part_tiles;  // 1 KiB tiles that cross slices
+  int pf_cap[5], pf_base[5];  // per phase: tiles per wave asked for ahead of it; where their LDS regions begin
 };
 
 bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
@@ -168,6 +173,30 @@ bool make_stage_plan(const pi_model* m, int n, StagePlan* p) {
     const size_t lds = stage_proj_lds_bytes(n, m->kt32() * nt, (mats[ph]->NRB + gs - 1) / gs);
     if (lds > p->lds) p->lds = lds;
     if (sk > 1 && (size_t)sk * mats[ph]->NRB > p->part_tiles) p->part_tiles = (size_t)sk * mats[ph]->NRB;
+  }
+  // What LDS a projection phase leaves free holds tiles asked for ahead of it (an equal region per
+  // wave).  They are asked for while the workgroup waits at the grid barrier before the phase, or
+  // after attention -- nothing else of the workgroup is in LDS then -- except those of the down
+  // projection, which a wave asks for while other waves still stream gate/up.  (The attention phase
+  // may use the same bytes: no tiles wait while it runs.)
+  size_t need[5];
+  for (int ph = 0; ph < 5; ++ph) {
+    const int gs = m->grid / p->sk[ph];
+    need[ph] = stage_proj_lds_bytes(n, m->kt32() * (mats[ph]->KT / p->sk[ph]), (mats[ph]->NRB + gs - 1) / gs);
+  }
+  // (one geometry for both, so that a wave's region for the down projection is its own region of
+  // gate/up, which only it has touched)
+  need[2] = need[3] = std::max(need[2], need[3]);
+  const bool parks = weight_tile_bytes(m->wdtype) == 1024 && m->wdtype != kWeightFP4B && m->park_override != 1;
+  for (int ph = 0; ph < 5; ++ph) {
+    p->pf_base[ph] = (int)((need[ph] + 1023) / 1024 * 1024);
+    const int room = (int)(((long)kLdsLimit - p->pf_base[ph]) / (1024 * (kStageThreads / 64)));
+    // (a sliced output projection has sixteen tiles per wave and no time to spare before it: asking for
+    // more than half of them ahead measures slower)
+    const int want = m->park_override > 1 ? m->park_override : (ph == 1 && p->sk[1] > 1 ? kParkMax / 2 : kParkMax);
+    p->pf_cap[ph] = parks ? std::max(0, std::min(room, want)) & ~1 : 0;
+    const size_t with_parked = (size_t)p->pf_base[ph] + (size_t)p->pf_cap[ph] * 1024 * (kStageThreads / 64);
+    if (p->pf_cap[ph] > 0 && with_parked > p->lds) p->lds = with_parked;
   }
   return true;
 }
@@ -498,9 +527,14 @@ int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
 }
 
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
-  if (!m || phase < 0 || phase > 6 || s_k < 0) return PI_E_ARG;
+  if (!m || phase < 0 || phase > 7 || s_k < 0) return PI_E_ARG;
   if (phase == 5) {
     m->trace_on = s_k != 0;
+    return PI_OK;
+  }
+  if (phase == 7) {
+    if (s_k > 64) return PI_E_ARG;
+    m->park_override = s_k;
     return PI_OK;
   }
   if (phase == 6) {
@@ -811,6 +845,10 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.rs = m->rs;
   a.sync = m->sync;
   for (int ph = 0; ph < 5; ++ph) a.sk[ph] = sp.sk[ph];
+  for (int ph = 0; ph < 5; ++ph) {
+    a.pf_cap8 |= (unsigned long long)sp.pf_cap[ph] << (8 * ph);
+    a.pf_base8 |= (unsigned long long)(sp.pf_base[ph] / 1024) << (8 * ph);
+  }
   a.attn_chunk = attn_chunk;
   a.attn_units_per_head = attn_units;
   a.timeout_ticks = kBarrierTimeoutTicks;

@@ -137,6 +137,12 @@ struct StageArgs {
   StageSync* sync;
   // work split
   int sk[5];  // column slices per projection phase: QKV, O, gate/up, down, LM head
+  // per projection phase (same order): tiles per wave that may be asked for ahead of the phase, into
+  // LDS, and the byte offset at which the eight waves' regions (pf_cap KiB each) begin -- behind what
+  // that phase, and any phase that may still run in the workgroup when they are asked for, keeps there
+  // (eight bits per phase, phase 0 lowest; the offsets in KiB: read with a shift, where an array
+  // indexed by the phase would be a load from the argument block at every use)
+  unsigned long long pf_cap8, pf_base8;
   int attn_chunk, attn_units_per_head;
   unsigned long long timeout_ticks;  // 100 MHz ticks a barrier wait may last
   unsigned epoch_base;               // barriers used by earlier launches on this model
@@ -193,5 +199,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+// Two floats -> two bf16, rounded to nearest even, in one word (the first in the low half): a vector
+// conversion, which the compiler turns into the chip's packed conversion instruction -- one
+// instruction where the integer arithmetic above takes ten.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, bf16x2));
+}
+__device__ __forceinline__ float bf16_low_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_high_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 }  // namespace pi

@@ -112,7 +112,11 @@ struct BarrierCtx {
 // boundary costs no round trip more than any other barrier.  (A workgroup that is late to look
 // may find workgroup 0's word of the NEXT barrier there; the set only changes at boundaries and
 // boundaries are never adjacent, so it reads the same set.)  sh[1] is that set.
-__device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
+// `arrived` runs in every wave once the workgroup's arrival is on its way (what a wave may usefully ask
+// memory for while it waits must not delay the arrival).
+template <typename Arrived>
+__device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark,
+                                             Arrived&& arrived) {
   __syncthreads();  // every wave of this workgroup has drained its stores
   if (A.wgtrace && mark >= 0 && (mark >> 3) == A.wgtrace_layer && (mark & 7) < 5 && threadIdx.x == 0)
     A.wgtrace[(blockIdx.x * 5 + (mark & 7)) * 8 + 4] = wall_clock64();
@@ -152,6 +156,7 @@ __device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc,
       word |= dead & 0xffffu;
     }
     if (lane == 0) __hip_atomic_store(&sy->flags[blockIdx.x], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    arrived();
     const __amdgpu_buffer_rsrc_t fr = rsrc_of(sy->flags);
     const int G = gridDim.x;
     Deadline dl;
@@ -182,9 +187,14 @@ __device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc,
       bc.sh[0] = ok;
       bc.sh[1] = dead;
     }
+  } else {
+    arrived();
   }
   __syncthreads();
   return __builtin_amdgcn_readfirstlane(bc.sh[0]) != 0;
+}
+__device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc, int layers_done, bool probe, int mark = -1) {
+  return grid_barrier(A, bc, layers_done, probe, mark, [] {});
 }
 
 // ---- per-wave weight stream -----------------------------------------------------------------
@@ -206,6 +216,7 @@ struct WaveStream {
   // loader cursor: flat index, tile within the slice's part of the row block, byte offset of the tile
   int lf, lt;
   uint32_t loff;
+  int pf;  // leading tiles of the range that were asked for ahead of the phase and wait in LDS
 };
 
 // Wave-uniform values computed with vector instructions (integer division) are moved back to
@@ -300,6 +311,7 @@ __device__ __forceinline__ void stream_make_uniform(WaveStream& S) {
   S.f0 = uni(S.f0); S.f1 = uni(S.f1); S.share = uni(S.share);
   S.slice = uni(S.slice); S.wave = uni(S.wave); S.rb0 = uni(S.rb0); S.R = uni(S.R);
   S.lf = uni(S.lf); S.lt = uni(S.lt); S.loff = (uint32_t)uni((int)S.loff);
+  S.pf = uni(S.pf);
 }
 
 template <int DT>
@@ -327,7 +339,35 @@ __device__ __forceinline__ void stream_init(WaveStream& S, const MatDev& M, int 
   const int q = uni(S.f0 / S.nt);
   S.lt = S.f0 - q * S.nt;
   S.loff = (uint32_t)((S.rb0 + q) * S.KT + S.t0 + S.lt) * (uint32_t)kTileBytes;
+  S.pf = 0;
   stream_make_uniform(S);
+}
+
+// Tiles asked for ahead of the phase.  A wave that has finished a phase has nothing to do until the
+// slowest workgroup has finished it too, and its ring lives in registers that the wait needs; but
+// the first tiles of its next range can travel meanwhile straight into LDS (no register is their
+// destination), `cap` of them at most and only tiles of the range's first row block, leaving that
+// row block at least one tile for the ring (so the streaming loop ends the row block as always).
+// The wave's own later loads (the barrier's poll, the staged activations) return behind these, in
+// order, so whatever it reads from its LDS region after those has landed.
+__device__ __forceinline__ int park_cap(const StageArgs& A, int pidx) { return (int)((A.pf_cap8 >> (8 * pidx)) & 0xffu); }
+__device__ __forceinline__ char* park_region(const StageArgs& A, char* lds, int pidx, int wave) {
+  return lds + ((int)((A.pf_base8 >> (8 * pidx)) & 0xffu) + wave * park_cap(A, pidx)) * 1024;
+}
+template <int DT>
+__device__ __forceinline__ void stream_park(WaveStream& S, char* region, int cap, int lane) {
+  if constexpr (weight_tile_bytes(DT) == 1024 && DT != kWeightFP4B) {
+    const int seg = min(S.nt - S.lt, S.f1 - S.f0) - 1;
+    const int P = uni(max(0, min(cap, seg)) & ~1);
+    const char* src = S.w + S.loff + lane * 16;
+    for (int i = 0; i < P; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + i * 1024),
+                                       (__attribute__((address_space(3))) void*)(region + i * 1024), 16, 0, 2);
+    S.pf = P;
+    S.lf += P;
+    S.lt += P;
+    S.loff += (uint32_t)(P * 1024);
+  }
 }
 
 // The ring of outstanding weight tiles: UR tiles, each 1 KiB (bf16: one 16-byte load per lane)
@@ -412,12 +452,15 @@ __device__ __forceinline__ void advance_loads(WaveStream& S, const PassPlan& P, 
   }
 }
 
-// Fill the (empty) ring with the first tiles of the wave's range.
+// Fill the (empty) ring with the first tiles of the wave's range.  `really` false: the same
+// instructions with out-of-range offsets (answered with zeros, no traffic), for a caller that must
+// not put its loads behind a branch but may not want them yet.
 template <int DT, int UR>
-__device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, int lane) {
+__device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, int lane, bool really = true) {
   constexpr int TB = Ring<DT, UR>::kTileBytes;
   PassPlan P;
   plan_loads<UR>(P, S, TB);
+  if (!really) P.nl = 0;
   issue_slots<DT, UR, 0, UR>(R, S, P, lane * 16);
   advance_loads(S, P, TB);
 }
@@ -468,13 +511,16 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
     }
   }
   const __amdgpu_buffer_rsrc_t gr = make_rsrc(gain ? gain : xin, gain ? (uint32_t)K * 4u : 0u);  // no gain: zeros, no traffic
+  // Every workgroup stages the same activations at the same moment: each starts somewhere else in
+  // the batch, so that they do not all ask the same memory channel for the same lines at once.
+  const unsigned rot = blockIdx.x * 2u;
   auto batch = [&](int id0, auto&& between) {
     f32x4 p[2][2], gq[2][2];
     int slot[2], xoff[2];
     bool in_k[2], in_items[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      const int id = id0 + q * kThreads + threadIdx.x;
+      const int id = id0 + q * kThreads + (int)((threadIdx.x + rot) & (kThreads - 1));
       const int cl = id & 3;
       const int i = (id >> 2) % n;
       const int tt = (id >> 2) / n;
@@ -528,11 +574,8 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const uint16_t h0 = f32_to_bf16_rne(v[2 * j]), h1 = f32_to_bf16_rne(v[2 * j + 1]);
-          const uint16_t l0 = f32_to_bf16_rne(v[2 * j] - bf16_to_f32(h0));
-          const uint16_t l1 = f32_to_bf16_rne(v[2 * j + 1] - bf16_to_f32(h1));
-          hi[j] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-          lo[j] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+          hi[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
+          lo[j] = pack_bf16(v[2 * j] - bf16_low_f32(hi[j]), v[2 * j + 1] - bf16_high_f32(hi[j]));
         }
         ((uint4*)lds)[slot[q]] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
         ((uint4*)lds)[slot[q] + lo_off] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
@@ -596,8 +639,7 @@ struct EpiCtx {
 __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem_idx, const float* v) {
   const __amdgpu_buffer_rsrc_t r = rsrc_of(cache);
   if (kv_dtype == PI_DTYPE_BF16) {
-    u32x2 p = {(uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16),
-               (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16)};
+    u32x2 p = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
     __builtin_amdgcn_raw_buffer_store_b64(p, r, (int)(elem_idx * 2), 0, kAgent);
   } else {
     st_ag4(r, (int)(elem_idx * 4), f32x4{v[0], v[1], v[2], v[3]});
@@ -780,6 +822,58 @@ struct PassLane {
   float wscale;    // 8-bit weights: the power-of-two scale the conversion applies
 };
 
+// One weight tile times its operand slots, added to the two accumulators.  `w` is the lane's 16 bytes of
+// the tile (fp32: `w` and `w2`, its two halves), `sc4` the lane's row's four scale bytes (block-scaled
+// weights), x0 / x1 the operand halves of the tile's 32-column parts.
+template <int DT>
+__device__ __forceinline__ void tile_mfma(ConsumeState& C, u32x4 w, u32x4 w2, uint32_t sc4, const u32x4* x0,
+                                          const u32x4* x1, float wscale) {
+  if constexpr (DT == kWeightBF16) {
+    const bf16x8 av = __builtin_bit_cast(bf16x8, w);
+    C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[0]), C.acc0, 0, 0, 0);
+    C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[0]), C.acc1, 0, 0, 0);
+  } else if constexpr (DT == kWeightFP8) {
+    // sixteen bytes -> two bf16 operands; the conversion is exact (three mantissa bits) and
+    // applies the model's power-of-two scale on the way
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      u32x4 o;
+      o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], wscale, false));
+      o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], wscale, true));
+      o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], wscale, false));
+      o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], wscale, true));
+      const bf16x8 av = __builtin_bit_cast(bf16x8, o);
+      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[h]), C.acc0, 0, 0, 0);
+      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[h]), C.acc1, 0, 0, 0);
+    }
+  } else if constexpr (weight_is_fp4(DT)) {
+    // sixteen bytes -> four bf16 operands (one per 32 columns), one byte = two weights; with
+    // block scales each of the four has the scale of its own 32 columns of the lane's row,
+    // 2^(byte - 127), which is the float whose exponent field is that byte
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      float sc = wscale;
+      if constexpr (DT == kWeightFP4B) sc = __uint_as_float(((sc4 >> (8 * h)) & 0xffu) << 23);
+      u32x4 o;
+      o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 0));
+      o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 1));
+      o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 2));
+      o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 3));
+      const bf16x8 av = __builtin_bit_cast(bf16x8, o);
+      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[h]), C.acc0, 0, 0, 0);
+      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[h]), C.acc1, 0, 0, 0);
+    }
+  } else {
+    const f32x4 w0 = __builtin_bit_cast(f32x4, w), w1 = __builtin_bit_cast(f32x4, w2);
+    const f32x4 a0 = __builtin_bit_cast(f32x4, x0[0]), a1 = __builtin_bit_cast(f32x4, x1[0]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], a0[q], C.acc0, 0, 0, 0);
+      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[q], a1[q], C.acc1, 0, 0, 0);
+    }
+  }
+}
+
 // A group of slots is consumed in a straight line behind one wave-uniform branch.  All operand
 // reads of the group are issued first and the matrix instructions follow, so the LDS latency is
 // paid once per group rather than twice per tile; a slot past the consumer's end multiplies by
@@ -806,58 +900,56 @@ __device__ __forceinline__ void consume_group(const Ring<DT, UR>& R, ConsumeStat
 #pragma unroll
   for (int j = 0; j < NG; ++j) {
     const int J = J0 + j;
-    if constexpr (DT == kWeightBF16) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, R.r[J]);
-      C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][0]), C.acc0, 0, 0, 0);
-      C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][0]), C.acc1, 0, 0, 0);
-    } else if constexpr (DT == kWeightFP8) {
-      // sixteen bytes -> two bf16 operands; the conversion is exact (three mantissa bits) and
-      // applies the model's power-of-two scale on the way
-      const u32x4 w = R.r[J];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        u32x4 o;
-        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], PLn.wscale, false));
-        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h], PLn.wscale, true));
-        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, false));
-        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[2 * h + 1], PLn.wscale, true));
-        const bf16x8 av = __builtin_bit_cast(bf16x8, o);
-        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
-        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
-      }
-    } else if constexpr (weight_is_fp4(DT)) {
-      // sixteen bytes -> four bf16 operands (one per 32 columns), one byte = two weights; with
-      // block scales each of the four has the scale of its own 32 columns of the lane's row,
-      // 2^(byte - 127), which is the float whose exponent field is that byte
-      const u32x4 w = R.r[J];
-#pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        float sc = PLn.wscale;
-        if constexpr (DT == kWeightFP4B) sc = __uint_as_float(((R.s[J] >> (8 * h)) & 0xffu) << 23);
-        u32x4 o;
-        o[0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 0));
-        o[1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 1));
-        o[2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 2));
-        o[3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w[h], sc, 3));
-        const bf16x8 av = __builtin_bit_cast(bf16x8, o);
-        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x0[j][h]), C.acc0, 0, 0, 0);
-        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, x1[j][h]), C.acc1, 0, 0, 0);
-      }
-    } else {
-      const f32x4 w0 = __builtin_bit_cast(f32x4, R.r[2 * J]), w1 = __builtin_bit_cast(f32x4, R.r[2 * J + 1]);
-      const f32x4 a0 = __builtin_bit_cast(f32x4, x0[j][0]), a1 = __builtin_bit_cast(f32x4, x1[j][0]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        C.acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w0[q], a0[q], C.acc0, 0, 0, 0);
-        C.acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[q], a1[q], C.acc1, 0, 0, 0);
-      }
-    }
+    if constexpr (DT == kWeightF32) tile_mfma<DT>(C, R.r[2 * J], R.r[2 * J + 1], 0u, x0[j], x1[j], PLn.wscale);
+    else tile_mfma<DT>(C, R.r[J], R.r[J], R.s[DT == kWeightFP4B ? J : 0], x0[j], x1[j], PLn.wscale);
     if (__builtin_expect(J == P.ec - 1 && J < P.nc, 0)) {  // the row block's last tile: set its sum aside
       C.pacc = C.acc0 + C.acc1;
       C.acc0 = f32x4{0.f, 0.f, 0.f, 0.f};
       C.acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
     }
   }
+}
+
+// The tiles that were asked for ahead of the phase: four at a time (an even count: the last group may
+// hold two) from the wave's LDS region, all of the consumer's current row block, which does not end
+// among them.
+template <int DT>
+__device__ __forceinline__ void consume_parked(ConsumeState& C, const PassLane& PLn, const char* region, int count,
+                                               int stride) {
+  constexpr int NX = weight_tile_cols(DT) / 32;
+  int i = 0;
+  for (; i + 4 <= count; i += 4) {
+    u32x4 w[4], x0[4][NX], x1[4][NX];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      w[j] = *(const u32x4*)(region + (i + j) * 1024 + PLn.lane16);
+      const int off = (C.t + i + j) * stride;
+#pragma unroll
+      for (int h = 0; h < NX; ++h) {
+        x0[j][h] = *(const u32x4*)(PLn.b0 + off + h * (stride / NX));
+        x1[j][h] = *(const u32x4*)(PLn.b1 + off + h * (stride / NX));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tile_mfma<DT>(C, w[j], w[j], 0u, x0[j], x1[j], PLn.wscale);
+  }
+  if (i < count) {
+    u32x4 w[2], x0[2][NX], x1[2][NX];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      w[j] = *(const u32x4*)(region + (i + j) * 1024 + PLn.lane16);
+      const int off = (C.t + i + j) * stride;
+#pragma unroll
+      for (int h = 0; h < NX; ++h) {
+        x0[j][h] = *(const u32x4*)(PLn.b0 + off + h * (stride / NX));
+        x1[j][h] = *(const u32x4*)(PLn.b1 + off + h * (stride / NX));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) tile_mfma<DT>(C, w[j], w[j], 0u, x0[j], x1[j], PLn.wscale);
+  }
+  C.f += count;
+  C.t += count;
 }
 
 // One pass over the ring, in groups of kGroup slots: the group's tiles are consumed (skipped as a
@@ -880,7 +972,7 @@ template <int DT, int UR>
 __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                               const char* lds, int n, int lane, const EpiCtx& e,
                                               const float* rscale, const FlushCtx& F, const MatDev* next,
-                                              int next_sk, int wave) {
+                                              int next_sk, int wave, int pidx, bool park_now) {
   constexpr int TB = Ring<DT, UR>::kTileBytes;
   ConsumeState C;
   C.f = S.f0;
@@ -897,6 +989,12 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   constexpr int KX = weight_tile_cols(DT) / 32;  // 32-column operand slots per weight tile
   PLn.b1 = PLn.b0 + (KX * S.nt + 1) * 64 * n;
   PLn.wscale = A.wscale;
+  if (S.pf > 0) {
+    consume_parked<DT>(C, PLn, park_region(A, const_cast<char*>(lds), pidx, wave), S.pf, KX * 64 * n);
+    C.f = uni(C.f);
+    C.t = uni(C.t);
+  }
+
   // The compiler treats the vector memory counter as unordered while loads AND stores are pending
   // and then waits for everything before it touches a ring slot -- in every pass of the loop, once
   // that state has reached the loop header.  So stores are waited for, in a form the compiler sees,
@@ -942,6 +1040,8 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   // starts its stream after the barrier instead (those loads overlap the activation staging).
   if (next) {
     stream_init<DT>(S, *next, next_sk, wave);
+    // (park_now is set behind gate/up only: the down projection follows)
+    if (park_now) stream_park<DT>(S, park_region(A, const_cast<char*>(lds), 3, wave), park_cap(A, 3), lane);
   }
 }
 
@@ -995,9 +1095,6 @@ __host__ __device__ inline AttnLds attn_lds_layout(int hd, int cp, int n_split) 
   return L;
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  return (uint32_t)f32_to_bf16_rne(a) | ((uint32_t)f32_to_bf16_rne(b) << 16);
-}
 
 template <int HD, int DT>
 __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, int h, int u, char* lds, unsigned tag) {
@@ -1089,8 +1186,8 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
               const float v0 = __uint_as_float(vraw[q][j >> 1][(2 * j) & 3]), v1 = __uint_as_float(vraw[q][j >> 1][(2 * j + 1) & 3]);
               kw[0][j] = pack_bf16(k0, k1);
               vw[0][j] = pack_bf16(v0, v1);
-              kw[1][j] = pack_bf16(k0 - bf16_to_f32((uint16_t)kw[0][j]), k1 - bf16_to_f32((uint16_t)(kw[0][j] >> 16)));
-              vw[1][j] = pack_bf16(v0 - bf16_to_f32((uint16_t)vw[0][j]), v1 - bf16_to_f32((uint16_t)(vw[0][j] >> 16)));
+              kw[1][j] = pack_bf16(k0 - bf16_low_f32(kw[0][j]), k1 - bf16_high_f32(kw[0][j]));
+              vw[1][j] = pack_bf16(v0 - bf16_low_f32(vw[0][j]), v1 - bf16_high_f32(vw[0][j]));
             }
           }
         }
@@ -1150,8 +1247,8 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
       const int rr = it / (HD / 4), d4 = (it % (HD / 4)) * 4;
       const f32x4 v = qoff[k] >= 0 ? qv[k] : f32x4{0.f, 0.f, 0.f, 0.f};
       const uint32_t h0 = pack_bf16(v[0], v[1]), h1 = pack_bf16(v[2], v[3]);
-      const uint32_t l0 = pack_bf16(v[0] - bf16_to_f32((uint16_t)h0), v[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
-      const uint32_t l1 = pack_bf16(v[2] - bf16_to_f32((uint16_t)h1), v[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
+      const uint32_t l0 = pack_bf16(v[0] - bf16_low_f32(h0), v[1] - bf16_high_f32(h0));
+      const uint32_t l1 = pack_bf16(v[2] - bf16_low_f32(h1), v[3] - bf16_high_f32(h1));
       *(uint2*)(lds + L.q_off[0] + rr * L.kstride + d4 * 2) = make_uint2(h0, h1);
       *(uint2*)(lds + L.q_off[1] + rr * L.kstride + d4 * 2) = make_uint2(l0, l1);
     }
@@ -1228,8 +1325,8 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
             wsum[b] += p[q];
           }
           const uint32_t h0 = pack_bf16(p[0], p[1]), h1 = pack_bf16(p[2], p[3]);
-          const uint32_t l0 = pack_bf16(p[0] - bf16_to_f32((uint16_t)h0), p[1] - bf16_to_f32((uint16_t)(h0 >> 16)));
-          const uint32_t l1 = pack_bf16(p[2] - bf16_to_f32((uint16_t)h1), p[3] - bf16_to_f32((uint16_t)(h1 >> 16)));
+          const uint32_t l0 = pack_bf16(p[0] - bf16_low_f32(h0), p[1] - bf16_high_f32(h0));
+          const uint32_t l1 = pack_bf16(p[2] - bf16_low_f32(h1), p[3] - bf16_high_f32(h1));
           *(uint2*)(lds + L.p_off[0] + rr * L.vstride + (ct * 16 + 4 * g) * 2) = make_uint2(h0, h1);
           *(uint2*)(lds + L.p_off[1] + rr * L.vstride + (ct * 16 + 4 * g) * 2) = make_uint2(l0, l1);
         }
@@ -1422,6 +1519,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
                                            const MatDev* next, int next_sk, int wave, int trace_layer,
                                            bool poll_x, int kind) {
+  const int pidx = kind == 0 ? 0 : kind - 1;  // index of the phase's plan: QKV, O, gate/up, down, LM head
   if (poll_x) __syncthreads();  // no grid barrier came before: the workgroup's slower waves are done with LDS
   stream_make_uniform(S);
   constexpr int KX = weight_tile_cols(DT) / 32;  // activations are staged in 32-column slots whatever the weight tile
@@ -1465,14 +1563,20 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   EpiCtx e2 = e;
   e2.resid = stage_resid ? resid : nullptr;
   e2.rb0 = S.rb0;
+  const auto park_resid = [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; };
+  // Where the phase's first tiles wait in LDS, the ring is asked for once the activations are
+  // staged and fills while those tiles are consumed: nothing then travels ahead of the activations
+  // (or of the re-reads of a phase that waits for them), which arrive 1.5-4 us earlier for it.
+  // Elsewhere the ring goes out right behind the activation loads.
+  const bool ring_late = park_cap(A, pidx) > 8;  // (fewer tiles are consumed before the ring's first tiles arrive)
   stage_x<DT>(xin, gain, K, A.n, KX * S.t0, KX * S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
-              [&] { ring_prefetch<DT, UR>(R, S, lane); },
-              [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; },
-              poll_x ? kPollLimit : 0u, &timed_out);
+              [&] { ring_prefetch<DT, UR>(R, S, lane, !ring_late); }, park_resid, poll_x ? kPollLimit : 0u, &timed_out);
+  if (ring_late) ring_prefetch<DT, UR>(R, S, lane);
   if (timed_out && threadIdx.x == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // (no global store may sit between the weight loads above and the streaming loop: with loads and
   // stores both pending the compiler stops counting and waits for everything at every ring slot)
-  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave);  // drains its stores
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave, pidx,
+                        /*park_now=*/kind == 3);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
 
@@ -1558,7 +1662,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   if (ok && !dead) {
     embed_phase(A);
     stream_init<DT>(S, table_mat<DT>(A, A.layer_begin, 0), A.sk[0], wave);
-    ok = grid_barrier(A, bc, -1, false);
+    ok = grid_barrier(A, bc, -1, false, -1, [&] { stream_park<DT>(S, park_region(A, lds, 0, wave), park_cap(A, 0), lane); });
   }
   // One pass of this loop is one phase; phases 0, 2, 3, 4 of a layer are the projections (QKV,
   // O, gate/up, down), phase 1 is attention, and a final pass after the last layer is the LM
@@ -1574,6 +1678,12 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
         break;
       wg_mark(A, l * 8 + 1, 2);
       stream_init<DT>(S, table_mat<DT>(A, l, 1), A.sk[1], wave);
+      if (park_cap(A, 1) > 0) {
+        // the tiles' region may overlap what slower waves of a workgroup without attention work still
+        // read for the QKV projection
+        __syncthreads();
+        stream_park<DT>(S, park_region(A, lds, 1, wave), park_cap(A, 1), lane);
+      }
       // No grid barrier here: the output projection asks for its weights at once and reads the
       // attention output until no piece of it is "empty" any more (the merging workgroups are
       // the last to finish this phase; everyone else's weight requests travel meanwhile).
@@ -1645,7 +1755,10 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     // the down projection for the SwiGLU output
     if (k == 0 || k == 3) continue;
     const bool boundary = k == 4;
-    if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k))) break;
+    const int npidx = k == 2 ? 2 : (l + 1 < A.layer_end ? 0 : 4);  // what follows the barrier: gate/up; the next QKV or the LM head
+    if (!(ok = grid_barrier(A, bc, boundary ? l + 1 : -1, boundary && l + 1 < A.layer_end, l * 8 + k,
+                            [&] { if (has_next) stream_park<DT>(S, park_region(A, lds, npidx, wave), park_cap(A, npidx), lane); })))
+      break;
     wg_mark(A, l * 8 + k, 5);
     if (boundary) {
       dead_tokens = (unsigned)__builtin_amdgcn_readfirstlane(bar_sh[1]);
@@ -1654,6 +1767,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   }
   if (ok && !dead && A.layer_end < L) hidden_out_phase(A);
   // Exit: the last workgroup to leave re-arms the barrier for the next launch and reports.
+  wave_drain();  // (a run that ends early may leave tiles on their way into LDS)
   __syncthreads();
   if (threadIdx.x == 0) {
     StageSync* sy = A.sync;

@@ -73,6 +73,48 @@ def test_ragged_shapes_match_oracle(name):
     gm.free()
 
 
+# Contractions long enough that every wave has several tiles of one row block at the start of its
+# range in every projection (32 to 88 tiles per row, one or two row blocks per workgroup).
+PARK_SHAPES = {
+    "park_bf16": synth.ModelShape("park_bf16", 2, 2048, 16, 4, 128, 2816, 1024, dtype="bf16"),
+    "park_w8": synth.ModelShape("park_w8", 2, 2048, 16, 4, 128, 2816, 1024, dtype="bf16", weight_format="fp8",
+                                weight_scale_exp2=-10),
+    "park_w4": synth.ModelShape("park_w4", 2, 4096, 32, 8, 128, 5632, 1024, dtype="bf16", weight_format="fp4",
+                                weight_scale_exp2=-6),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PARK_SHAPES) + ["odd_bf16_hd64"])
+def test_tiles_asked_for_ahead_of_a_phase_change_no_bit(name):
+    """Weight tiles that a wave asks for ahead of a phase (into LDS, while it waits for the phase to
+    begin) are the first tiles of its range and are consumed first, in the same order and on the same
+    accumulators as when they come through the ring: logits and the run's K/V must not change by a
+    bit whatever the number of such tiles (none, 2, 6, the built-in choice, more than LDS holds)."""
+    sh = PARK_SHAPES.get(name) or ODD_SHAPES[name]
+    seed, n_cells, T = 5, 160, 33
+    gm = gpu_loader.load_model(sh, seed, 0.1)
+    gkv = pi.KVCache(gm, n_cells)
+    gpu_loader.prefill_kv_synthetic(gkv, sh, seed, T)
+    for n in (1, 5, 16):
+        parent = synth.random_tree(2, n, n)
+        toks = synth.sibling_distinct_tokens(sh, 2, n, parent)
+        rd = synth.tree_run(parent, T, T)
+        first = None
+        for cap in (1, 2, 6, 0, 64):
+            gm.set_plan(7, cap)
+            st, done, lg, _, grun = forward(gm, gkv, rd, toks)
+            assert (st, done) == (pi.PI_OK, sh.n_layers), (n, cap)
+            image = gkv.raw()  # the whole cache, the run's cells included
+            pi.kv_rollback(gkv, grun.slots, n)
+            if first is None:
+                first = (lg, image)
+                continue
+            assert np.array_equal(lg, first[0]), (n, cap)
+            assert np.array_equal(image, first[1]), (n, cap)
+    gm.set_plan(7, 0)
+    gm.free()
+
+
 def test_a_contraction_shorter_than_the_smallest_ring_is_refused():
     """d_model = 96 is three 32-column tiles, fewer than the smallest ring of outstanding tiles:
     the forward refuses on the host (no launch), and the model is otherwise intact."""
