@@ -31,6 +31,8 @@ struct pi_model {
   LayerDev* layers_dev = nullptr;
   // activation scratch of the one run in flight
   float *x = nullptr, *q = nullptr, *o = nullptr, *a = nullptr, *ssq = nullptr, *part = nullptr;
+  char* xs = nullptr;  // the residual stream in the form the projections stage (o and a are in that form too)
+  int last_n = 0;      // tokens of the last forward (the staged form's layout depends on it)
   unsigned* kv_ready = nullptr;
   RunState* rs = nullptr;
   StageSync* sync = nullptr;
@@ -330,6 +332,7 @@ int32_t pi_model_load(const pi_model_config* cfg, pi_model** out) {
   if (e == hipSuccess) e = dev_alloc(m, &m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2), false);
   if (e == hipSuccess) e = dev_alloc(m, &m->x, (size_t)PI_MAX_BATCH * d * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->q, (size_t)PI_MAX_BATCH * nq * sizeof(float), true);
+  if (e == hipSuccess) e = dev_alloc(m, &m->xs, (size_t)PI_MAX_BATCH * d * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->o, (size_t)PI_MAX_BATCH * nq * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->a, (size_t)PI_MAX_BATCH * c.ffn * sizeof(float), true);
   if (e == hipSuccess) e = dev_alloc(m, &m->ssq, (size_t)(d / 16) * 16 * sizeof(float), true);
@@ -494,8 +497,35 @@ int32_t pi_debug_read_scratch(pi_model* m, int32_t which, float* dst_host, int64
   const float* src = which == 0 ? m->x : which == 1 ? m->q : which == 2 ? m->o : which == 3 ? m->a : nullptr;
   if (!src) return PI_E_ARG;
   hipError_t e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = hipMemcpy(dst_host, src, (size_t)count * sizeof(float), hipMemcpyDeviceToHost);
-  return hip_status(e);
+  if (which < 2) {
+    if (e == hipSuccess) e = hipMemcpy(dst_host, src, (size_t)count * sizeof(float), hipMemcpyDeviceToHost);
+    return hip_status(e);
+  }
+  // The attention and SwiGLU outputs live in the form the next projection stages: per piece of eight
+  // columns and token a 16-byte slot in each of two arrays (bf16 model: eight high parts / eight low
+  // parts; fp32 model: the first / the last four values).  Put back as [n][K] floats.
+  const int n = m->last_n;
+  const int K = which == 2 ? m->n_q_rows() : m->cfg.ffn;
+  if (n < 1 || count != (int64_t)n * K) return PI_E_ARG;
+  std::vector<uint32_t> raw((size_t)count);
+  if (e == hipSuccess) e = hipMemcpy(raw.data(), src, (size_t)count * sizeof(float), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_status(e);
+  const size_t arr_words = (size_t)(K / 8) * n * 4;
+  const auto word = [&](int array, int c8, int i, int w) { return raw[array * arr_words + ((size_t)c8 * n + i) * 4 + w]; };
+  const auto as_float = [](uint32_t u) { float f; memcpy(&f, &u, 4); return f; };
+  for (int i = 0; i < n; ++i)
+    for (int c = 0; c < K; ++c) {
+      const int c8 = c / 8, p = c % 8;
+      float v;
+      if (m->cfg.dtype == PI_DTYPE_BF16) {
+        const uint32_t h = word(0, c8, i, p / 2), l = word(1, c8, i, p / 2);
+        v = as_float(p % 2 ? h & 0xffff0000u : h << 16) + as_float(p % 2 ? l & 0xffff0000u : l << 16);
+      } else {
+        v = as_float(word(p / 4, c8, i, p % 4));
+      }
+      dst_host[(size_t)i * K + c] = v;
+    }
+  return PI_OK;
 }
 
 int32_t pi_debug_wgtrace(pi_model* m, int32_t layer, uint64_t* dst_host) {
@@ -831,6 +861,8 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.kv_dtype = kv->dtype;
   a.kv_len = kv->len_dev;
   a.x = m->x;
+  a.xs = m->xs;
+  m->last_n = n;
   a.q = m->q;
   a.o = m->o;
   a.a = m->a;

@@ -125,7 +125,10 @@ struct StageArgs {
   int n_cells, kv_dtype;
   const int32_t* kv_len;
   // scratch
+  // x, q: fp32 [n][.]; o (attention output), a (SwiGLU output) and xs (the residual stream times the
+  // next projection's RMSNorm gain): in the staged form the projection phases copy into LDS
   float *x, *q, *o, *a, *ssq;
+  char* xs;
   float* part;   // three regions of [NRB][S_k][256] partial tiles that cross slices; all-ones while empty
   size_t part_half_floats;  // floats per region
   float* attn_o;   // [Hkv][units][R][hd]

@@ -467,30 +467,81 @@ __device__ __forceinline__ void ring_prefetch(Ring<DT, UR>& R, WaveStream& S, in
 
 constexpr uint32_t kEmptyWord = 0xFFFFFFFFu;  // all-ones: "nothing here yet" in buffers that workgroups poll
 
+// ---- activations between phases: the staged form ------------------------------------------------
+// What a projection phase multiplies its weights with is the same for every workgroup -- n rows of K
+// activations, times the RMSNorm gain where the phase has one -- and every workgroup needs all of it
+// (or its column slice) in LDS, as the matrix instruction's second operand: split into a bf16 high
+// and low part for a bf16 model.  So the PRODUCER of the activations (the residual, SwiGLU and
+// attention epilogues, the stage input) writes them to memory in exactly that form, once, and a
+// consumer copies its slice into LDS with loads that write LDS directly: no registers, no
+// arithmetic, everything in flight at once.
+//   Piece (c8, i) = columns 8 c8 .. 8 c8 + 7 of token i is 16-byte slot c8 * n + i of two arrays, the
+//   second (K / 8) * n slots behind the first.  bf16 model: array 0 holds the pieces' eight high
+//   parts, array 1 the eight low parts (value - high part, rounded to bf16).  fp32 model: array 0
+//   holds the first four values of the piece, array 1 the last four.
+// A phase's slice of k tiles [t0, t0 + nt) is the contiguous slot range [4 t0 n, 4 (t0 + nt) n) of
+// both arrays; columns past K do not exist in memory (the consumer's descriptor ends with the
+// arrays, and loads beyond it write zeros).
+__device__ __forceinline__ uint32_t staged_array_bytes(int K, int n) { return (uint32_t)(K >> 3) * (uint32_t)n * 16u; }
+// Store columns c0 .. c0 + 3 (c0 a multiple of 4) of token i.
+template <int DT>
+__device__ __forceinline__ void store_staged4(char* base, int K, int n, int i, int c0, f32x4 v) {
+  const __amdgpu_buffer_rsrc_t r = rsrc_of(base);
+  const int slot16 = ((c0 >> 3) * n + i) * 16, half = (c0 >> 2) & 1;
+  const int arr = (int)staged_array_bytes(K, n);
+  if constexpr (DT != kWeightF32) {
+    const uint32_t h0 = pack_bf16(v[0], v[1]), h1 = pack_bf16(v[2], v[3]);
+    const uint32_t l0 = pack_bf16(v[0] - bf16_low_f32(h0), v[1] - bf16_high_f32(h0));
+    const uint32_t l1 = pack_bf16(v[2] - bf16_low_f32(h1), v[3] - bf16_high_f32(h1));
+    st_ag2(r, slot16 + half * 8, __uint_as_float(h0), __uint_as_float(h1));
+    st_ag2(r, arr + slot16 + half * 8, __uint_as_float(l0), __uint_as_float(l1));
+  } else {
+    st_ag4(r, half * arr + slot16, v);
+  }
+}
+// Store columns c0, c0 + 1 (c0 even) of token i.
+template <int DT>
+__device__ __forceinline__ void store_staged2(char* base, int K, int n, int i, int c0, float v0, float v1) {
+  const __amdgpu_buffer_rsrc_t r = rsrc_of(base);
+  const int slot16 = ((c0 >> 3) * n + i) * 16;
+  const int arr = (int)staged_array_bytes(K, n);
+  if constexpr (DT != kWeightF32) {
+    const uint32_t h = pack_bf16(v0, v1);
+    const uint32_t l = pack_bf16(v0 - bf16_low_f32(h), v1 - bf16_high_f32(h));
+    const int off = slot16 + ((c0 >> 1) & 3) * 4;
+    __builtin_amdgcn_raw_buffer_store_b32(h, r, off, 0, kAgent);
+    __builtin_amdgcn_raw_buffer_store_b32(l, r, arr + off, 0, kAgent);
+  } else {
+    st_ag2(r, ((c0 >> 2) & 1) * arr + slot16 + (c0 & 2) * 4, v0, v1);
+  }
+}
+
+// vmcnt(N) as the wait instruction that the compiler's own counter tracking takes into account
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+
 // ---- activation staging (once per phase and workgroup) ---------------------------------------
-// LDS slot (tt, g, i) holds x[i][32(t0+tt) + 8g + 0..7] (times the gain), in two 16-byte halves
-// lo_off = (nt + 1) * 4 * n slots apart: bf16 model: the hi parts and the lo parts of the eight
-// values; fp32 model: the first four and the last four floats.  The slots of one more tile
-// (tt = nt) are all zero in both halves: the streaming loop multiplies by them where a slot of
-// its ring holds nothing.
+// LDS slot (tt, g, i) holds the piece of token i that starts at column 32(t0+tt) + 8g, array 0 in
+// the first half of the operand area and array 1 lo_off = (nt + 1) * 4 * n slots behind it.  The
+// slots of one more tile (tt = nt) are all zero in both halves: the streaming loop multiplies by
+// them where a slot of its ring holds nothing.
+// The copy: the slice is cut into pieces of 1 KiB (one load instruction of a wave), wave w takes
+// pieces w, w + 8, ... of both arrays.  `mid` (the caller's weight requests: kMidLoads load
+// instructions, always) goes out behind them, so the activations, being older, are waited for
+// alone.
 // Also computes 1/sqrt(mean x^2 + eps) per token (scaled phases) from the per-16-column partial
-// sums of squares, summed in a fixed order.
-// Every load of a batch (partial sums, activations, gains) is issued outside any branch, and
-// those of the last batch before `mid` runs; the caller's `mid` starts the weight stream, so the activations and the
-// first weight tiles travel together and the activations, being older, are waited for alone.
-// (A load inside a branch would be waited for at the join, together with everything younger.)
-// `post` runs before the closing workgroup barrier.
+// sums of squares, summed in a fixed order.  `post` runs before the closing workgroup barrier.
 // poll_limit > 0: the activations may still be on their way (no grid barrier separates this phase
-// from their producer); a 16-byte piece that reads as the all-ones "empty" pattern is read again,
-// at most poll_limit times.  Their producer overwrites every piece, and a later phase puts the
-// pattern back once every workgroup has staged them.
-template <int DT, typename Mid, typename Post>
-__device__ __forceinline__ void stage_x(const float* xin, const float* gain, int K, int n, int t0, int nt, char* lds,
-                                        const float* ssq, int n_blocks, float eps, float* red, float* rscale,
-                                        Mid&& mid, Post&& post, unsigned poll_limit, bool* timed_out) {
-  const int items = nt * n * 4;
+// from their producer): a slot with an all-ones word is "empty"; a wave whose pieces hold one asks
+// for those pieces again, at most poll_limit times.  Their producer overwrites every slot, and a
+// later phase puts the pattern back once every workgroup has staged them.
+template <int kMidLoads, typename Mid, typename Post>
+__device__ __forceinline__ void stage_x(const char* xs, int K, int n, int t0, int nt, char* lds, const float* ssq,
+                                        int n_blocks, float eps, float* red, float* rscale, Mid&& mid, Post&& post,
+                                        unsigned poll_limit, bool* timed_out, int wave, int lane) {
   const int lo_off = (nt + 1) * 4 * n;
-  const __amdgpu_buffer_rsrc_t xr = rsrc_of(xin);
   for (int z = nt * 4 * n + threadIdx.x; z < lo_off; z += kThreads) {
     ((uint4*)lds)[z] = make_uint4(0u, 0u, 0u, 0u);
     ((uint4*)lds)[lo_off + z] = make_uint4(0u, 0u, 0u, 0u);
@@ -503,93 +554,52 @@ __device__ __forceinline__ void stage_x(const float* xin, const float* gain, int
     // The loads stay unconditional; the ones nobody needs (an unscaled phase; the columns of tokens
     // the run does not have) get out-of-range offsets, which the hardware answers with zeros
     // without going to memory -- every workgroup reads these same few lines at the same moment.
-    const __amdgpu_buffer_rsrc_t sr = make_rsrc(ssq ? ssq : xin, ssq ? (uint32_t)n_blocks * 64u : 0u);
+    const __amdgpu_buffer_rsrc_t sr = make_rsrc(ssq ? ssq : (const float*)xs, ssq ? (uint32_t)n_blocks * 64u : 0u);
 #pragma unroll
     for (int q = 0; q < kMaxPer; ++q) {  // plain (non-atomic) agent-scope loads: all in flight at once
       const int b = min(sb0 + q * kGroups, n_blocks - 1);
       part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, si < n ? (b * 16 + si) * 4 : 0x7ffffff0, 0, kAgent));
     }
   }
-  const __amdgpu_buffer_rsrc_t gr = make_rsrc(gain ? gain : xin, gain ? (uint32_t)K * 4u : 0u);  // no gain: zeros, no traffic
-  // Every workgroup stages the same activations at the same moment: each starts somewhere else in
-  // the batch, so that they do not all ask the same memory channel for the same lines at once.
-  const unsigned rot = blockIdx.x * 2u;
-  auto batch = [&](int id0, auto&& between) {
-    f32x4 p[2][2], gq[2][2];
-    int slot[2], xoff[2];
-    bool in_k[2], in_items[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int id = id0 + q * kThreads + (int)((threadIdx.x + rot) & (kThreads - 1));
-      const int cl = id & 3;
-      const int i = (id >> 2) % n;
-      const int tt = (id >> 2) / n;
-      const int k0 = (t0 + tt) * kKTile + cl * 8;
-      slot[q] = (tt * 4 + cl) * n + i;
-      in_items[q] = id < items;
-      in_k[q] = in_items[q] && k0 < K;
-      const int off = in_k[q] ? (i * K + k0) * 4 : 0;
-      xoff[q] = off;
-      p[q][0] = ld_ag4(xr, off);
-      p[q][1] = ld_ag4(xr, off + 16);
-      const int goff = in_k[q] ? k0 : 0;
-      gq[q][0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(gr, goff * 4, 0, 0));
-      gq[q][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(gr, goff * 4 + 16, 0, 0));
+  const uint32_t arr = staged_array_bytes(K, n);
+  const __amdgpu_buffer_rsrc_t r0 = make_rsrc(xs, arr), r1 = make_rsrc(xs + arr, arr);
+  const int bytes = nt * 4 * n * 16, src0 = t0 * 4 * n * 16;  // the slice, in each array
+  const int pieces = (bytes + 1023) >> 10;
+  typedef __attribute__((address_space(3))) void* lds_ptr;
+  const auto pull = [&](int c) {  // piece c of both arrays (lanes past the slice's end stay out)
+    const int off = c * 1024 + lane * 16;
+    if (off < bytes) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r0, (lds_ptr)(lds + c * 1024), 16, off, src0, 0, kAgent);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r1, (lds_ptr)(lds + lo_off * 16 + c * 1024), 16, off, src0, 0, kAgent);
     }
-    between();
-    if (poll_limit) {
-      // producers store 8 or 16 bytes at a time: a piece is here when neither 8-byte half is empty
-      const auto empty = [](f32x4 t) {
-        return (__float_as_uint(t[0]) == kEmptyWord && __float_as_uint(t[1]) == kEmptyWord) ||
-               (__float_as_uint(t[2]) == kEmptyWord && __float_as_uint(t[3]) == kEmptyWord);
-      };
-      for (unsigned spin = 0;; ++spin) {
+  };
+  for (int c = wave; c < pieces; c += kWaves) pull(c);
+  mid();
+  wait_vm<kMidLoads>();  // this wave's pieces are in LDS
+  if (poll_limit) {
+    for (unsigned spin = 0;; ++spin) {
+      bool again = false;
+      for (int c = wave; c < pieces; c += kWaves) {
+        const int off = c * 1024 + lane * 16;
         bool missing = false;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) missing = missing || (in_k[q] && (empty(p[q][0]) || empty(p[q][1])));
-        if (!__syncthreads_or(missing)) break;  // the whole workgroup goes round again together
-        if (spin >= poll_limit) {               // the same count in every thread: a uniform way out
-          *timed_out = true;
-          break;
+        if (off < bytes) {
+          const u32x4 a = *(const u32x4*)(lds + off), b = *(const u32x4*)(lds + lo_off * 16 + off);
+          missing = a[0] == kEmptyWord || a[1] == kEmptyWord || a[2] == kEmptyWord || a[3] == kEmptyWord ||
+                    b[0] == kEmptyWord || b[1] == kEmptyWord || b[2] == kEmptyWord || b[3] == kEmptyWord;
         }
-        __builtin_amdgcn_s_sleep(1);
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          p[q][0] = ld_ag4(xr, xoff[q]);
-          p[q][1] = ld_ag4(xr, xoff[q] + 16);
+        if (__builtin_amdgcn_ballot_w64(missing) != 0) {
+          pull(c);
+          again = true;
         }
+      }
+      if (!again) break;
+      if (spin >= poll_limit) {
+        *timed_out = true;
+        break;
       }
       wave_settle();  // the re-reads are younger than the weight loads: leave nothing of them pending
     }
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      if (!in_items[q]) continue;
-      float v[8];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[j] = in_k[q] ? p[q][0][j] * (gain ? gq[q][0][j] : 1.0f) : 0.0f;
-        v[4 + j] = in_k[q] ? p[q][1][j] * (gain ? gq[q][1][j] : 1.0f) : 0.0f;
-      }
-      if (DT != kWeightF32) {
-        uint32_t hi[4], lo[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          hi[j] = pack_bf16(v[2 * j], v[2 * j + 1]);
-          lo[j] = pack_bf16(v[2 * j] - bf16_low_f32(hi[j]), v[2 * j + 1] - bf16_high_f32(hi[j]));
-        }
-        ((uint4*)lds)[slot[q]] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-        ((uint4*)lds)[slot[q] + lo_off] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-      } else {
-        ((float4*)lds)[slot[q]] = make_float4(v[0], v[1], v[2], v[3]);
-        ((float4*)lds)[slot[q] + lo_off] = make_float4(v[4], v[5], v[6], v[7]);
-      }
-    }
-  };
-  // `mid` goes with the last batch: every activation load is then older than the weight loads (a
-  // load younger than those could only be waited for together with them).
-  int id0 = 0;
-  for (; id0 + 2 * kThreads < items; id0 += 2 * kThreads) batch(id0, [] {});
-  batch(id0, mid);
+  }
   if (ssq) {
     float ssum = 0.0f;
 #pragma unroll
@@ -634,6 +644,11 @@ struct EpiCtx {
   const float2* rope;
   const f32x4* resid;  // RESID: LDS copy of the residual rows of the workgroup's row blocks, [row block][lane]
   int rb0;             // first row block of the workgroup
+  // RESID: the new residual rows are also written in the staged form the next projection reads, times
+  // that projection's RMSNorm gain (null: nobody reads them in that form)
+  char* staged_out;
+  const float* gain_next;  // [N]
+  const f32x4* gres;       // LDS copy of the gains of the workgroup's rows, [row block][lane] (null: read in place)
 };
 
 __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem_idx, const float* v) {
@@ -647,6 +662,7 @@ __device__ __forceinline__ void store_kv4(char* cache, int kv_dtype, size_t elem
 }
 
 // The accumulator tile of a wave: lane l holds rows 16rb + 4(l>>4) + 0..3 for token l & 15.
+template <int DT>
 __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int lane, const float* rscale) {
   const int EPI = e.epi;
   const int i = lane & 15, g = lane >> 4;
@@ -693,6 +709,10 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
       const f32x4 x = (e.resid ? e.resid[(rb - e.rb0) * 64 + lane] : ld_ag4(xr, off)) + acc;
       st_ag4(xr, off, x);
       s = sum_sq4(x[0], x[1], x[2], x[3]);
+      if (e.staged_out) {
+        const f32x4 gn = e.gres ? e.gres[(rb - e.rb0) * 64 + lane] : *(const f32x4*)(e.gain_next + row);
+        store_staged4<DT>(e.staged_out, e.N, e.n, i, row, x * gn);
+      }
     }
     s += __shfl_xor(s, 16);
     s += __shfl_xor(s, 32);
@@ -701,8 +721,8 @@ __device__ __forceinline__ void epilogue(const EpiCtx& e, int rb, f32x4 acc, int
     if (!live || row >= e.N) return;
     const float r = rscale[i];
     const float g0 = acc[0] * r, u0 = acc[1] * r, g1 = acc[2] * r, u1 = acc[3] * r;
-    st_ag2(rsrc_of(e.out), (i * (e.N / 2) + row / 2) * 4, g0 / (1.0f + expf(-g0)) * u0,
-           g1 / (1.0f + expf(-g1)) * u1);
+    // (in the staged form: the down projection is its only reader)
+    store_staged2<DT>((char*)e.out, e.N / 2, e.n, i, row / 2, g0 / (1.0f + expf(-g0)) * u0, g1 / (1.0f + expf(-g1)) * u1);
   } else {  // EPI_LOGITS: read by later kernels only
     if (!live || row >= e.N) return;
     const float r = rscale[i];
@@ -734,6 +754,7 @@ struct FlushCtx {
 };
 
 // Returns whether global memory was touched (false: the tile was parked in LDS and that is all).
+template <int DT>
 __device__ __forceinline__ bool flush_rowblock(const StageArgs& A, const WaveStream& S, int S_k, int rb,
                                                f32x4 acc, int lane, const EpiCtx& e, const float* rscale,
                                                const FlushCtx& F) {
@@ -798,7 +819,7 @@ __device__ __forceinline__ bool flush_rowblock(const StageArgs& A, const WaveStr
       }
     }
   }
-  epilogue(e, rb, acc, lane, rscale);
+  epilogue<DT>(e, rb, acc, lane, rscale);
   return true;
 }
 
@@ -1013,7 +1034,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.f += P.nc;
     if (P.ec <= P.nc) {  // a row block ended in this pass
       // (a tile parked in LDS leaves no store behind: the ring stays in flight across it)
-      if (flush_rowblock(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F)) wave_settle();
+      if (flush_rowblock<DT>(A, S, S_k, C.rb, C.pacc, lane, e, rscale, F)) wave_settle();
       C.rb += 1;
       C.t = P.nc - P.ec;
     } else {
@@ -1023,7 +1044,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.t = uni(C.t);
     C.rb = uni(C.rb);
   }
-  if (C.t > 0) (void)flush_rowblock(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
+  if (C.t > 0) (void)flush_rowblock<DT>(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
   for (int b = 0; b < 2; ++b) {
     if (!F.rearm[b]) continue;
     const int pieces = F.rearm_n[b] / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -1378,7 +1399,7 @@ __device__ void attn_unit(const StageArgs& A, const char* kl, const char* vl, in
 
 // Merge step of unit (h, u): wait (bounded) until every unit of kv head h has published, then
 // combine the units, in unit order, for this unit's share of the head's query rows.
-template <int HD>
+template <int HD, int DT>
 __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* sh) {
   const int tid = threadIdx.x;
   const int G = A.n_q_heads / A.n_kv_heads;
@@ -1408,7 +1429,7 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
   }
   __syncthreads();
   if (!__builtin_amdgcn_readfirstlane(sh[0])) return false;
-  const __amdgpu_buffer_rsrc_t oor = rsrc_of(A.o), por = rsrc_of(A.attn_o), mlr = rsrc_of(A.attn_ml);
+  const __amdgpu_buffer_rsrc_t por = rsrc_of(A.attn_o), mlr = rsrc_of(A.attn_ml);
   const int my_rows = (R - u + upH - 1) / upH;
   for (int e = tid; e < my_rows * (HD / 4); e += kThreads) {
     const int r = u + (e / (HD / 4)) * upH, d4 = (e % (HD / 4)) * 4;
@@ -1439,7 +1460,8 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
     }
     const int gq = r / A.n, i = r % A.n;
     const float inv = 1.0f / Ls;
-    st_ag4(oor, ((i * A.n_q_heads + h * G + gq) * HD + d4) * 4, o * inv);
+    // (in the staged form: the output projection is its only reader)
+    store_staged4<DT>((char*)A.o, A.n_q_heads * HD, A.n, i, (h * G + gq) * HD + d4, o * inv);
   }
   return true;
 }
@@ -1461,9 +1483,9 @@ __device__ bool attention_phase(const StageArgs& A, const char* kl, const char* 
   for (int w = blockIdx.x; ok && w < units; w += gridDim.x) {
     const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
     switch (A.head_dim) {
-      case 32: ok = attn_merge<32>(A, h, u, tag, sh); break;
-      case 64: ok = attn_merge<64>(A, h, u, tag, sh); break;
-      default: ok = attn_merge<128>(A, h, u, tag, sh); break;
+      case 32: ok = attn_merge<32, DT>(A, h, u, tag, sh); break;
+      case 64: ok = attn_merge<64, DT>(A, h, u, tag, sh); break;
+      default: ok = attn_merge<128, DT>(A, h, u, tag, sh); break;
     }
   }
   wave_drain();
@@ -1471,7 +1493,9 @@ __device__ bool attention_phase(const StageArgs& A, const char* kl, const char* 
 }
 
 // ---- stage input / output ---------------------------------------------------------------------
-__device__ void embed_phase(const StageArgs& A) {
+// (also writes the staged form of the residual stream, times the first layer's attention gain)
+template <int DT>
+__device__ void embed_phase(const StageArgs& A, const float* gain) {
   const int per_row = A.d / 4;
   const int total = A.n * per_row;
   const int stride = gridDim.x * kThreads;
@@ -1497,6 +1521,8 @@ __device__ void embed_phase(const StageArgs& A) {
         }
       }
       st_ag4(rsrc_of(A.x), (i * A.d + c) * 4, f32x4{v[0], v[1], v[2], v[3]});
+      const f32x4 gn = *(const f32x4*)(gain + c);
+      store_staged4<DT>(A.xs, A.d, A.n, i, c, f32x4{v[0], v[1], v[2], v[3]} * gn);
     }
     float s = sum_sq4(v[0], v[1], v[2], v[3]);
     s += __shfl_xor(s, 1);
@@ -1515,7 +1541,7 @@ __device__ void hidden_out_phase(const StageArgs& A) {
 // ---- one projection phase: stage activations, stream, flush ----------------------------------------
 template <int DT, int UR>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
-                                           const float* xin, const float* gain, bool scaled, int K,
+                                           const char* xin, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
                                            const MatDev* next, int next_sk, int wave, int trace_layer,
                                            bool poll_x, int kind) {
@@ -1545,34 +1571,47 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   F.xpart = A.part + (size_t)(kind % 3) * A.part_half_floats;
   f32x4* resid = F.part + (kWaves - 1) * 64;
   const int Gs = uni((int)gridDim.x / S_k);
-  const bool stage_resid = e.epi == EPI_RESID && uni((S.NRB + Gs - 1) / Gs) <= kMaxResidBlocks;  // as sized by the host
+  const int r_max = uni((S.NRB + Gs - 1) / Gs);
+  f32x4* gres = resid + r_max * 64;  // behind the residual rows: the next projection's gains for the same rows
+  const bool stage_resid = e.epi == EPI_RESID && r_max <= kMaxResidBlocks;  // as sized by the host
   // Nothing of the previous phase is pending any more (every wave drained before the barrier);
   // said in a form the compiler's counter tracking sees, so that the waits below are counted.
   wave_settle();
   // The residual rows of the workgroup's row blocks (at most one row block per wave): the load
   // goes out first and is parked in LDS behind the activations.
   const bool has_r = stage_resid && wave < S.R;
-  f32x4 rv;
+  f32x4 rv, gv;
   bool rv_live;
   {
     const int i = lane & 15, row = (S.rb0 + wave) * kRowBlock + (lane >> 4) * 4;
     rv_live = has_r && i < e.n && row < e.N;
     rv = ld_ag4(rsrc_of(e.out), rv_live ? (i * e.N + row) * 4 : 0);
+    const bool gv_live = rv_live && e.gain_next;
+    gv = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+        make_rsrc(e.gain_next ? e.gain_next : (const float*)xin, gv_live ? (uint32_t)e.N * 4u : 0u), gv_live ? row * 4 : 0, 0, 0));
   }
   bool timed_out = false;
   EpiCtx e2 = e;
   e2.resid = stage_resid ? resid : nullptr;
+  e2.gres = stage_resid ? gres : nullptr;
   e2.rb0 = S.rb0;
-  const auto park_resid = [&] { if (has_r) resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f}; };
+  const auto park_resid = [&] {
+    if (has_r) {
+      resid[wave * 64 + lane] = rv_live ? rv : f32x4{0.f, 0.f, 0.f, 0.f};
+      gres[wave * 64 + lane] = gv;
+    }
+  };
   // Where the phase's first tiles wait in LDS, the ring is asked for once the activations are
   // staged and fills while those tiles are consumed: nothing then travels ahead of the activations
   // (or of the re-reads of a phase that waits for them), which arrive 1.5-4 us earlier for it.
   // Elsewhere the ring goes out right behind the activation loads.
   const bool ring_late = park_cap(A, pidx) > 8;  // (fewer tiles are consumed before the ring's first tiles arrive)
-  stage_x<DT>(xin, gain, K, A.n, KX * S.t0, KX * S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
-              [&] { ring_prefetch<DT, UR>(R, S, lane, !ring_late); }, park_resid, poll_x ? kPollLimit : 0u, &timed_out);
+  constexpr int kRingLoads = Ring<DT, UR>::kRegs + (DT == kWeightFP4B ? UR : 0);  // load instructions of one ring_prefetch
+  stage_x<kRingLoads>(xin, K, A.n, KX * S.t0, KX * S.nt, lds, scaled ? A.ssq : nullptr, A.d / 16, A.eps, red, rscale,
+                      [&] { ring_prefetch<DT, UR>(R, S, lane, !ring_late); }, park_resid, poll_x ? kPollLimit : 0u,
+                      &timed_out, wave, lane);
   if (ring_late) ring_prefetch<DT, UR>(R, S, lane);
-  if (timed_out && threadIdx.x == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (timed_out && lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // (no global store may sit between the weight loads above and the streaming loop: with loads and
   // stores both pending the compiler stops counting and waits for everything at every ring slot)
   consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave, pidx,
@@ -1660,7 +1699,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   unsigned dead_tokens = (unsigned)__builtin_amdgcn_readfirstlane(bar_sh[1]);  // tokens of cancelled runs
   bool dead = dead_tokens == all_tokens;  // nothing left to do
   if (ok && !dead) {
-    embed_phase(A);
+    embed_phase<DT>(A, table_layer<DT>(A, A.layer_begin).attn_gain);
     stream_init<DT>(S, table_mat<DT>(A, A.layer_begin, 0), A.sk[0], wave);
     ok = grid_barrier(A, bc, -1, false, -1, [&] { stream_park<DT>(S, park_region(A, lds, 0, wave), park_cap(A, 0), lane); });
   }
@@ -1706,32 +1745,37 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     e.kv_tag = bc.epoch + 1;  // attention of this layer starts without a barrier in between and looks for the same number
     e.rope = A.rope;
     e.resid = nullptr;
+    e.gres = nullptr;
     e.rb0 = 0;
     e.ssq_out = A.ssq;
+    e.staged_out = nullptr;
+    e.gain_next = nullptr;
     MatDev M, nxt;
-    const float* xin;
-    const float* gain = nullptr;
+    const char* xin;
     bool scaled = false, has_next = true;
     int sk, nsk = 1;
     if (k == 5) {  // final RMSNorm + LM head
-      M = A.lm_head; sk = A.sk[4]; xin = A.x; gain = A.final_gain; scaled = true;
+      M = A.lm_head; sk = A.sk[4]; xin = A.xs; scaled = true;
       e.epi = EPI_LOGITS; e.out = A.logits_out; has_next = false; nxt = M;
     } else {
       const LayerDev W = table_layer<DT>(A, l);
       if (k == 0) {  // RMSNorm + QKV projection + RoPE + KV write
-        M = W.qkv; sk = A.sk[0]; xin = A.x; gain = W.attn_gain; scaled = true;
+        M = W.qkv; sk = A.sk[0]; xin = A.xs; scaled = true;
         e.epi = EPI_QKV; e.out = A.q; has_next = false; nxt = M;
       } else if (k == 2) {  // output projection + residual
-        M = W.o; sk = A.sk[1]; xin = A.o; e.epi = EPI_RESID; e.out = A.x; nxt = W.gateup; nsk = A.sk[2];
+        M = W.o; sk = A.sk[1]; xin = (const char*)A.o; e.epi = EPI_RESID; e.out = A.x; nxt = W.gateup; nsk = A.sk[2];
+        e.staged_out = A.xs; e.gain_next = W.ffn_gain;
       } else if (k == 3) {  // RMSNorm + gate/up + SwiGLU
-        M = W.gateup; sk = A.sk[2]; xin = A.x; gain = W.ffn_gain; scaled = true;
+        M = W.gateup; sk = A.sk[2]; xin = A.xs; scaled = true;
         e.epi = EPI_SWIGLU; e.out = A.a; nxt = W.down; nsk = A.sk[3];
       } else {  // down projection + residual; then the next layer's QKV or the LM head
-        M = W.down; sk = A.sk[3]; xin = A.a; e.epi = EPI_RESID; e.out = A.x;
+        M = W.down; sk = A.sk[3]; xin = (const char*)A.a; e.epi = EPI_RESID; e.out = A.x;
         if (l + 1 < A.layer_end) {
           nxt = table_mat<DT>(A, l + 1, 0); nsk = A.sk[0];
+          e.staged_out = A.xs; e.gain_next = table_layer<DT>(A, l + 1).attn_gain;
         } else if (A.layer_end == L) {
           nxt = A.lm_head; nsk = A.sk[4];
+          e.staged_out = A.xs; e.gain_next = A.final_gain;
         } else {
           has_next = false; nxt = M;
         }
@@ -1746,7 +1790,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       wave_drain();
       A.trace[A.trace_cap - 1] = wall_clock64();
     }
-    proj_phase<DT, UR>(A, R, S, sk, xin, gain, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
+    proj_phase<DT, UR>(A, R, S, sk, xin, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
                        has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
                        /*poll_x=*/k == 2 || k == 4, /*kind=*/k);
     wg_mark(A, l * 8 + k, 3);
@@ -1793,7 +1837,9 @@ size_t attn_lds_bytes(int head_dim, int dtype, int max_unit_cells) {
 
 size_t stage_proj_lds_bytes(int n, int nt, int r_max) {
   if (r_max > kMaxResidBlocks) r_max = 0;  // too many row blocks per workgroup: residual rows are read in place
-  return (size_t)(nt + 1) * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + r_max) * 1024;
+  // operand slots (+ the zero tile), the reduction scratch, seven parked partial tiles, and per row
+  // block of the workgroup its residual rows and the next projection's gains for them
+  return (size_t)(nt + 1) * 128 * n + (kStageThreads + 16) * sizeof(float) + (kStageThreads / 64 - 1 + 2 * r_max) * 1024;
 }
 
 namespace {
