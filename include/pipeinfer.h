@@ -446,7 +446,9 @@ const char* pi_strerror(int32_t status);
  * a larger figure means fewer column slices and more staging per workgroup.  phase 7: s_k = weight tiles
  * (1 KiB each) a wave may ask for ahead of a phase, into LDS, while it waits for the phase to begin
  * (0 restores the built-in choice, 1 = none, otherwise an even figure up to 64; always limited by the
- * LDS the projection phases leave free). */
+ * LDS the projection phases leave free).  phase 8: s_k = attention work units aimed at per 100
+ * workgroups (0 restores the built-in 75; units are handed out in the order in which workgroups
+ * finish the QKV projection, so below 100 the slowest take none). */
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k);
 /* Debug hook: copy `count` floats of an activation scratch buffer of the last run to the host
  * (which: 0 residual stream x[n][d], 1 q[n][Hq*hd], 2 attention output [n][Hq*hd],

@@ -48,6 +48,7 @@ struct pi_model {
   std::vector<void*> allocs;
   std::vector<uint8_t> set_flags;  // per (kind, layer)
   int sk_override[5] = {0, 0, 0, 0, 0};
+  int attn_share_override = 0;  // tuning hook: attention units per 100 workgroups aimed at (0: built-in)
   int park_override = 0;  // tuning hook: 0 = built-in rule, 1 = no tiles ahead of a phase, else the cap per wave
   size_t lds_budget = 0;  // tuning hook: what every projection phase's split aims to stay under (0: built-in per phase)
   size_t part_tiles = 0;  // capacity of each region of `part`, in 1 KiB tiles
@@ -557,7 +558,12 @@ int32_t pi_debug_read_trace(pi_model* m, uint64_t* dst_host, int32_t count) {
 }
 
 int32_t pi_debug_set_plan(pi_model* m, int32_t phase, int32_t s_k) {
-  if (!m || phase < 0 || phase > 7 || s_k < 0) return PI_E_ARG;
+  if (!m || phase < 0 || phase > 8 || s_k < 0) return PI_E_ARG;
+  if (phase == 8) {
+    if (s_k > 400) return PI_E_ARG;
+    m->attn_share_override = s_k;
+    return PI_OK;
+  }
   if (phase == 5) {
     m->trace_on = s_k != 0;
     return PI_OK;
@@ -623,8 +629,9 @@ int32_t pi_kv_alloc(const pi_model* m, int32_t n_cells, int32_t kv_dtype, pi_kv*
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_o, rows * kv->head_dim * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_ml, rows * 2 * sizeof(float));
   kv->attn_flag_stride = (int)max_units;
-  if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_flags, kv->n_kv_heads * max_units * sizeof(unsigned));
-  if (e == hipSuccess) e = hipMemset(kv->attn_flags, 0, kv->n_kv_heads * max_units * sizeof(unsigned));
+  // (one word more: the counter from which workgroups draw their attention units)
+  if (e == hipSuccess) e = hipMalloc((void**)&kv->attn_flags, (kv->n_kv_heads * max_units + 1) * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(kv->attn_flags, 0, (kv->n_kv_heads * max_units + 1) * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(kv->k, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->v, 0, kv->bytes_each);
   if (e == hipSuccess) e = hipMemset(kv->len_dev, 0, sizeof(int32_t));
@@ -792,7 +799,10 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   int attn_chunk, attn_units;
   {
     constexpr size_t kAttnLdsBudget = 140 * 1024;
-    long per_head = m->grid / c.n_kv_heads;
+    // about three units per four workgroups: the workgroups that finish the QKV projection last then
+    // draw no unit (the kernel hands units out in the order of arrival)
+    const int share = m->attn_share_override ? m->attn_share_override : 75;
+    long per_head = (long)m->grid * share / 100 / c.n_kv_heads;
     if (per_head < 1) per_head = 1;
     int chunk = (int)((run->prefix_len + per_head - 1) / per_head);
     chunk = ((chunk + 31) / 32) * 32;
@@ -804,6 +814,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
     attn_chunk = chunk;
     attn_units = (run->prefix_len + chunk - 1) / chunk;
     if (attn_units < 1) attn_units = 1;
+    if ((long)attn_units * c.n_kv_heads > 64L * m->grid) return PI_E_SHAPE;  // a workgroup draws at most 64 units per layer
     const size_t al = attn_lds_bytes(c.head_dim, c.dtype, chunk + PI_WINDOW);
     if (al > sp.lds) sp.lds = al;
   }
@@ -874,6 +885,7 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.attn_ml = kv->attn_ml;
   a.attn_flags = kv->attn_flags;
   a.attn_flag_stride = kv->attn_flag_stride;
+  a.attn_ticket = kv->attn_flags + (size_t)kv->n_kv_heads * kv->attn_flag_stride;
   a.rs = m->rs;
   a.sync = m->sync;
   for (int ph = 0; ph < 5; ++ph) a.sk[ph] = sp.sk[ph];

@@ -134,6 +134,7 @@ struct StageArgs {
   float* attn_o;   // [Hkv][units][R][hd]
   float* attn_ml;  // [Hkv][units][R][2]
   unsigned* attn_flags;  // [Hkv][attn_flag_stride]: barrier number at which a unit last published
+  unsigned* attn_ticket; // one word: the tickets by which workgroups draw attention units, from 0 in every launch
   unsigned* kv_ready;    // [2 * n_kv_rows / 16]: per 16-row block of K, then of V: the tag of the QKV phase that last wrote the run's cells
   int attn_flag_stride;
   RunState* rs;

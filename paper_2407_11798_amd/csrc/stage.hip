@@ -1466,12 +1466,28 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
   return true;
 }
 
+// Which workgroup takes which unit is decided when the workgroups get here: each draws tickets from a
+// counter (the same number of draws for everyone, so a layer's tickets start at a known value), and a
+// ticket below the number of units is that unit.  The workgroups that finish the QKV projection first
+// draw the units, and when there are fewer units than workgroups the slowest -- whose queries
+// everyone waits for anyway -- draw none: the phase then ends one unit's work after the last query
+// is in memory, not after the slowest workgroup has also staged and worked a unit of its own.
+// Results do not depend on who computes what (units are merged in unit order).
 // All units first, then all merges: a workgroup never waits while it still owes a unit, so the
 // waits in the merge step cannot deadlock even when a workgroup serves several units.
+constexpr int kMaxAttnRounds = 64;
 template <int DT>
-__device__ bool attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds, unsigned tag, int* sh) {
+__device__ bool attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds, unsigned tag, int* sh,
+                                int* tickets, int layer_rel) {
   const int units = A.n_kv_heads * A.attn_units_per_head;
-  for (int w = blockIdx.x; w < units; w += gridDim.x) {
+  const int rounds = (units + (int)gridDim.x - 1) / (int)gridDim.x;  // <= kMaxAttnRounds (host)
+  const unsigned base = (unsigned)layer_rel * (unsigned)rounds * gridDim.x;
+  for (int r = 0; r < rounds; ++r) {
+    if (threadIdx.x == 0)
+      tickets[r] = (int)(__hip_atomic_fetch_add(A.attn_ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - base);
+    __syncthreads();
+    const int w = __builtin_amdgcn_readfirstlane(tickets[r]);
+    if (w >= units) continue;
     const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
     switch (A.head_dim) {
       case 32: attn_unit<32, DT>(A, kl, vl, h, u, lds, tag); break;
@@ -1480,7 +1496,9 @@ __device__ bool attention_phase(const StageArgs& A, const char* kl, const char* 
     }
   }
   bool ok = true;
-  for (int w = blockIdx.x; ok && w < units; w += gridDim.x) {
+  for (int r = 0; ok && r < rounds; ++r) {
+    const int w = __builtin_amdgcn_readfirstlane(tickets[r]);
+    if (w >= units) continue;
     const int h = w / A.attn_units_per_head, u = w % A.attn_units_per_head;
     switch (A.head_dim) {
       case 32: ok = attn_merge<32, DT>(A, h, u, tag, sh); break;
@@ -1623,6 +1641,7 @@ template <int DT, int UR>
 __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
   extern __shared__ __align__(16) char lds[];
   __shared__ int bar_sh[2];
+  __shared__ int attn_tickets[kMaxAttnRounds];
   __shared__ int pflag[kWaves];
   if (threadIdx.x < kWaves) pflag[threadIdx.x] = 0;
   const int lane = threadIdx.x & 63;
@@ -1678,6 +1697,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     if (lane == 0) {
       __hip_atomic_store(&A.rs->status, status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(&A.rs->layers_done, A.layer_begin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(A.attn_ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // (two grid barriers before its first use)
     }
     wave_drain();
   }
@@ -1713,7 +1733,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     if (k == 1) {
       wg_mark(A, l * 8 + 1, 0);
       if (!(ok = attention_phase<DT>(A, A.kbase + (size_t)l * A.kv_layer_bytes, A.vbase + (size_t)l * A.kv_layer_bytes, lds,
-                                     bc.epoch + 1, bar_sh)))
+                                     bc.epoch + 1, bar_sh, attn_tickets, l - A.layer_begin)))
         break;
       wg_mark(A, l * 8 + 1, 2);
       stream_init<DT>(S, table_mat<DT>(A, l, 1), A.sk[1], wave);

@@ -246,6 +246,15 @@ def test_plan_override_grows_the_cross_slice_buffer():
         assert (st, done) == (pi.PI_OK, sh.n_layers), plan
         assert _tol_ok(lg, ref, sh.dtype), plan
         pi.kv_rollback(gkv, grun.slots, 6)
+    # attention units per 100 workgroups: few large units (all drawn by the first workgroups to arrive),
+    # the built-in choice, several units per workgroup
+    for share in (3, 0, 400):
+        gm.set_plan(8, share)
+        st, done, lg, _, grun = forward(gm, gkv, rd, toks)
+        assert (st, done) == (pi.PI_OK, sh.n_layers), share
+        assert _tol_ok(lg, ref, sh.dtype), share
+        pi.kv_rollback(gkv, grun.slots, 6)
+    gm.set_plan(8, 0)
     # a split that leaves a slice fewer tiles than the smallest ring is refused, not launched
     gm.set_plan(0, 8)
     with pytest.raises(pi.PiError) as err:
