@@ -140,9 +140,11 @@ int choose_sk(const pi_model* m, int phase, const PackedMat& w, int n, size_t bu
   }
   if (!fits && budget < kProjLdsLimit) return choose_sk(m, phase, w, n, kProjLdsLimit);
   if (fits && !ov && (phase == 3 || (phase == 1 && n >= 4))) {
-    // one row block per wave: the largest split with at most eight row blocks per workgroup
+    // one row block per wave: the largest split with at most eight row blocks per workgroup (the
+    // down projection below eight tokens: four, two waves to a row block -- 1 % on the 7B shape)
+    const long per_wg = phase == 3 && n < 8 ? 4 : 8;
     int star = fits;
-    for (int sk = fits * 2; sk <= m->grid && (long)w.NRB * sk <= 8L * m->grid && w.KT / sk >= 16; sk *= 2)
+    for (int sk = fits * 2; sk <= m->grid && (long)w.NRB * sk <= per_wg * m->grid && w.KT / sk >= 16; sk *= 2)
       if (usable(sk, budget)) star = sk;
     fits = star;
   }
