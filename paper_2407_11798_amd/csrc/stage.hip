@@ -555,11 +555,13 @@ __device__ __forceinline__ void stage_x(const char* xs, int K, int n, int t0, in
     // the run does not have) get out-of-range offsets, which the hardware answers with zeros
     // without going to memory -- every workgroup reads these same few lines at the same moment.
     const __amdgpu_buffer_rsrc_t sr = make_rsrc(ssq ? ssq : (const float*)xs, ssq ? (uint32_t)n_blocks * 64u : 0u);
+    // One per-lane offset for all of them, the block's part in the instruction's scalar offset (blocks
+    // past the last are out of the descriptor's range): sixteen per-lane offsets would be sixteen live
+    // registers, which a kernel variant short of registers spills and then reloads one load at a time.
+    const int voff = si < n ? (sb0 * 16 + si) * 4 : 0x7ffffff0;
 #pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) {  // plain (non-atomic) agent-scope loads: all in flight at once
-      const int b = min(sb0 + q * kGroups, n_blocks - 1);
-      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, si < n ? (b * 16 + si) * 4 : 0x7ffffff0, 0, kAgent));
-    }
+    for (int q = 0; q < kMaxPer; ++q)  // plain (non-atomic) agent-scope loads: all in flight at once
+      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, voff, q * kGroups * 64, kAgent));
   }
   const uint32_t arr = staged_array_bytes(K, n);
   const __amdgpu_buffer_rsrc_t r0 = make_rsrc(xs, arr), r1 = make_rsrc(xs + arr, arr);
