@@ -994,7 +994,7 @@ __device__ __forceinline__ void ring_pass(Ring<DT, UR>& R, const WaveStream& S, 
 template <int DT, int UR>
 __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                               const char* lds, int n, int lane, const EpiCtx& e,
-                                              const float* rscale, const FlushCtx& F, const MatDev* next,
+                                              const float* rscale, const FlushCtx& F, const MatDev next, bool has_next,
                                               int next_sk, int wave, int pidx, bool park_now) {
   constexpr int TB = Ring<DT, UR>::kTileBytes;
   ConsumeState C;
@@ -1047,6 +1047,7 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
     C.rb = uni(C.rb);
   }
   if (C.t > 0) (void)flush_rowblock<DT>(A, S, S_k, C.rb, C.acc0 + C.acc1, lane, e, rscale, F);  // range ends inside a row block
+#pragma unroll  // (a loop over the two entries would index them at run time and put the context into scratch memory)
   for (int b = 0; b < 2; ++b) {
     if (!F.rearm[b]) continue;
     const int pieces = F.rearm_n[b] / 4, per = (pieces + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -1061,8 +1062,9 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
   // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
   // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
   // starts its stream after the barrier instead (those loads overlap the activation staging).
-  if (next) {
-    stream_init<DT>(S, *next, next_sk, wave);
+  // (the next matrix by value: through a pointer it would sit in scratch memory, one round trip away)
+  if (has_next) {
+    stream_init<DT>(S, next, next_sk, wave);
     // (park_now is set behind gate/up only: the down projection follows)
     if (park_now) stream_park<DT>(S, park_region(A, const_cast<char*>(lds), 3, wave), park_cap(A, 3), lane);
   }
@@ -1563,7 +1565,7 @@ template <int DT, int UR>
 __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, WaveStream& S, int S_k,
                                            const char* xin, bool scaled, int K,
                                            const EpiCtx& e, char* lds, int* pflag, unsigned tag, int lane,
-                                           const MatDev* next, int next_sk, int wave, int trace_layer,
+                                           const MatDev next, bool has_next, int next_sk, int wave, int trace_layer,
                                            bool poll_x, int kind) {
   const int pidx = kind == 0 ? 0 : kind - 1;  // index of the phase's plan: QKV, O, gate/up, down, LM head
   if (poll_x) __syncthreads();  // no grid barrier came before: the workgroup's slower waves are done with LDS
@@ -1634,7 +1636,7 @@ __device__ __forceinline__ void proj_phase(const StageArgs& A, Ring<DT, UR>& R, 
   if (timed_out && lane == 0) __hip_atomic_store(&A.sync->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // (no global store may sit between the weight loads above and the streaming loop: with loads and
   // stores both pending the compiler stops counting and waits for everything at every ring slot)
-  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, next_sk, wave, pidx,
+  consume_phase<DT, UR>(A, R, S, S_k, lds, A.n, lane, e2, rscale, F, next, has_next, next_sk, wave, pidx,
                         /*park_now=*/kind == 3);  // drains its stores
   wg_mark(A, trace_layer, 2);
 }
@@ -1813,7 +1815,7 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
       A.trace[A.trace_cap - 1] = wall_clock64();
     }
     proj_phase<DT, UR>(A, R, S, sk, xin, scaled, M.K, e, lds, pflag, (unsigned)ph + 1u, lane,
-                       has_next ? &nxt : nullptr, nsk, wave, l * 8 + k,
+                       nxt, has_next, nsk, wave, l * 8 + k,
                        /*poll_x=*/k == 2 || k == 4, /*kind=*/k);
     wg_mark(A, l * 8 + k, 3);
     if (k == 5) break;
