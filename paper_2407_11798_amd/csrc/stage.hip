@@ -978,12 +978,13 @@ __device__ __forceinline__ void consume_parked(ConsumeState& C, const PassLane& 
 // One pass over the ring, in groups of kGroup slots: the group's tiles are consumed (skipped as a
 // whole when the consumer has nothing for the group), then the group's slots are refilled,
 // outside any branch.
-constexpr int kGroup = 4;
+template <int DT>
+constexpr int group_size() { return DT == kWeightBF16 ? 4 : 2; }  // (a 4-bit tile has four operand slots: sixteen live operand registers per slot)
 template <int DT, int UR, int J0>
 __device__ __forceinline__ void ring_pass(Ring<DT, UR>& R, const WaveStream& S, ConsumeState& C, const PassPlan& P,
                                           const PassLane& PLn) {
   if constexpr (J0 < UR) {
-    constexpr int J1 = J0 + kGroup < UR ? J0 + kGroup : UR;
+    constexpr int J1 = J0 + group_size<DT>() < UR ? J0 + group_size<DT>() : UR;
     if (J0 < P.nc) consume_group<DT, UR, J0, J1>(R, C, P, PLn);
     issue_slots<DT, UR, J0, J1>(R, S, P, PLn.lane16);
     ring_pass<DT, UR, J1>(R, S, C, P, PLn);
