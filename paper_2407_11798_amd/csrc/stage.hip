@@ -229,18 +229,6 @@ __device__ __forceinline__ T* uni_ptr(T* p) {
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
   return (T*)(((uint64_t)hi << 32) | lo);
 }
-// The per-layer tables live in device memory and are reached through generic pointers, which
-// the compiler must assume per-lane; their contents are the same for every lane.
-__device__ __forceinline__ MatDev uni_mat(const MatDev& m) {
-  MatDev r;
-  r.w = uni_ptr(m.w);
-  r.s = uni_ptr(m.s);
-  r.N = uni(m.N);
-  r.K = uni(m.K);
-  r.NRB = uni(m.NRB);
-  r.KT = uni(m.KT);
-  return r;
-}
 // The per-layer table does not change while a kernel runs and the layer index is the same in every
 // lane: read through the constant address space it comes by scalar loads, straight into scalar
 // registers and through the scalar cache, instead of a vector load whose ~1 us the wave would sit
@@ -266,32 +254,13 @@ __device__ __forceinline__ LayerDev tab_layer(LayerTab t, int l) {
   r.ffn_gain = t[l].ffn_gain;
   return r;
 }
-// (The block-scaled kernel, which also carries the scale plane's descriptor through its streaming loop,
-// is the one variant that measures slower with the table in scalar registers: it keeps the vector load.)
-template <int DT>
-__device__ __forceinline__ MatDev table_mat(const StageArgs& A, int l, int which);
-template <int DT>
-__device__ __forceinline__ LayerDev table_layer(const StageArgs& A, int l);
-__device__ __forceinline__ LayerDev uni_layer(const LayerDev& l) {
-  LayerDev r;
-  r.qkv = uni_mat(l.qkv);
-  r.o = uni_mat(l.o);
-  r.gateup = uni_mat(l.gateup);
-  r.down = uni_mat(l.down);
-  r.attn_gain = uni_ptr(l.attn_gain);
-  r.ffn_gain = uni_ptr(l.ffn_gain);
-  return r;
-}
-
 template <int DT>
 __device__ __forceinline__ MatDev table_mat(const StageArgs& A, int l, int which) {  // which: 0 QKV, 1 O
-  if constexpr (DT == kWeightFP4B) return uni_mat(which == 0 ? A.layers[l].qkv : A.layers[l].o);
-  else return tab_mat(which == 0 ? ((LayerTab)A.layers)[l].qkv : ((LayerTab)A.layers)[l].o);
+  return tab_mat(which == 0 ? ((LayerTab)A.layers)[l].qkv : ((LayerTab)A.layers)[l].o);
 }
 template <int DT>
 __device__ __forceinline__ LayerDev table_layer(const StageArgs& A, int l) {
-  if constexpr (DT == kWeightFP4B) return uni_layer(A.layers[l]);
-  else return tab_layer((LayerTab)A.layers, l);
+  return tab_layer((LayerTab)A.layers, l);
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
@@ -546,22 +515,17 @@ __device__ __forceinline__ void stage_x(const char* xs, int K, int n, int t0, in
     ((uint4*)lds)[z] = make_uint4(0u, 0u, 0u, 0u);
     ((uint4*)lds)[lo_off + z] = make_uint4(0u, 0u, 0u, 0u);
   }
-  constexpr int kGroups = kThreads / 16;
-  constexpr int kMaxPer = 16;  // up to 16 * 32 = 512 blocks of 16 columns (d_model <= 8192) in one batch
-  float part[kMaxPer];
-  const int si = threadIdx.x & 15, sb0 = threadIdx.x >> 4;
+  // Partial sums of squares, [block of 16 columns][16 tokens]: a lane reads four tokens of a block
+  // with one 128-bit load (lane t: tokens 4 (t & 3) .., blocks t >> 2, + 128, + 256, ...: two loads per
+  // lane at d_model 4096), all in flight at once.  Unscaled phases and blocks past the last get
+  // out-of-range offsets, which the hardware answers with zeros without going to memory.
+  constexpr int kSsqLoads = 4;  // up to 4 * 128 = 512 blocks of 16 columns (d_model <= 8192) at once
+  f32x4 part[kSsqLoads];
   {
-    // The loads stay unconditional; the ones nobody needs (an unscaled phase; the columns of tokens
-    // the run does not have) get out-of-range offsets, which the hardware answers with zeros
-    // without going to memory -- every workgroup reads these same few lines at the same moment.
     const __amdgpu_buffer_rsrc_t sr = make_rsrc(ssq ? ssq : (const float*)xs, ssq ? (uint32_t)n_blocks * 64u : 0u);
-    // One per-lane offset for all of them, the block's part in the instruction's scalar offset (blocks
-    // past the last are out of the descriptor's range): sixteen per-lane offsets would be sixteen live
-    // registers, which a kernel variant short of registers spills and then reloads one load at a time.
-    const int voff = si < n ? (sb0 * 16 + si) * 4 : 0x7ffffff0;
+    const int voff = (int)threadIdx.x * 16;  // block (tid >> 2), tokens 4 (tid & 3) ..
 #pragma unroll
-    for (int q = 0; q < kMaxPer; ++q)  // plain (non-atomic) agent-scope loads: all in flight at once
-      part[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(sr, voff, q * kGroups * 64, kAgent));
+    for (int q = 0; q < kSsqLoads; ++q) part[q] = ld_ag4(sr, voff + q * (kThreads * 16));
   }
   const uint32_t arr = staged_array_bytes(K, n);
   const __amdgpu_buffer_rsrc_t r0 = make_rsrc(xs, arr), r1 = make_rsrc(xs + arr, arr);
@@ -603,16 +567,22 @@ __device__ __forceinline__ void stage_x(const char* xs, int K, int n, int t0, in
     }
   }
   if (ssq) {
-    float ssum = 0.0f;
+    f32x4 ssum = (part[0] + part[1]) + (part[2] + part[3]);
+    for (int b = (int)(threadIdx.x >> 2) + kSsqLoads * (kThreads / 4); b < n_blocks; b += kThreads / 4)  // d_model > 8192
+      ssum += ld_ag4(make_rsrc(ssq, (uint32_t)n_blocks * 64u), (b * 16 + (int)(threadIdx.x & 3) * 4) * 4);
+    // lanes with the same tokens (equal lane & 3) first, by shuffles in a fixed order, then the eight
+    // waves through LDS: a chain of dependent LDS reads would cost most of a microsecond here
 #pragma unroll
-    for (int q = 0; q < kMaxPer; ++q) ssum += sb0 + q * kGroups < n_blocks ? part[q] : 0.0f;
-    if (si < n)
-      for (int b = sb0 + kMaxPer * kGroups; b < n_blocks; b += kGroups) ssum += ld_ag(ssq + b * 16 + si);
-    red[threadIdx.x] = ssum;  // red[b0 * 16 + i]
+    for (int sh = 4; sh < 64; sh *= 2) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) ssum[j] += __shfl_xor(ssum[j], sh);
+    }
+    if (lane < 4) *(f32x4*)(red + wave * 16 + lane * 4) = ssum;
     __syncthreads();
     if (threadIdx.x < 16) {
       float t = 0.0f;
-      for (int b = 0; b < kGroups; ++b) t += red[b * 16 + threadIdx.x];
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) t += red[w * 16 + threadIdx.x];
       rscale[threadIdx.x] = 1.0f / sqrtf(t / (float)K + eps);
     }
   }
