@@ -1029,16 +1029,14 @@ __device__ __forceinline__ void consume_phase(const StageArgs& A, Ring<DT, UR>& 
       if (piece < pieces) __builtin_amdgcn_raw_buffer_store_b128(empty, rr, piece * 16, 0, kAgent);
     }
   }
+  // The wave's place in the next phase is worked out (integer divisions) while its stores are on their
+  // way.  (The next matrix by value: through a pointer it would sit in scratch memory, one round trip
+  // away.)
+  if (has_next) stream_init<DT>(S, next, next_sk, wave);
   wave_drain();  // this wave's stores are complete (the wait also covers loads, so it comes first)
-  // The ring is free: start the next phase's weight stream before the barrier, so HBM stays busy
-  // while the grid synchronises.  Wave 0 polls the barrier and loads return in order, so it
-  // starts its stream after the barrier instead (those loads overlap the activation staging).
-  // (the next matrix by value: through a pointer it would sit in scratch memory, one round trip away)
-  if (has_next) {
-    stream_init<DT>(S, next, next_sk, wave);
-    // (park_now is set behind gate/up only: the down projection follows)
-    if (park_now) stream_park<DT>(S, park_region(A, const_cast<char*>(lds), 3, wave), park_cap(A, 3), lane);
-  }
+  // (park_now is set behind gate/up only: the down projection follows; elsewhere the next phase's first
+  // tiles are asked for behind the arrival at the grid barrier)
+  if (has_next && park_now) stream_park<DT>(S, park_region(A, const_cast<char*>(lds), 3, wave), park_cap(A, 3), lane);
 }
 
 // ---- attention phase ----------------------------------------------------------------------------
