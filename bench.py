@@ -35,9 +35,10 @@ def algorithmic_bytes(shape, layer_bytes, lm_bytes, prefix_len, n):
     return shape.n_layers * layer_bytes + lm_bytes + n * shape.d_model * es + kv
 
 
-def cpu_baseline(shape, prefix_len, n, seed):
+def cpu_baseline(shape, prefix_len, n, seed, other_ns=()):
     """The CPU oracle timed on a bounded sample: a 2-layer and a 10-layer model of the same
-    layer shape (KV prefix included), extrapolated linearly to the full depth."""
+    layer shape (KV prefix included), extrapolated linearly to the full depth; `n` is the batch size
+    the headline figure is quoted on, `other_ns` are timed on the same two models."""
     import dataclasses
     import numpy as np
     import synth
@@ -48,7 +49,8 @@ def cpu_baseline(shape, prefix_len, n, seed):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    times = {}
+    ns = [n] + [m for m in other_ns if m != n]
+    times = {m: {} for m in ns}
     lo, hi = (2, 10) if shape.n_layers >= 10 else (1, shape.n_layers)
     for nl in (lo, hi):
         sh = dataclasses.replace(shape, n_layers=nl, name="%s_l%d" % (shape.name, nl))
@@ -58,19 +60,27 @@ def cpu_baseline(shape, prefix_len, n, seed):
         for l in range(nl):
             for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "wg", "wu", "wd"):
                 om.weights(name, l)          # generation is not part of the timed region
-        okv = from_synth.kv_synthetic(sh, seed, prefix_len + 64, prefix_len)
-        run = synth.linear_run(n, prefix_len)
-        toks = synth.tokens_host(sh, seed, n, synth.T_DRAFT)
-        t0 = time.perf_counter()
-        out = oracle.stage_forward(om, okv, run, 0, nl, tokens=toks)
-        oracle.verify_greedy(toks, run["parent"], out["logits"].astype(np.float32), int(toks[0]))
-        times[nl] = time.perf_counter() - t0
-    per_layer = (times[hi] - times[lo]) / float(hi - lo) if hi > lo else times[lo] / lo
-    full = times[lo] + per_layer * (shape.n_layers - lo)
+        for m in ns:
+            okv = from_synth.kv_synthetic(sh, seed, prefix_len + 64, prefix_len)
+            run = synth.linear_run(m, prefix_len)
+            toks = synth.tokens_host(sh, seed, m, synth.T_DRAFT)
+            t0 = time.perf_counter()
+            out = oracle.stage_forward(om, okv, run, 0, nl, tokens=toks)
+            oracle.verify_greedy(toks, run["parent"], out["logits"].astype(np.float32), int(toks[0]))
+            times[m][nl] = time.perf_counter() - t0
+
+    def full_forward(m):
+        t = times[m]
+        per_layer = (t[hi] - t[lo]) / float(hi - lo) if hi > lo else t[lo] / lo
+        return t[lo] + per_layer * (shape.n_layers - lo)
+
+    full = full_forward(n)
     return {"value": n / full, "unit": "verified tokens/s", "cores": cores, "kind": "oracle",
+            "per_batch": {str(m): m / full_forward(m) for m in ns},
             "sample": "n=%d, T=%d: timed %d-layer (%.2fs) and %d-layer (%.2fs) models of the same layer shape, "
-                      "extrapolated to %d layers (%.1fs per forward)" % (n, prefix_len, lo, times[lo], hi, times[hi],
-                                                                         shape.n_layers, full)}
+                      "extrapolated to %d layers (%.1fs per forward); per_batch: the same two models at n = %s"
+                      % (n, prefix_len, lo, times[n][lo], hi, times[n][hi], shape.n_layers, full,
+                         ", ".join(str(m) for m in ns))}
 
 
 def time_forward(pi, torch, model, kv, run, n, layer_begin, layer_end, steps, warmup, shape):
@@ -701,7 +711,7 @@ def main():
                      "algorithmic_bytes_per_launch": hb["algorithmic_GB"] * 1e9},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, T, int(head), args.seed)
+        out["cpu_baseline"] = cpu_baseline(shape, T, int(head), args.seed, [int(b) for b in batches])
     print(json.dumps(out))
 
 
