@@ -430,6 +430,66 @@ int32_t pi_sched_on_speculation_stopped(pi_sched* s, int32_t logits_waiting);
 int32_t pi_sched_state(const pi_sched* s, double* cutoff, int32_t* n_accepted, int32_t* ids, int32_t cap,
                        int32_t* n_runs);
 
+/* ---- Continuous asynchronous speculation: the head node's loop ------------------------------
+ * Sections "Asynchronous Speculation", "Continuous Speculation", "Pipelined KV Cache
+ * Multibuffering" and "Early Inference Cancellation", with one GPU's stream in the role of the
+ * pipeline: verification runs are queued back to back; while the oldest has not finished, further
+ * micro-batches of draft tokens are issued, each a run with a sequence partition, a record and a
+ * cancel word of its own, each building on the entries of the one before it (early sharing); when a
+ * result arrives it is sampled (greedy), its accepted entries join every sequence, and every queued
+ * run the new tokens contradict is cancelled through its cancel word.  The loop only sequences the
+ * entry points above (pi_sched_*, pi_kvmeta_*, pi_stage_forward_multi, pi_verify_greedy_chained,
+ * pi_kvmeta_compact) on one stream; the output is the token sequence plain greedy decoding gives.
+ *
+ * The draft model is the caller's: draft(ctx, position, &token, &confidence) returns PI_OK and the
+ * draft model's token for `position` with its confidence in [0, 1] (the loop stops extending a
+ * micro-batch when the confidence is below the reactive cutoff); alternative (may be NULL) returns 1
+ * and the draft model's second choice for `position`, 0 if it has none, a negative status on error:
+ * with it a run is a small tree, its chain plus one alternative leaf hanging at least two positions
+ * above the chain's end, each branch with a partition of its own.  Both are called from inside
+ * pi_spec_generate, on the calling thread; a non-zero status ends the call with that status.
+ *   prefix_len: the cache holds canonical cells 0 .. prefix_len-1 (positions 0 .. prefix_len-1);
+ *   first_token: the accepted token at position prefix_len, whose entry is not in the cache yet;
+ *   depth: weight passes in flight (1..16); micro_batch: draft tokens per run (1..4);
+ *   runs_per_pass: consecutive runs sharing one pass over the weights (1..8); n_seq: sequence
+ *   identifiers of the cell metadata (2..PI_MAX_SEQ); base_cutoff/recovery/decay: as pi_sched_create.
+ * The cache must have room for the window: prefix_len + PI_WINDOW <= n_cells, and as generation
+ * goes on, accepted length + PI_WINDOW <= n_cells (PI_E_SHAPE otherwise); positions must stay below
+ * the model's max_pos (PI_E_ARG).  A pi_spec owns its metadata table, its run records and its
+ * buffers; the model and the cache stay the caller's and must not be used by others meanwhile. */
+typedef struct pi_spec pi_spec;
+typedef int32_t (*pi_draft_fn)(void* ctx, int32_t position, int32_t* token, double* confidence);
+typedef int32_t (*pi_alternative_fn)(void* ctx, int32_t position, int32_t* token);
+typedef struct {
+  int32_t prefix_len, first_token;
+  int32_t depth, micro_batch, runs_per_pass, n_seq;
+  double base_cutoff, recovery, decay;
+  pi_draft_fn draft;
+  pi_alternative_fn alternative; /* may be NULL */
+  void* ctx;
+} pi_spec_config;
+typedef struct {
+  int64_t passes, runs, non_speculative, speculative, discarded, cancelled, layers_skipped, tokens_speculated,
+      tokens_accepted_from_drafts, compactions, cutoff_stops, tree_runs, alternatives_accepted;
+} pi_spec_stats;
+/* Blocking (allocates its buffers; `stream` is the stream every later call of this pi_spec uses). */
+int32_t pi_spec_create(pi_model* m, pi_kv* kv, const pi_spec_config* cfg, void* stream, pi_spec** out);
+/* Run until n_tokens have been generated after first_token and copy them to tokens_out (host);
+ * a later call with a larger n_tokens continues and returns the longer sequence from its start.
+ * Blocking.  After an error the handle only accepts pi_spec_get_stats and pi_spec_free. */
+int32_t pi_spec_generate(pi_spec* s, int32_t n_tokens, int32_t* tokens_out);
+/* Wait for every pass in flight, deal with its results, and fold the window's canonical cells into
+ * the dense prefix (pi_kvmeta_compact on the loop's table and the cache): afterwards cells
+ * 0 .. *dense_len-1 hold positions 0 .. *dense_len-1, the cache's canonical length is *dense_len,
+ * and *n_accepted tokens (prompt included) are accepted, the last of which has no entry yet
+ * (*dense_len == *n_accepted - 1).  Either pointer may be NULL.  Blocking. */
+int32_t pi_spec_settle(pi_spec* s, int32_t* n_accepted, int32_t* dense_len);
+/* The loop's cell metadata as pi_kvmeta_read gives it (n_cells entries each; either may be NULL).
+ * Blocking. */
+int32_t pi_spec_read_cells(const pi_spec* s, int32_t* pos_host, uint32_t* seq_host);
+int32_t pi_spec_get_stats(const pi_spec* s, pi_spec_stats* out);
+int32_t pi_spec_free(pi_spec* s);
+
 /* Device-visible address of pinned, mapped host memory (e.g. a cancel word the head node
  * stores into from the host): host_ptr must lie in memory allocated as pinned host memory.
  * PI_E_HIP if it does not. */

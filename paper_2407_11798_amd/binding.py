@@ -38,6 +38,7 @@ EXPORTS = [
     "pi_sched_create", "pi_sched_free", "pi_sched_begin_run", "pi_sched_accept_tokens", "pi_sched_complete_run",
     "pi_sched_want_speculation", "pi_sched_on_speculated", "pi_sched_on_speculation_stopped", "pi_sched_state",
     "pi_mapped_device_pointer",
+    "pi_spec_create", "pi_spec_generate", "pi_spec_settle", "pi_spec_read_cells", "pi_spec_get_stats", "pi_spec_free",
 ]
 
 
@@ -46,6 +47,25 @@ class PiModelConfig(ctypes.Structure):
                 ("n_kv_heads", c_int32), ("head_dim", c_int32), ("ffn", c_int32), ("vocab", c_int32),
                 ("rms_eps", c_float), ("rope_base", c_float), ("dtype", c_int32), ("max_pos", c_int32),
                 ("weight_dtype", c_int32), ("weight_scale_exp2", c_int32)]
+
+
+PI_DRAFT_FN = ctypes.CFUNCTYPE(c_int32, c_void_p, c_int32, POINTER(c_int32), POINTER(c_double))
+PI_ALTERNATIVE_FN = ctypes.CFUNCTYPE(c_int32, c_void_p, c_int32, POINTER(c_int32))
+
+
+class PiSpecConfig(ctypes.Structure):
+    _fields_ = [("prefix_len", c_int32), ("first_token", c_int32), ("depth", c_int32), ("micro_batch", c_int32),
+                ("runs_per_pass", c_int32), ("n_seq", c_int32), ("base_cutoff", c_double), ("recovery", c_double),
+                ("decay", c_double), ("draft", PI_DRAFT_FN), ("alternative", PI_ALTERNATIVE_FN), ("ctx", c_void_p)]
+
+
+SPEC_STATS = ["passes", "runs", "non_speculative", "speculative", "discarded", "cancelled", "layers_skipped",
+              "tokens_speculated", "tokens_accepted_from_drafts", "compactions", "cutoff_stops", "tree_runs",
+              "alternatives_accepted"]
+
+
+class PiSpecStats(ctypes.Structure):
+    _fields_ = [(name, c_int64) for name in SPEC_STATS]
 
 
 class PiRunDesc(ctypes.Structure):
@@ -134,6 +154,12 @@ def lib():
         L.pi_sched_on_speculated.argtypes = [c_void_p]
         L.pi_sched_on_speculation_stopped.argtypes = [c_void_p, c_int32]
         L.pi_sched_state.argtypes = [c_void_p, POINTER(c_double), POINTER(c_int32), c_void_p, c_int32, POINTER(c_int32)]
+        L.pi_spec_create.argtypes = [c_void_p, c_void_p, POINTER(PiSpecConfig), c_void_p, POINTER(c_void_p)]
+        L.pi_spec_generate.argtypes = [c_void_p, c_int32, c_void_p]
+        L.pi_spec_settle.argtypes = [c_void_p, POINTER(c_int32), POINTER(c_int32)]
+        L.pi_spec_read_cells.argtypes = [c_void_p, c_void_p, c_void_p]
+        L.pi_spec_get_stats.argtypes = [c_void_p, POINTER(PiSpecStats)]
+        L.pi_spec_free.argtypes = [c_void_p]
         for name in EXPORTS:
             if name != "pi_strerror":
                 getattr(L, name).restype = c_int32

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipeinfer_hip.so")
-SOURCES = ["api.hip", "stage.hip", "misc.hip", "pack.hip", "kvmeta.hip", "sched.hip"]
+SOURCES = ["api.hip", "stage.hip", "misc.hip", "pack.hip", "kvmeta.hip", "sched.hip", "spec.hip"]
 
 
 def build(verbose: bool = False) -> str:

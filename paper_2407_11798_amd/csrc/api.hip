@@ -71,6 +71,7 @@ struct pi_kv {
 };
 
 namespace pi {
+ModelView model_view(const pi_model* m) { return ModelView{m->cfg.n_layers, m->cfg.vocab, m->cfg.max_pos}; }
 KvView kv_view(pi_kv* kv) {
   return KvView{kv->k, kv->v, kv->dtype, kv->n_layers, kv->n_kv_heads, kv->n_cells, kv->head_dim, kv->len_dev};
 }

@@ -170,6 +170,10 @@ struct KvView {
   int32_t* len_dev;  // canonical length, on the device
 };
 KvView kv_view(pi_kv* kv);
+struct ModelView {
+  int n_layers, vocab, max_pos;
+};
+ModelView model_view(const pi_model* m);
 
 // ---- launch wrappers (each defined next to its kernels) ---------------------------------
 hipError_t launch_repack(const void* src, int src_dtype, int rows, int cols, PackedMat dst,

@@ -102,3 +102,18 @@ def test_cell_metadata_calls_refuse_bad_arguments_without_touching_a_device():
     assert lib.pi_kvmeta_compact(None, None, 0, None, None) == B.PI_E_ARG
     assert lib.pi_kvmeta_read(None, None, None) == B.PI_E_ARG
     assert lib.pi_kvmeta_free(None) == B.PI_E_ARG
+
+
+def test_speculation_loop_calls_refuse_bad_arguments_without_touching_a_device():
+    lib = pi.lib()
+    B = pi.binding
+    out = ctypes.c_void_p()
+    cfg = B.PiSpecConfig(0, 1, 3, 4, 1, 32, 0.3, 0.05, 0.05, B.PI_DRAFT_FN(), B.PI_ALTERNATIVE_FN(), None)
+    assert lib.pi_spec_create(None, None, ctypes.byref(cfg), None, ctypes.byref(out)) == B.PI_E_ARG
+    assert lib.pi_spec_create(None, None, None, None, None) == B.PI_E_ARG
+    assert out.value is None
+    assert lib.pi_spec_generate(None, 1, None) == B.PI_E_ARG
+    assert lib.pi_spec_settle(None, None, None) == B.PI_E_ARG
+    assert lib.pi_spec_read_cells(None, None, None) == B.PI_E_ARG
+    assert lib.pi_spec_get_stats(None, None) == B.PI_E_ARG
+    assert lib.pi_spec_free(None) == B.PI_E_ARG

@@ -92,14 +92,12 @@ def test_output_equals_plain_greedy_decoding(tiny_truth, alpha, depth, mb, cutof
                                recovery=cutoff[1], decay=cutoff[2], runs_per_pass=rpp,
                                alternative=alternative if beta is not None else None)
     out = cs.generate(n_gen)
-    st = cs.stats
     assert out == G[:n_gen], "first difference at %d" % next(i for i in range(n_gen) if out[i] != G[i])
     # the canonical entries are exactly the accepted tokens' (all but the last, which has no entry yet)
-    while cs.fifo:
-        cs._process_head()
-    cs._compact()
-    pos, seq = cs.meta.read()
-    n_acc = len(cs.accepted)
+    n_acc, dense = cs.settle()
+    st = cs.stats
+    pos, seq = cs.read_cells()
+    assert n_acc >= T + 1 + n_gen and dense == n_acc - 1
     assert pos[:n_acc - 1].tolist() == list(range(n_acc - 1)) and not (pos[n_acc - 1:] >= 0).any()
     assert len(gkv) == n_acc - 1
     assert st["runs"] == st["speculative"] + st["non_speculative"]

@@ -16,7 +16,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2407_11798_amd", "csrc")
 OUT = os.path.join(ROOT, "_build")
-SOURCES = ["api.hip", "stage.hip", "misc.hip", "pack.hip", "kvmeta.hip", "sched.hip"]
+SOURCES = ["api.hip", "stage.hip", "misc.hip", "pack.hip", "kvmeta.hip", "sched.hip", "spec.hip"]
 SAN = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
        "-fno-sanitize-recover=undefined"]
 
