@@ -1449,9 +1449,11 @@ __device__ bool attn_merge(const StageArgs& A, int h, int u, unsigned tag, int* 
 // All units first, then all merges: a workgroup never waits while it still owes a unit, so the
 // waits in the merge step cannot deadlock even when a workgroup serves several units.
 constexpr int kMaxAttnRounds = 64;
-template <int DT>
-__device__ bool attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds, unsigned tag, int* sh,
-                                int* tickets, int layer_rel) {
+// `between` runs in every wave when the workgroup's units are done (LDS is free from then on) and before
+// its merge steps wait for the other units.
+template <int DT, typename Between>
+__device__ __forceinline__ bool attention_phase(const StageArgs& A, const char* kl, const char* vl, char* lds, unsigned tag,
+                                                int* sh, int* tickets, int layer_rel, Between&& between) {
   const int units = A.n_kv_heads * A.attn_units_per_head;
   const int rounds = (units + (int)gridDim.x - 1) / (int)gridDim.x;  // <= kMaxAttnRounds (host)
   const unsigned base = (unsigned)layer_rel * (unsigned)rounds * gridDim.x;
@@ -1468,6 +1470,7 @@ __device__ bool attention_phase(const StageArgs& A, const char* kl, const char* 
       default: attn_unit<128, DT>(A, kl, vl, h, u, lds, tag); break;
     }
   }
+  between();
   bool ok = true;
   for (int r = 0; ok && r < rounds; ++r) {
     const int w = __builtin_amdgcn_readfirstlane(tickets[r]);
@@ -1705,17 +1708,25 @@ __global__ void __launch_bounds__(kThreads, 1) stage_kernel(const StageArgs A) {
     const int k = l < A.layer_end ? ph % 5 : 5;  // 5: LM head
     if (k == 1) {
       wg_mark(A, l * 8 + 1, 0);
+      // The output projection's first tiles are asked for once the workgroup's units are done, ahead of its
+      // merge steps: those wait for the other units anyway, and the workgroup that merges last is the one
+      // the output projection waits for.  (Not where the projection is unsliced and twice as many tiles
+      // are asked for: the merge steps' own loads return behind them, which costs what the order gains.)
+      const bool ask_early = A.sk[1] > 1;
+      const auto ask_o = [&] {
+        stream_init<DT>(S, table_mat<DT>(A, l, 1), A.sk[1], wave);
+        if (park_cap(A, 1) > 0) {
+          // the tiles' region may overlap what slower waves of a workgroup without attention work still
+          // read for the QKV projection
+          __syncthreads();
+          stream_park<DT>(S, park_region(A, lds, 1, wave), park_cap(A, 1), lane);
+        }
+      };
       if (!(ok = attention_phase<DT>(A, A.kbase + (size_t)l * A.kv_layer_bytes, A.vbase + (size_t)l * A.kv_layer_bytes, lds,
-                                     bc.epoch + 1, bar_sh, attn_tickets, l - A.layer_begin)))
+                                     bc.epoch + 1, bar_sh, attn_tickets, l - A.layer_begin, [&] { if (ask_early) ask_o(); })))
         break;
       wg_mark(A, l * 8 + 1, 2);
-      stream_init<DT>(S, table_mat<DT>(A, l, 1), A.sk[1], wave);
-      if (park_cap(A, 1) > 0) {
-        // the tiles' region may overlap what slower waves of a workgroup without attention work still
-        // read for the QKV projection
-        __syncthreads();
-        stream_park<DT>(S, park_region(A, lds, 1, wave), park_cap(A, 1), lane);
-      }
+      if (!ask_early) ask_o();
       // No grid barrier here: the output projection asks for its weights at once and reads the
       // attention output until no piece of it is "empty" any more (the merging workgroups are
       // the last to finish this phase; everyone else's weight requests travel meanwhile).
