@@ -17,6 +17,7 @@ constexpr size_t kProjLdsBudget = 96 * 1024;  // bytes of LDS the QKV phase shou
 constexpr size_t kLdsLimit = 159 * 1024;      // dynamic LDS of a workgroup (160 KiB per compute unit; a little is static)
 constexpr int kParkMax = 16;                  // tiles a wave may ask for ahead of a phase (1 KiB of LDS each)
 constexpr size_t kProjLdsLimit = 150 * 1024;  // ... and may take where no split fits the budget (160 KiB; a little is static)
+constexpr size_t kSlowPollLayerBytes = 256u << 20;  // a layer's weights from which barrier waits space their looks
 constexpr unsigned long long kBarrierTimeoutTicks = 200000000ull;  // 2 s of the 100 MHz clock
 
 }  // namespace
@@ -899,6 +900,14 @@ int32_t stage_forward_groups(pi_model* m, pi_kv* kv, const pi_run_desc* run, int
   a.attn_chunk = attn_chunk;
   a.attn_units_per_head = attn_units;
   a.timeout_ticks = kBarrierTimeoutTicks;
+  {
+    // 256 workgroups looking at the arrival words back to back slow down the workgroups still streaming;
+    // where a layer streams long enough for that to show (measured: the bf16 7B shape, -0.6 % from four
+    // tokens on; 8-bit and 4-bit weights, the 70B shape and small models +-0 or worse), the looks are spaced.
+    const LayerWeights& L0 = m->layers[0];
+    const size_t layer_bytes = L0.qkv.bytes + L0.o.bytes + L0.gateup.bytes + L0.down.bytes;
+    a.slow_poll = layer_bytes >= kSlowPollLayerBytes && run->n >= 4 ? 1 : 0;
+  }
   a.epoch_base = m->epoch;
   m->epoch += (unsigned)(5 * (layer_end - layer_begin) + 4);  // every barrier this launch can reach
   a.trace = m->trace_on ? m->trace : nullptr;  // a clock read per barrier is not free: only on request

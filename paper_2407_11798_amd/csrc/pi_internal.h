@@ -149,6 +149,7 @@ struct StageArgs {
   unsigned long long pf_cap8, pf_base8;
   int attn_chunk, attn_units_per_head;
   unsigned long long timeout_ticks;  // 100 MHz ticks a barrier wait may last
+  int slow_poll;                     // a barrier's looks at the arrival words are spaced ~0.7 us apart (else back to back)
   unsigned epoch_base;               // barriers used by earlier launches on this model
   unsigned long long* trace;  // optional: 100 MHz timestamps, one per barrier passed by workgroup 0
   int trace_cap;

@@ -173,7 +173,10 @@ __device__ __forceinline__ bool grid_barrier(const StageArgs& A, BarrierCtx& bc,
         for (int q = 0; q < 4; ++q) all = all && (idx + q >= G || (short)((f[q] - want) >> 16) >= 0);
       }
       if (__builtin_amdgcn_ballot_w64(!all) == 0) break;
-      __builtin_amdgcn_s_sleep(1);
+      if (A.slow_poll)
+        __builtin_amdgcn_s_sleep(24);
+      else
+        __builtin_amdgcn_s_sleep(1);
       if (deadline_passed(dl, spin, A.timeout_ticks)) {
         ok = 0;
         break;
