@@ -22,9 +22,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per stage_kernel launch measured with rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated
 # against a device copy (profiles/stage_kernel_*.md give the commands).  Keyed by (shape, prefix, n).
 # These are typed in from those runs, not read at run time: re-take them when the kernel changes.
-MEASURED_TRAFFIC_BYTES = {("llama7b", 512, 8): 14.203e9, ("llama7b_w8", 512, 8): 7.394e9,
-                          ("llama7b_w4", 512, 8): 4.071e9, ("llama7b_w4b", 512, 8): 4.277e9,
-                          ("llama70b", 2048, 8): 141.914e9}
+MEASURED_TRAFFIC_BYTES = {("llama7b", 512, 8): 14.200e9, ("llama7b_w8", 512, 8): 7.397e9,
+                          ("llama7b_w4", 512, 8): 4.068e9, ("llama7b_w4b", 512, 8): 4.276e9,
+                          ("llama70b", 2048, 8): 141.915e9}
 
 
 def algorithmic_bytes(shape, layer_bytes, lm_bytes, prefix_len, n):
